@@ -1,0 +1,197 @@
+/*
+ * dash.h -- C ABI of the MI355X (gfx950) library for the hot path of block-diagonal
+ * Shampoo as organised by DASH (arXiv 2602.02016): every Kronecker factor is a B x B
+ * block of one stacked N x B x B tensor (paper Section 4.1), and the optimizer step is
+ *   accumulate (Algorithm 1, EMA lines) -> inverse p-th roots of the damped factors by
+ *   Newton-DB (Section 3.3) or Chebyshev/Clenshaw (Appendix A) after Frobenius scaling
+ *   (Section 3.4) -> preconditioned update (Algorithm 1, last line) -> optional
+ *   block-wise Adam grafting (Section 2.3).
+ *
+ * Conventions for every call below
+ *   - "dev" pointers are DEVICE pointers to contiguous row-major fp32 stacks [N][B][B]
+ *     (strides B*B, B, 1) on the context's device.  They are owned by the caller; the
+ *     library never allocates or frees device memory and keeps no reference after the
+ *     work it enqueued has run.  "host" pointers are ordinary host memory.
+ *   - B must be a positive multiple of 64; N >= 0 (N == 0 is a no-op returning DASH_OK).
+ *   - Work is enqueued on the context's HIP stream and is asynchronous with respect to
+ *     the host; the caller synchronises the stream before reading results.
+ *   - Inputs declared const are never written.  Outputs must not overlap inputs unless
+ *     a call says so.
+ *   - Errors in arguments or launches are reported through the return code (and the
+ *     text of dash_last_error); nothing is thrown and nothing aborts.  Numerical
+ *     failure (a non-finite root, e.g. a block that is not positive definite) is
+ *     reported through the optional per-block flag array, never by a return code.
+ *   - Two calls on the same context must not overlap in time (they share the workspace).
+ */
+#ifndef DASH_H
+#define DASH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dash_ctx dash_ctx;
+
+typedef enum {
+    DASH_OK = 0,
+    DASH_ERR_INVALID_ARG = 1, /* null pointer, bad size, bad enum, aliasing that is not allowed */
+    DASH_ERR_UNSUPPORTED = 2, /* valid request this build does not implement */
+    DASH_ERR_WORKSPACE = 3,   /* workspace missing or too small for even one block */
+    DASH_ERR_HIP = 4          /* a HIP runtime call failed (no device, launch error, ...) */
+} dash_status;
+
+typedef enum { DASH_NEWTON_DB = 0, DASH_CHEBYSHEV = 1 } dash_method;
+typedef enum { DASH_SCALE_FROBENIUS = 0, DASH_SCALE_TRACE = 1, DASH_SCALE_NONE = 2 } dash_scaling;
+/* DASH_FP32: fp32 MFMA operands.  DASH_BF16_ACC32: iterates stored in fp32, every matmul
+ * operand rounded to bf16 (round to nearest even), fp32 accumulation -- the recipe of
+ * Appendix A.3 with bf16 in place of fp16, applied to both methods. */
+typedef enum { DASH_FP32 = 0, DASH_BF16_ACC32 = 1 } dash_precision;
+
+/* ---- context ------------------------------------------------------------------- */
+
+/* Creates a context bound to HIP device `device` and to `hip_stream` (a hipStream_t
+ * passed as void*; NULL = the device's default stream).  The stream stays owned by the
+ * caller and must outlive the context.  Fails with DASH_ERR_HIP when no such device. */
+dash_status dash_create(dash_ctx** out, int device, void* hip_stream);
+dash_status dash_destroy(dash_ctx* ctx);
+
+/* Device scratch the iterative calls need.  dash_workspace_bytes(n, ...) is the size
+ * that lets n blocks be processed in one chunk; with a smaller workspace the library
+ * walks the stack in chunks of as many blocks as fit (at least one must fit, otherwise
+ * DASH_ERR_WORKSPACE).  The workspace is caller-owned device memory, 256-byte aligned,
+ * and may be replaced between calls. */
+size_t dash_workspace_bytes(int64_t n_blocks, int B, dash_method method, int p,
+                            dash_precision precision);
+dash_status dash_set_workspace(dash_ctx* ctx, void* dev_ptr, size_t bytes);
+
+/* Text of the last error on this context (valid until the next failing call). */
+const char* dash_last_error(const dash_ctx* ctx);
+const char* dash_status_string(dash_status s);
+
+/* Launch statistics since the last reset: number of batched B x B x B matmul launches
+ * (one launch computing two products counts two) and, if timing was switched on with
+ * dash_set_timing(ctx, 1), the summed device time of those launches measured with HIP
+ * events on the context's stream (dash_get_stats synchronises the stream then).  Used
+ * to check the paper's matmul counts (Section 3.3: 3 per Newton-DB iteration, first
+ * iteration 1; Appendix A.2: degree d costs d-1) and for the roofline figure. */
+typedef struct {
+    int64_t matmul_products;   /* B x B x B products per block, summed over launches   */
+    int64_t matmul_launches;   /* kernel launches of the batched matmul kernel          */
+    double  matmul_block_products; /* sum over launches of products * blocks in launch  */
+    double  matmul_ms;         /* summed event time of those launches (0 if timing off) */
+} dash_stats;
+dash_status dash_reset_stats(dash_ctx* ctx);
+dash_status dash_set_timing(dash_ctx* ctx, int on);
+dash_status dash_get_stats(dash_ctx* ctx, dash_stats* out /* host */);
+
+/* ---- the batched matmul primitive (the paper's `bmm`, Sections 3.1 and 4.1) ------ */
+
+/* C_i <- alpha * op(A_i) * op(B_i) + beta * D_i + gamma * I   for i in [0, N).
+ * op(X) = X or X^T per trans flag (0/1).  A, Bm, D, C: dev [N][B][B].  D may be NULL
+ * when beta == 0 and may be the same pointer as C (in-place accumulate); C must not
+ * overlap A or Bm. */
+dash_status dash_gemm_batched(dash_ctx* ctx, int transA, int transB,
+                              const float* A, const float* Bm, const float* D, float* C,
+                              int64_t N, int B, float alpha, float beta, float gamma,
+                              dash_precision precision);
+
+/* ---- Algorithm 1, EMA lines ------------------------------------------------------ */
+
+/* L_i <- beta * L_i + alpha * G_i G_i^T,  R_i <- beta * R_i + alpha * G_i^T G_i.
+ * The paper uses alpha = 1 - beta.  G: dev const [N][B][B]; L, R: dev in/out [N][B][B]
+ * (they may be the two halves of one [2N][B][B] stack, Section 4.1 "stack"). */
+dash_status dash_accumulate_factors(dash_ctx* ctx, const float* G, float* L, float* R,
+                                    int64_t N, int B, float beta, float alpha);
+
+/* ---- Section 3.4 scaling --------------------------------------------------------- */
+
+/* s_i = ||A_i + eps I||_F (Frobenius), tr(A_i + eps I) (trace) or 1 (none).
+ * A: dev const [N][B][B]; s_out: dev [N]. */
+dash_status dash_block_norms(dash_ctx* ctx, const float* A, int64_t N, int B, float eps,
+                             dash_scaling scaling, float* s_out);
+
+/* ---- inverse roots (Section 3.3 Newton-DB; Appendix A Chebyshev) ----------------- */
+
+/* X_i <- approximately (A_i + eps I)^(-1/p), p in {2, 4}.
+ *   Steps: A_d = A + eps I; s = norm(A_d) per `scaling`; A_s = A_d / s;
+ *          X = s^(-1/p) * root(A_s).
+ *   DASH_NEWTON_DB: `iters` >= 1 updates of (Y, Z) per call, the first in closed form
+ *          (E_1 = 3/2 I - 1/2 A_s, Y_1 = A_s E_1, Z_1 = E_1); p = 4 chains two calls
+ *          (first keeps Y, second keeps Z) with `iters` updates each and no rescaling
+ *          in between.  cheb_* arguments are ignored.
+ *   DASH_CHEBYSHEV: `iters` is the degree d >= 2; cheb_coeffs is a HOST array of d+1
+ *          doubles (c_0..c_d, e.g. from dash_chebyshev_fit); the scaled block is mapped
+ *          with S = (2 A_s - (a+b) I) / (b-a) for [a,b] = [cheb_a, cheb_b], then the
+ *          reduced Clenshaw recurrence (d-1 matmuls) is evaluated.
+ *   A: dev const [N][B][B]; X: dev out [N][B][B], must not overlap A.
+ *   scale_out: dev [N] receiving s_i, or NULL.  nonfinite_out: dev int32 [N], set to 1
+ *   for every block whose result holds a NaN/Inf and to 0 otherwise, or NULL.
+ *   Needs a workspace (dash_set_workspace). */
+dash_status dash_inverse_root(dash_ctx* ctx, const float* A, float* X, int64_t N, int B,
+                              dash_method method, int p, int iters, float eps,
+                              dash_scaling scaling, dash_precision precision,
+                              const double* cheb_coeffs, double cheb_a, double cheb_b,
+                              float* scale_out, int32_t* nonfinite_out);
+
+/* Host-only: coefficients c_0..c_d of the Chebyshev series of x^(-1/p) on [a, b], fitted
+ * at n_points Chebyshev nodes as in Appendix A.1 (cosine sums, c_0 halved), in double.
+ * coeffs_out: host array of degree+1 doubles.  Needs no context and no GPU. */
+dash_status dash_chebyshev_fit(int p, int degree, double a, double b, int n_points,
+                               double* coeffs_out);
+
+/* ---- Algorithm 1, update direction ------------------------------------------------ */
+
+/* U_i <- Linv_i * G_i * Rinv_i.  All dev [N][B][B]; U must not overlap the inputs.
+ * Needs workspace for one [N][B][B] temporary (or chunks of it). */
+dash_status dash_precondition(dash_ctx* ctx, const float* Linv, const float* G,
+                              const float* Rinv, float* U, int64_t N, int B);
+
+/* ---- Section 2.3 block-wise Adam grafting ------------------------------------------ */
+
+/* Acc <- beta_g Acc + (1-beta_g) G.G ; P = G / (eps_g + sqrt(Acc)) ;
+ * s_i = ||P_i||_F / ||U_i||_F ; theta_i <- theta_i - lr * s_i * U_i.
+ * G, U: dev const [N][B][B]; Acc, theta: dev in/out [N][B][B]; s_out: dev [N] or NULL.
+ * theta may be NULL (then only Acc and s_out are produced). */
+dash_status dash_graft_update(dash_ctx* ctx, const float* G, const float* U, float* Acc,
+                              float* theta, int64_t N, int B, float beta_g, float eps_g,
+                              float lr, float* s_out);
+
+/* ---- one optimizer step (Algorithm 1 on a stack) ----------------------------------- */
+
+typedef struct {
+    const float* G;      /* dev const [N][B][B] gradient blocks                         */
+    float* S;            /* dev in/out [2N][B][B]: L blocks then R blocks               */
+    float* X;            /* dev [2N][B][B]: roots of the damped factors; written when
+                            refresh != 0, read (cached roots, Section 4.1) otherwise    */
+    float* U;            /* dev out [N][B][B] preconditioned update                     */
+    int64_t N;           /* gradient blocks                                             */
+    int32_t B;
+    float beta, alpha;   /* EMA weights (paper: alpha = 1 - beta)                       */
+    float eps;           /* damping                                                     */
+    int32_t method;      /* dash_method                                                 */
+    int32_t p;           /* 2 or 4                                                      */
+    int32_t iters;       /* Newton-DB updates per call, or Chebyshev degree             */
+    int32_t scaling;     /* dash_scaling                                                */
+    int32_t precision;   /* dash_precision                                              */
+    int32_t refresh;     /* 0: skip the inverse roots and use X as given                */
+    const double* cheb_coeffs; /* host, degree+1 doubles (Chebyshev only)               */
+    double cheb_a, cheb_b;
+    int32_t* nonfinite_out;    /* dev int32 [2N] or NULL                                */
+    /* grafting (all optional: graft != 0 switches it on) */
+    int32_t graft;
+    float* graft_acc;    /* dev in/out [N][B][B]                                        */
+    float* theta;        /* dev in/out [N][B][B] or NULL                                */
+    float beta_g, eps_g, lr;
+} dash_step_args;
+
+/* accumulate into S -> (if refresh) inverse roots of all 2N blocks of S into X ->
+ * U = X_L G X_R -> (if graft) grafted update.  args: host pointer. */
+dash_status dash_step(dash_ctx* ctx, const dash_step_args* args);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DASH_H */

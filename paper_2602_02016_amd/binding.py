@@ -1,0 +1,296 @@
+"""ctypes binding of libdash.so (include/dash.h).
+
+Argument marshalling only: tensors are checked (CUDA/HIP device, float32, contiguous,
+shape [N,B,B]) and their device pointers handed to the C ABI.  torch is used for device
+memory and for the stream; every arithmetic step runs in the library's HIP kernels.
+There is no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdash.so")
+
+# enums of dash.h
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
+NEWTON_DB, CHEBYSHEV = 0, 1
+SCALE_FROBENIUS, SCALE_TRACE, SCALE_NONE = 0, 1, 2
+FP32, BF16_ACC32 = 0, 1
+
+_METHODS = {"newton_db": NEWTON_DB, "ndb": NEWTON_DB, "chebyshev": CHEBYSHEV, "cheb": CHEBYSHEV}
+_SCALINGS = {"frobenius": SCALE_FROBENIUS, "trace": SCALE_TRACE, "none": SCALE_NONE}
+_PRECISIONS = {"fp32": FP32, "bf16": BF16_ACC32}
+
+
+class DashError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"dash status {status}: {message}")
+        self.status = status
+
+
+class _Stats(C.Structure):
+    _fields_ = [("matmul_products", C.c_int64), ("matmul_launches", C.c_int64),
+                ("matmul_block_products", C.c_double), ("matmul_ms", C.c_double)]
+
+
+class _StepArgs(C.Structure):
+    _fields_ = [
+        ("G", C.c_void_p), ("S", C.c_void_p), ("X", C.c_void_p), ("U", C.c_void_p),
+        ("N", C.c_int64), ("B", C.c_int32),
+        ("beta", C.c_float), ("alpha", C.c_float), ("eps", C.c_float),
+        ("method", C.c_int32), ("p", C.c_int32), ("iters", C.c_int32),
+        ("scaling", C.c_int32), ("precision", C.c_int32), ("refresh", C.c_int32),
+        ("cheb_coeffs", C.POINTER(C.c_double)), ("cheb_a", C.c_double), ("cheb_b", C.c_double),
+        ("nonfinite_out", C.c_void_p),
+        ("graft", C.c_int32), ("graft_acc", C.c_void_p), ("theta", C.c_void_p),
+        ("beta_g", C.c_float), ("eps_g", C.c_float), ("lr", C.c_float),
+    ]
+
+
+_lib = None
+
+
+def load_library(path: str = LIB_PATH):
+    """Loads libdash.so and declares the prototypes.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(path):
+        raise DashError(ERR_HIP, f"{path} not found: build it first (python -m paper_2602_02016_amd.build)")
+    lib = C.CDLL(path)
+    vp, i32, i64, f32, f64 = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_double
+    lib.dash_create.argtypes = [C.POINTER(vp), i32, vp]
+    lib.dash_destroy.argtypes = [vp]
+    lib.dash_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
+    lib.dash_workspace_bytes.restype = C.c_size_t
+    lib.dash_set_workspace.argtypes = [vp, vp, C.c_size_t]
+    lib.dash_last_error.argtypes = [vp]
+    lib.dash_last_error.restype = C.c_char_p
+    lib.dash_status_string.argtypes = [i32]
+    lib.dash_status_string.restype = C.c_char_p
+    lib.dash_reset_stats.argtypes = [vp]
+    lib.dash_set_timing.argtypes = [vp, i32]
+    lib.dash_get_stats.argtypes = [vp, C.POINTER(_Stats)]
+    lib.dash_gemm_batched.argtypes = [vp, i32, i32, vp, vp, vp, vp, i64, i32, f32, f32, f32, i32]
+    lib.dash_accumulate_factors.argtypes = [vp, vp, vp, vp, i64, i32, f32, f32]
+    lib.dash_block_norms.argtypes = [vp, vp, i64, i32, f32, i32, vp]
+    lib.dash_inverse_root.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, f32, i32, i32,
+                                      C.POINTER(f64), f64, f64, vp, vp]
+    lib.dash_chebyshev_fit.argtypes = [i32, i32, f64, f64, i32, C.POINTER(f64)]
+    lib.dash_precondition.argtypes = [vp, vp, vp, vp, vp, i64, i32]
+    lib.dash_graft_update.argtypes = [vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, vp]
+    lib.dash_step.argtypes = [vp, C.POINTER(_StepArgs)]
+    for name in ("dash_create", "dash_destroy", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
+                 "dash_get_stats", "dash_gemm_batched", "dash_accumulate_factors", "dash_block_norms",
+                 "dash_inverse_root", "dash_chebyshev_fit", "dash_precondition", "dash_graft_update", "dash_step"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def chebyshev_fit(p: int, degree: int, a: float, b: float, n_points: int = 10000):
+    """Host-side coefficient fit of the library (double precision); returns a list."""
+    lib = load_library()
+    out = (C.c_double * (degree + 1))()
+    st = lib.dash_chebyshev_fit(p, degree, a, b, n_points, out)
+    if st != OK:
+        raise DashError(st, lib.dash_status_string(st).decode())
+    return list(out)
+
+
+def _enum(table, v):
+    return table[v] if isinstance(v, str) else int(v)
+
+
+class Dash:
+    """One library context bound to a device and to torch's current stream on it."""
+
+    def __init__(self, device: int = 0, stream=None):
+        import torch
+        self._torch = torch
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise DashError(ERR_HIP, "no GPU visible; the HIP path has no CPU fallback")
+        self.device = torch.device("cuda", device)
+        torch.cuda.set_device(self.device)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)
+        self.stream = stream
+        h = C.c_void_p()
+        st = self.lib.dash_create(C.byref(h), device, C.c_void_p(stream.cuda_stream))
+        if st != OK:
+            raise DashError(st, "dash_create failed: " + self.lib.dash_status_string(st).decode())
+        self.h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.dash_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- helpers -----------------------------------------------------------------------
+    def _check(self, st: int):
+        if st != OK:
+            raise DashError(st, self.lib.dash_last_error(self.h).decode() or self.lib.dash_status_string(st).decode())
+
+    def _stack(self, t, name: str, n: Optional[int] = None, b: Optional[int] = None):
+        torch = self._torch
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+                and t.dim() == 3 and t.shape[1] == t.shape[2]):
+            raise DashError(ERR_INVALID_ARG, f"{name}: need a contiguous float32 device tensor of shape [N,B,B]")
+        if n is not None and (t.shape[0] != n or t.shape[1] != b):
+            raise DashError(ERR_INVALID_ARG, f"{name}: shape {tuple(t.shape)} does not match [{n},{b},{b}]")
+        return C.c_void_p(t.data_ptr())
+
+    def _vec(self, t, name: str, n: int, dtype):
+        torch = self._torch
+        if t is None:
+            return C.c_void_p(None)
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous() and t.numel() == n):
+            raise DashError(ERR_INVALID_ARG, f"{name}: need a contiguous {dtype} device tensor of {n} elements")
+        return C.c_void_p(t.data_ptr())
+
+    def workspace_bytes(self, n_blocks: int, B: int, method="newton_db", p: int = 4, precision="fp32") -> int:
+        return int(self.lib.dash_workspace_bytes(n_blocks, B, _enum(_METHODS, method), p, _enum(_PRECISIONS, precision)))
+
+    def set_workspace_bytes(self, nbytes: int):
+        """Gives the context a torch-allocated scratch tensor of at least nbytes."""
+        torch = self._torch
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = None
+            self._ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=self.device)
+        self._check(self.lib.dash_set_workspace(self.h, C.c_void_p(self._ws.data_ptr()), self._ws.numel()))
+
+    def ensure_workspace(self, n_blocks: int, B: int, method="newton_db", p: int = 4, precision="fp32",
+                         max_bytes: Optional[int] = None):
+        """Sizes the workspace for n_blocks in one chunk (capped by max_bytes: the library then chunks)."""
+        need = self.workspace_bytes(n_blocks, B, method, p, precision)
+        if max_bytes is not None:
+            need = min(need, int(max_bytes))
+        if self._ws is None or self._ws.numel() < need:
+            self.set_workspace_bytes(need)
+
+    # ---- statistics --------------------------------------------------------------------
+    def reset_stats(self):
+        self._check(self.lib.dash_reset_stats(self.h))
+
+    def set_timing(self, on: bool):
+        self._check(self.lib.dash_set_timing(self.h, 1 if on else 0))
+
+    def get_stats(self) -> dict:
+        s = _Stats()
+        self._check(self.lib.dash_get_stats(self.h, C.byref(s)))
+        return dict(matmul_products=s.matmul_products, matmul_launches=s.matmul_launches,
+                    matmul_block_products=s.matmul_block_products, matmul_ms=s.matmul_ms)
+
+    # ---- the calls of dash.h -------------------------------------------------------------
+    def gemm_batched(self, A, Bm, C_out, D=None, transA=False, transB=False, alpha=1.0, beta=0.0, gamma=0.0,
+                     precision="fp32"):
+        n, b = A.shape[0], A.shape[1]
+        self._check(self.lib.dash_gemm_batched(
+            self.h, int(transA), int(transB), self._stack(A, "A"), self._stack(Bm, "B", n, b),
+            self._stack(D, "D", n, b) if D is not None else C.c_void_p(None), self._stack(C_out, "C", n, b),
+            n, b, alpha, beta, gamma, _enum(_PRECISIONS, precision)))
+        return C_out
+
+    def accumulate_factors(self, G, L, R, beta: float, alpha: Optional[float] = None):
+        if alpha is None:
+            alpha = 1.0 - beta
+        n, b = G.shape[0], G.shape[1]
+        self._check(self.lib.dash_accumulate_factors(self.h, self._stack(G, "G"), self._stack(L, "L", n, b),
+                                                     self._stack(R, "R", n, b), n, b, beta, alpha))
+
+    def block_norms(self, A, eps: float = 0.0, scaling="frobenius", out=None):
+        torch = self._torch
+        n, b = A.shape[0], A.shape[1]
+        if out is None:
+            out = torch.empty(n, dtype=torch.float32, device=self.device)
+        self.ensure_workspace(1, b)
+        self._check(self.lib.dash_block_norms(self.h, self._stack(A, "A"), n, b, eps, _enum(_SCALINGS, scaling),
+                                              self._vec(out, "s_out", n, torch.float32)))
+        return out
+
+    def inverse_root(self, A, X=None, method="newton_db", p: int = 4, iters: int = 10, eps: float = 0.0,
+                     scaling="frobenius", precision="fp32", cheb_coeffs: Optional[Sequence[float]] = None,
+                     cheb_a: float = 0.0, cheb_b: float = 1.0, scale_out=None, nonfinite_out=None,
+                     workspace_max_bytes: Optional[int] = None):
+        torch = self._torch
+        n, b = A.shape[0], A.shape[1]
+        if X is None:
+            X = torch.empty_like(A)
+        coeffs = None
+        if cheb_coeffs is not None:
+            coeffs = (C.c_double * len(cheb_coeffs))(*[float(v) for v in cheb_coeffs])
+            if _enum(_METHODS, method) == CHEBYSHEV and len(cheb_coeffs) != iters + 1:
+                raise DashError(ERR_INVALID_ARG, "Chebyshev: need degree+1 coefficients")
+        if n > 0:
+            self.ensure_workspace(n, b, method, p, precision, workspace_max_bytes)
+        self._check(self.lib.dash_inverse_root(
+            self.h, self._stack(A, "A"), self._stack(X, "X", n, b), n, b, _enum(_METHODS, method), p, iters, eps,
+            _enum(_SCALINGS, scaling), _enum(_PRECISIONS, precision), coeffs, cheb_a, cheb_b,
+            self._vec(scale_out, "scale_out", n, torch.float32), self._vec(nonfinite_out, "nonfinite_out", n, torch.int32)))
+        return X
+
+    def precondition(self, Linv, G, Rinv, U=None):
+        torch = self._torch
+        n, b = G.shape[0], G.shape[1]
+        if U is None:
+            U = torch.empty_like(G)
+        if n > 0 and (self._ws is None or self._ws.numel() < n * b * b * 4):
+            self.set_workspace_bytes(n * b * b * 4)
+        self._check(self.lib.dash_precondition(self.h, self._stack(Linv, "Linv", n, b), self._stack(G, "G"),
+                                               self._stack(Rinv, "Rinv", n, b), self._stack(U, "U", n, b), n, b))
+        return U
+
+    def graft_update(self, G, U, Acc, theta=None, beta_g: float = 0.999, eps_g: float = 1e-8, lr: float = 0.0,
+                     s_out=None):
+        torch = self._torch
+        n, b = G.shape[0], G.shape[1]
+        if n > 0 and (self._ws is None or self._ws.numel() < 512 * n):
+            self.set_workspace_bytes(512 * n)
+        self._check(self.lib.dash_graft_update(
+            self.h, self._stack(G, "G"), self._stack(U, "U", n, b), self._stack(Acc, "Acc", n, b),
+            self._stack(theta, "theta", n, b) if theta is not None else C.c_void_p(None), n, b, beta_g, eps_g, lr,
+            self._vec(s_out, "s_out", n, torch.float32)))
+
+    def step(self, G, S, X, U, beta: float, eps: float, alpha: Optional[float] = None, method="newton_db", p: int = 4,
+             iters: int = 10, scaling="frobenius", precision="fp32", refresh: bool = True,
+             cheb_coeffs: Optional[Sequence[float]] = None, cheb_a: float = 0.0, cheb_b: float = 1.0,
+             nonfinite_out=None, graft_acc=None, theta=None, beta_g: float = 0.999, eps_g: float = 1e-8,
+             lr: float = 0.0, workspace_max_bytes: Optional[int] = None):
+        torch = self._torch
+        n, b = G.shape[0], G.shape[1]
+        if alpha is None:
+            alpha = 1.0 - beta
+        a = _StepArgs()
+        a.G = self._stack(G, "G").value
+        a.S = self._stack(S, "S", 2 * n, b).value
+        a.X = self._stack(X, "X", 2 * n, b).value
+        a.U = self._stack(U, "U", n, b).value
+        a.N, a.B = n, b
+        a.beta, a.alpha, a.eps = beta, alpha, eps
+        a.method, a.p, a.iters = _enum(_METHODS, method), p, iters
+        a.scaling, a.precision, a.refresh = _enum(_SCALINGS, scaling), _enum(_PRECISIONS, precision), int(refresh)
+        keep = None
+        if cheb_coeffs is not None:
+            keep = (C.c_double * len(cheb_coeffs))(*[float(v) for v in cheb_coeffs])
+            a.cheb_coeffs = C.cast(keep, C.POINTER(C.c_double))
+        a.cheb_a, a.cheb_b = cheb_a, cheb_b
+        a.nonfinite_out = self._vec(nonfinite_out, "nonfinite_out", 2 * n, torch.int32).value
+        a.graft = int(graft_acc is not None)
+        a.graft_acc = self._stack(graft_acc, "graft_acc", n, b).value if graft_acc is not None else None
+        a.theta = self._stack(theta, "theta", n, b).value if theta is not None else None
+        a.beta_g, a.eps_g, a.lr = beta_g, eps_g, lr
+        if n > 0:
+            self.ensure_workspace(2 * n, b, method, p, precision, workspace_max_bytes)
+        self._check(self.lib.dash_step(self.h, C.byref(a)))
+        return U

@@ -1,0 +1,546 @@
+// Host side of the C ABI declared in include/dash.h: argument checks, workspace
+// carving, chunking of long stacks, and the launch sequences of the paper's methods.
+// Every arithmetic step runs in the kernels of gemm.hip / elementwise.hip.
+#include "../../include/dash.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace dash;
+
+struct dash_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    char* ws = nullptr;
+    size_t ws_bytes = 0;
+    char err[512] = {0};
+    // statistics
+    int64_t mm_products = 0, mm_launches = 0;
+    double mm_block_products = 0.0;
+    bool timing = false;
+    std::vector<hipEvent_t> ev_pool;   // start/stop pairs
+    size_t ev_used = 0;
+    double ms_done = 0.0;
+};
+
+namespace {
+
+constexpr size_t SCALARS_PER_BLOCK = 512;   // bytes of per-block scalars (slab partials, s, 1/s, s^(-1/p))
+constexpr size_t WS_ALIGN = 256;
+
+dash_status fail(dash_ctx* c, dash_status s, const char* fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return s;
+}
+
+#define HIP_TRY(ctx, expr)                                                                   \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fail(ctx, DASH_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));   \
+    } while (0)
+
+#define DASH_TRY(expr)                     \
+    do {                                   \
+        dash_status s_ = (expr);           \
+        if (s_ != DASH_OK) return s_;      \
+    } while (0)
+
+bool valid_B(int B) { return B > 0 && B % 64 == 0 && B <= 16384; }
+
+bool overlap(const void* a, const void* b, size_t bytes) {
+    const char* x = (const char*)a;
+    const char* y = (const char*)b;
+    return x < y + bytes && y < x + bytes;
+}
+
+int buffers_needed(dash_method m) { return m == DASH_NEWTON_DB ? 5 : 3; }
+
+size_t per_block_bytes(int B, dash_method m, dash_precision prec) {
+    size_t mat = (size_t)B * B * sizeof(float);
+    size_t n = (size_t)buffers_needed(m) * mat + SCALARS_PER_BLOCK;
+    if (prec == DASH_BF16_ACC32) n += (size_t)buffers_needed(m) * mat / 2;   // bf16 operand copies
+    return n;
+}
+
+// ---- matmul launch with statistics / optional event timing ------------------------------
+dash_status run_gemm(dash_ctx* c, const GemmLaunch& g) {
+    if (g.nblocks <= 0) return DASH_OK;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->timing) {
+        if (c->ev_used + 2 > c->ev_pool.size()) {
+            for (int i = 0; i < 2; ++i) {
+                hipEvent_t e;
+                HIP_TRY(c, hipEventCreate(&e));
+                c->ev_pool.push_back(e);
+            }
+        }
+        e0 = c->ev_pool[c->ev_used];
+        e1 = c->ev_pool[c->ev_used + 1];
+        c->ev_used += 2;
+        HIP_TRY(c, hipEventRecord(e0, c->stream));
+    }
+    HIP_TRY(c, launch_gemm(g, c->stream));
+    if (c->timing) HIP_TRY(c, hipEventRecord(e1, c->stream));
+    c->mm_products += g.nprob;
+    c->mm_launches += 1;
+    c->mm_block_products += (double)g.nprob * (double)g.nblocks;
+    return DASH_OK;
+}
+
+dash_status collect_events(dash_ctx* c) {
+    if (c->ev_used == 0) return DASH_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, c->ev_pool[i], c->ev_pool[i + 1]));
+        c->ms_done += ms;
+    }
+    c->ev_used = 0;
+    return DASH_OK;
+}
+
+GemmProblem problem(const float* A, const float* B, const float* D, float* C, const float* mult, float alpha,
+                    float beta, float gamma, int ta = 0, int tb = 0) {
+    GemmProblem p;
+    p.A = A; p.B = B; p.D = D; p.C = C; p.mult = mult;
+    p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
+    return p;
+}
+
+dash_status gemm1(dash_ctx* c, const GemmProblem& p, int64_t n, int B, int32_t* nonfinite = nullptr) {
+    GemmLaunch g;
+    memset(&g, 0, sizeof(g));
+    g.prob[0] = p; g.prob[1] = p; g.nprob = 1; g.B = B; g.nblocks = n; g.nonfinite = nonfinite; g.bf16 = 0;
+    return run_gemm(c, g);
+}
+
+dash_status gemm2(dash_ctx* c, const GemmProblem& p0, const GemmProblem& p1, int64_t n, int B) {
+    GemmLaunch g;
+    memset(&g, 0, sizeof(g));
+    g.prob[0] = p0; g.prob[1] = p1; g.nprob = 2; g.B = B; g.nblocks = n; g.nonfinite = nullptr; g.bf16 = 0;
+    return run_gemm(c, g);
+}
+
+// ---- workspace carving -----------------------------------------------------------------
+struct Carve {
+    char* p;
+    char* end;
+    void* take(size_t bytes) {
+        size_t a = (bytes + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN;
+        if (p + a > end) return nullptr;
+        void* r = p;
+        p += a;
+        return r;
+    }
+};
+
+// ---- Newton-DB on one chunk (paper Section 3.3) -----------------------------------------
+// One call: from the input M (already scaled so that its spectrum lies in (0,1]) run
+// `iters` updates of (Y, Z); the first is the closed form E_1 = 3/2 I - 1/2 M, Z_1 = E_1,
+// Y_1 = M E_1.  keepY: the caller wants Y_k (first call of p = 4), otherwise Z_k.  The
+// iterate that is not wanted is not computed in the last iteration (its value is unused),
+// which saves one product per call relative to 3k-2.
+// M is buf[mi]; on return *out_idx names the buffer with the wanted iterate, unless
+// `final_out` is given: then the wanted Z_k is written there, multiplied by unscale_b.
+dash_status ndb_call(dash_ctx* c, float* buf[5], int mi, int64_t n, int B, int iters, bool keepY,
+                     bool m_needs_init, const float* A_in, float eps, const float* inv_s, float* final_out,
+                     const float* unscale, int32_t* nonfinite, int* out_idx) {
+    hipStream_t st = c->stream;
+    // free list management over the 5 buffers
+    bool used[5] = {false, false, false, false, false};
+    auto grab = [&]() { for (int i = 0; i < 5; ++i) if (!used[i]) { used[i] = true; return i; } return -1; };
+    int y, z;
+    if (m_needs_init) {
+        // first call: M = (A + eps I)/s -> buf[y]; E_1 = 1.5 I - 0.5 M -> buf[z]
+        y = grab(); z = grab();
+        HIP_TRY(c, launch_scale_shift(A_in, n, B, eps, inv_s, 1.f, 0.f, buf[y], -0.5f, 1.5f, buf[z], nullptr, st));
+    } else {
+        // chained call: M is buf[mi] as it stands; E_1 = 1.5 I - 0.5 M
+        used[mi] = true; y = mi; z = grab();
+        HIP_TRY(c, launch_scale_shift(buf[y], n, B, 0.f, nullptr, -0.5f, 1.5f, buf[z], 0.f, 0.f, nullptr, nullptr, st));
+    }
+    if (iters == 1) {
+        if (keepY) {
+            int y1 = grab();
+            DASH_TRY(gemm1(c, problem(buf[y], buf[z], nullptr, buf[y1], nullptr, 1.f, 0.f, 0.f), n, B));
+            *out_idx = y1;
+        } else if (final_out) {
+            // X = unscale * Z_1: no product at all
+            HIP_TRY(c, launch_scale_shift(buf[z], n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nonfinite, st));
+        } else {
+            *out_idx = z;
+        }
+        return DASH_OK;
+    }
+    {   // Y_1 = M E_1
+        int y1 = grab();
+        DASH_TRY(gemm1(c, problem(buf[y], buf[z], nullptr, buf[y1], nullptr, 1.f, 0.f, 0.f), n, B));
+        used[y] = false; y = y1;
+    }
+    for (int it = 2; it <= iters; ++it) {
+        const bool last = it == iters;
+        int e = grab();
+        // E = 1.5 I - 0.5 Z Y
+        DASH_TRY(gemm1(c, problem(buf[z], buf[y], nullptr, buf[e], nullptr, -0.5f, 0.f, 1.5f), n, B));
+        if (!last) {
+            int y2 = grab(), z2 = grab();
+            DASH_TRY(gemm2(c, problem(buf[y], buf[e], nullptr, buf[y2], nullptr, 1.f, 0.f, 0.f),
+                           problem(buf[e], buf[z], nullptr, buf[z2], nullptr, 1.f, 0.f, 0.f), n, B));
+            used[y] = used[z] = used[e] = false;
+            y = y2; z = z2;
+        } else if (keepY) {
+            int y2 = grab();
+            DASH_TRY(gemm1(c, problem(buf[y], buf[e], nullptr, buf[y2], nullptr, 1.f, 0.f, 0.f), n, B));
+            *out_idx = y2;
+        } else if (final_out) {
+            DASH_TRY(gemm1(c, problem(buf[e], buf[z], nullptr, final_out, unscale, 1.f, 0.f, 0.f), n, B, nonfinite));
+        } else {
+            int z2 = grab();
+            DASH_TRY(gemm1(c, problem(buf[e], buf[z], nullptr, buf[z2], nullptr, 1.f, 0.f, 0.f), n, B));
+            *out_idx = z2;
+        }
+    }
+    return DASH_OK;
+}
+
+// ---- Clenshaw on one chunk (paper Appendix A.2, reduced form, d-1 products) --------------
+dash_status clenshaw_chunk(dash_ctx* c, float* buf[3], const float* A, float* X, int64_t n, int B, int d,
+                           const double* cf, double ca, double cb, float eps, const float* inv_s,
+                           const float* unscale, int32_t* nonfinite) {
+    hipStream_t st = c->stream;
+    float* S = buf[0];
+    float* b1 = buf[1];   // B_{k+1}
+    float* b2 = buf[2];   // B_{k+2}
+    const float m1 = (float)(2.0 / (cb - ca)), m0 = (float)(-(ca + cb) / (cb - ca));
+    // S = (2 A_s - (a+b) I)/(b-a);  B_{d-1} = 2 c_d S + c_{d-1} I.  B_d = c_d I is never stored:
+    // it only enters B_{d-2} through "- B_d + c_{d-2} I" = (c_{d-2} - c_d) I.
+    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, m1, m0, S, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
+                                  nullptr, st));
+    if (d == 2) {
+        // result = S B_1 - B_2 + c_0 I with B_2 = c_2 I
+        return gemm1(c, problem(S, b1, nullptr, X, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B, nonfinite);
+    }
+    // k = d-2: B_{d-2} = 2 S B_{d-1} + (c_{d-2} - c_d) I
+    DASH_TRY(gemm1(c, problem(S, b1, nullptr, b2, nullptr, 2.f, 0.f, (float)(cf[d - 2] - cf[d])), n, B));
+    { float* t = b1; b1 = b2; b2 = t; }   // b1 = B_{d-2}, b2 = B_{d-1}
+    for (int k = d - 3; k >= 1; --k) {
+        // B_k = 2 S B_{k+1} - B_{k+2} + c_k I, written over B_{k+2}
+        DASH_TRY(gemm1(c, problem(S, b1, b2, b2, nullptr, 2.f, -1.f, (float)cf[k]), n, B));
+        float* t = b1; b1 = b2; b2 = t;
+    }
+    // result = S B_1 - B_2 + c_0 I, un-scaled
+    return gemm1(c, problem(S, b1, b2, X, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite);
+}
+
+}  // namespace
+
+// =========================================================================================
+// public ABI
+// =========================================================================================
+
+extern "C" {
+
+const char* dash_status_string(dash_status s) {
+    switch (s) {
+        case DASH_OK: return "ok";
+        case DASH_ERR_INVALID_ARG: return "invalid argument";
+        case DASH_ERR_UNSUPPORTED: return "unsupported";
+        case DASH_ERR_WORKSPACE: return "workspace missing or too small";
+        case DASH_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+dash_status dash_create(dash_ctx** out, int device, void* hip_stream) {
+    if (!out) return DASH_ERR_INVALID_ARG;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return DASH_ERR_HIP;
+    if (hipSetDevice(device) != hipSuccess) return DASH_ERR_HIP;
+    dash_ctx* c = new (std::nothrow) dash_ctx();
+    if (!c) return DASH_ERR_HIP;
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    *out = c;
+    return DASH_OK;
+}
+
+dash_status dash_destroy(dash_ctx* c) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    delete c;
+    return DASH_OK;
+}
+
+size_t dash_workspace_bytes(int64_t n_blocks, int B, dash_method method, int p, dash_precision precision) {
+    (void)p;
+    if (n_blocks <= 0 || !valid_B(B)) return 0;
+    return (size_t)n_blocks * per_block_bytes(B, method, precision) + 4 * WS_ALIGN * 16;
+}
+
+dash_status dash_set_workspace(dash_ctx* c, void* dev_ptr, size_t bytes) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (dev_ptr && ((uintptr_t)dev_ptr % WS_ALIGN)) return fail(c, DASH_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    c->ws = (char*)dev_ptr;
+    c->ws_bytes = dev_ptr ? bytes : 0;
+    return DASH_OK;
+}
+
+const char* dash_last_error(const dash_ctx* c) { return c ? c->err : "null context"; }
+
+dash_status dash_reset_stats(dash_ctx* c) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    DASH_TRY(collect_events(c));
+    c->mm_products = c->mm_launches = 0;
+    c->mm_block_products = 0.0;
+    c->ms_done = 0.0;
+    return DASH_OK;
+}
+
+dash_status dash_set_timing(dash_ctx* c, int on) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    DASH_TRY(collect_events(c));
+    c->timing = on != 0;
+    return DASH_OK;
+}
+
+dash_status dash_get_stats(dash_ctx* c, dash_stats* out) {
+    if (!c || !out) return DASH_ERR_INVALID_ARG;
+    DASH_TRY(collect_events(c));
+    out->matmul_products = c->mm_products;
+    out->matmul_launches = c->mm_launches;
+    out->matmul_block_products = c->mm_block_products;
+    out->matmul_ms = c->ms_done;
+    return DASH_OK;
+}
+
+dash_status dash_gemm_batched(dash_ctx* c, int transA, int transB, const float* A, const float* Bm, const float* D,
+                              float* C, int64_t N, int B, float alpha, float beta, float gamma,
+                              dash_precision precision) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64 (N=%lld B=%d)", (long long)N, B);
+    if (N == 0) return DASH_OK;
+    if (!A || !Bm || !C) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    if (!D && beta != 0.f) return fail(c, DASH_ERR_INVALID_ARG, "beta != 0 needs D");
+    if (precision != DASH_FP32) return fail(c, DASH_ERR_UNSUPPORTED, "bf16 operands not built yet");
+    const size_t bytes = (size_t)N * B * B * sizeof(float);
+    if (overlap(C, A, bytes) || overlap(C, Bm, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "C overlaps an operand");
+    if (D && D != C && overlap(C, D, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "D must equal C or be disjoint from it");
+    HIP_TRY(c, hipSetDevice(c->device));
+    return gemm1(c, problem(A, Bm, D, C, nullptr, alpha, beta, gamma, transA ? 1 : 0, transB ? 1 : 0), N, B);
+}
+
+dash_status dash_accumulate_factors(dash_ctx* c, const float* G, float* L, float* R, int64_t N, int B, float beta,
+                                    float alpha) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64 (N=%lld B=%d)", (long long)N, B);
+    if (N == 0) return DASH_OK;
+    if (!G || !L || !R) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    const size_t bytes = (size_t)N * B * B * sizeof(float);
+    if (overlap(L, G, bytes) || overlap(R, G, bytes) || overlap(L, R, bytes))
+        return fail(c, DASH_ERR_INVALID_ARG, "G, L, R must not overlap");
+    HIP_TRY(c, hipSetDevice(c->device));
+    // L = beta L + alpha G G^T ; R = beta R + alpha G^T G  (EMA fused in the epilogue)
+    DASH_TRY(gemm1(c, problem(G, G, L, L, nullptr, alpha, beta, 0.f, 0, 1), N, B));
+    DASH_TRY(gemm1(c, problem(G, G, R, R, nullptr, alpha, beta, 0.f, 1, 0), N, B));
+    return DASH_OK;
+}
+
+dash_status dash_block_norms(dash_ctx* c, const float* A, int64_t N, int B, float eps, dash_scaling scaling,
+                             float* s_out) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64");
+    if ((int)scaling < 0 || (int)scaling > 2) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
+    if (N == 0) return DASH_OK;
+    if (!A || !s_out) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    HIP_TRY(c, hipSetDevice(c->device));
+    const int P = norm_slabs(B);
+    const size_t per = SCALARS_PER_BLOCK;
+    if (!c->ws || c->ws_bytes < per) return fail(c, DASH_ERR_WORKSPACE, "workspace needed (%zu bytes per block)", per);
+    const int64_t chunk = (int64_t)(c->ws_bytes / per);
+    for (int64_t b0 = 0; b0 < N; b0 += chunk) {
+        const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
+        float* partial = (float*)c->ws;
+        if (scaling != DASH_SCALE_NONE)
+            HIP_TRY(c, launch_norm_partials(A + (size_t)b0 * B * B, nb, B, eps, (int)scaling, partial, c->stream));
+        HIP_TRY(c, launch_finalize_scale(partial, nb, P, (int)scaling, 2, s_out + b0, nullptr, nullptr, c->stream));
+    }
+    return DASH_OK;
+}
+
+dash_status dash_chebyshev_fit(int p, int degree, double a, double b, int n_points, double* coeffs_out) {
+    if ((p != 2 && p != 4) || degree < 0 || n_points < degree + 1 || !(b > a) || !(a > 0.0) || !coeffs_out)
+        return DASH_ERR_INVALID_ARG;
+    // cosine-series fit at the Chebyshev nodes theta_v = (2v+1) pi / (2N)  (Appendix A.1)
+    const double pi = 3.14159265358979323846;
+    std::vector<double> fx(n_points), th(n_points);
+    for (int v = 0; v < n_points; ++v) {
+        th[v] = (2.0 * v + 1.0) * pi / (2.0 * n_points);
+        const double x = 0.5 * (b - a) * std::cos(th[v]) + 0.5 * (b + a);
+        fx[v] = std::pow(x, -1.0 / p);
+    }
+    for (int k = 0; k <= degree; ++k) {
+        double acc = 0.0;
+        for (int v = 0; v < n_points; ++v) acc += fx[v] * std::cos(k * th[v]);
+        coeffs_out[k] = 2.0 / n_points * acc;
+    }
+    coeffs_out[0] *= 0.5;
+    return DASH_OK;
+}
+
+dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, int B, dash_method method, int p,
+                              int iters, float eps, dash_scaling scaling, dash_precision precision,
+                              const double* cheb_coeffs, double cheb_a, double cheb_b, float* scale_out,
+                              int32_t* nonfinite_out) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64 (N=%lld B=%d)", (long long)N, B);
+    if (p != 2 && p != 4) return fail(c, DASH_ERR_INVALID_ARG, "p must be 2 or 4 (got %d)", p);
+    if (method != DASH_NEWTON_DB && method != DASH_CHEBYSHEV) return fail(c, DASH_ERR_INVALID_ARG, "bad method");
+    if ((int)scaling < 0 || (int)scaling > 2) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
+    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32) return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
+    if (method == DASH_NEWTON_DB && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Newton-DB needs iters >= 1");
+    if (method == DASH_CHEBYSHEV) {
+        if (iters < 2) return fail(c, DASH_ERR_INVALID_ARG, "Chebyshev needs degree >= 2");
+        if (!cheb_coeffs) return fail(c, DASH_ERR_INVALID_ARG, "Chebyshev needs coefficients");
+        if (!(cheb_b > cheb_a)) return fail(c, DASH_ERR_INVALID_ARG, "Chebyshev interval must have b > a");
+    }
+    if (!(eps >= 0.f)) return fail(c, DASH_ERR_INVALID_ARG, "eps must be >= 0");
+    if (N == 0) return DASH_OK;
+    if (!A || !X) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    if (overlap(A, X, (size_t)N * B * B * sizeof(float))) return fail(c, DASH_ERR_INVALID_ARG, "X overlaps A");
+    if (precision != DASH_FP32) return fail(c, DASH_ERR_UNSUPPORTED, "bf16 operands not built yet");
+    HIP_TRY(c, hipSetDevice(c->device));
+
+    const size_t per = per_block_bytes(B, method, precision);
+    const size_t slack = 4 * WS_ALIGN * 16;
+    if (!c->ws || c->ws_bytes < per + slack)
+        return fail(c, DASH_ERR_WORKSPACE, "workspace holds %zu bytes, one block needs %zu", c->ws_bytes, per + slack);
+    int64_t chunk = (int64_t)((c->ws_bytes - slack) / per);
+    if (chunk > N) chunk = N;
+
+    const size_t mat = (size_t)B * B;
+    const int P = norm_slabs(B);
+    const int nbuf = buffers_needed(method);
+    hipStream_t st = c->stream;
+
+    for (int64_t b0 = 0; b0 < N; b0 += chunk) {
+        const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
+        Carve cv{c->ws, c->ws + c->ws_bytes};
+        float* partial = (float*)cv.take((size_t)nb * P * sizeof(float));
+        float* s = (float*)cv.take((size_t)nb * sizeof(float));
+        float* inv_s = (float*)cv.take((size_t)nb * sizeof(float));
+        float* unscale = (float*)cv.take((size_t)nb * sizeof(float));
+        float* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+        for (int i = 0; i < nbuf; ++i) buf[i] = (float*)cv.take((size_t)nb * mat * sizeof(float));
+        if (!partial || !s || !inv_s || !unscale || !buf[nbuf - 1])
+            return fail(c, DASH_ERR_WORKSPACE, "internal: workspace carve failed");
+
+        const float* Ac = A + (size_t)b0 * mat;
+        float* Xc = X + (size_t)b0 * mat;
+        int32_t* nf = nonfinite_out ? nonfinite_out + b0 : nullptr;
+        if (nf) HIP_TRY(c, launch_fill_i32(nf, nb, 0, st));
+
+        // Section 3.4: s = ||A + eps I||_F (or trace), kept with 1/s and s^(-1/p)
+        if (scaling != DASH_SCALE_NONE) HIP_TRY(c, launch_norm_partials(Ac, nb, B, eps, (int)scaling, partial, st));
+        HIP_TRY(c, launch_finalize_scale(partial, nb, P, (int)scaling, p, scale_out ? scale_out + b0 : s, inv_s, unscale, st));
+
+        if (method == DASH_NEWTON_DB) {
+            int idx = -1;
+            if (p == 2) {
+                DASH_TRY(ndb_call(c, buf, -1, nb, B, iters, false, true, Ac, eps, inv_s, Xc, unscale, nf, &idx));
+            } else {
+                DASH_TRY(ndb_call(c, buf, -1, nb, B, iters, true, true, Ac, eps, inv_s, nullptr, nullptr, nullptr, &idx));
+                int idx2 = -1;
+                DASH_TRY(ndb_call(c, buf, idx, nb, B, iters, false, false, nullptr, 0.f, nullptr, Xc, unscale, nf, &idx2));
+            }
+        } else {
+            DASH_TRY(clenshaw_chunk(c, buf, Ac, Xc, nb, B, iters, cheb_coeffs, cheb_a, cheb_b, eps, inv_s, unscale, nf));
+        }
+    }
+    return DASH_OK;
+}
+
+dash_status dash_precondition(dash_ctx* c, const float* Linv, const float* G, const float* Rinv, float* U, int64_t N,
+                              int B) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64 (N=%lld B=%d)", (long long)N, B);
+    if (N == 0) return DASH_OK;
+    if (!Linv || !G || !Rinv || !U) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    const size_t mat = (size_t)B * B, bytes = (size_t)N * mat * sizeof(float);
+    if (overlap(U, Linv, bytes) || overlap(U, G, bytes) || overlap(U, Rinv, bytes))
+        return fail(c, DASH_ERR_INVALID_ARG, "U overlaps an input");
+    HIP_TRY(c, hipSetDevice(c->device));
+    const size_t per = mat * sizeof(float);
+    if (!c->ws || c->ws_bytes < per) return fail(c, DASH_ERR_WORKSPACE, "workspace holds %zu bytes, one block needs %zu", c->ws_bytes, per);
+    int64_t chunk = (int64_t)(c->ws_bytes / per);
+    if (chunk > N) chunk = N;
+    float* T = (float*)c->ws;
+    for (int64_t b0 = 0; b0 < N; b0 += chunk) {
+        const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
+        const size_t o = (size_t)b0 * mat;
+        DASH_TRY(gemm1(c, problem(Linv + o, G + o, nullptr, T, nullptr, 1.f, 0.f, 0.f), nb, B));
+        DASH_TRY(gemm1(c, problem(T, Rinv + o, nullptr, U + o, nullptr, 1.f, 0.f, 0.f), nb, B));
+    }
+    return DASH_OK;
+}
+
+dash_status dash_graft_update(dash_ctx* c, const float* G, const float* U, float* Acc, float* theta, int64_t N, int B,
+                              float beta_g, float eps_g, float lr, float* s_out) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64");
+    if (N == 0) return DASH_OK;
+    if (!G || !U || !Acc) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    HIP_TRY(c, hipSetDevice(c->device));
+    const size_t per = SCALARS_PER_BLOCK;
+    if (!c->ws || c->ws_bytes < per) return fail(c, DASH_ERR_WORKSPACE, "workspace needed (%zu bytes per block)", per);
+    int64_t chunk = (int64_t)(c->ws_bytes / per);
+    if (chunk > N) chunk = N;
+    const size_t mat = (size_t)B * B;
+    float* partial = (float*)c->ws;
+    for (int64_t b0 = 0; b0 < N; b0 += chunk) {
+        const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
+        const size_t o = (size_t)b0 * mat;
+        HIP_TRY(c, launch_graft_partials(G + o, U + o, Acc + o, nb, B, beta_g, eps_g, partial, c->stream));
+        HIP_TRY(c, launch_graft_apply(U + o, theta ? theta + o : nullptr, partial, nb, B, lr, s_out ? s_out + b0 : nullptr, c->stream));
+    }
+    return DASH_OK;
+}
+
+dash_status dash_step(dash_ctx* c, const dash_step_args* a) {
+    if (!c || !a) return DASH_ERR_INVALID_ARG;
+    if (a->N < 0 || !valid_B(a->B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64");
+    if (a->N == 0) return DASH_OK;
+    if (!a->G || !a->S || !a->X || !a->U) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    if (a->graft && !a->graft_acc) return fail(c, DASH_ERR_INVALID_ARG, "grafting needs graft_acc");
+    const size_t mat = (size_t)a->B * a->B;
+    float* L = a->S;
+    float* R = a->S + (size_t)a->N * mat;
+    // Algorithm 1: EMA of the factors
+    DASH_TRY(dash_accumulate_factors(c, a->G, L, R, a->N, a->B, a->beta, a->alpha));
+    // roots of all 2N damped blocks in one call over the stack [L; R] (Section 4.1)
+    if (a->refresh)
+        DASH_TRY(dash_inverse_root(c, a->S, a->X, 2 * a->N, a->B, (dash_method)a->method, a->p, a->iters, a->eps,
+                                   (dash_scaling)a->scaling, (dash_precision)a->precision, a->cheb_coeffs, a->cheb_a,
+                                   a->cheb_b, nullptr, a->nonfinite_out));
+    // Algorithm 1: U = L^{-1/p} G R^{-1/p}
+    DASH_TRY(dash_precondition(c, a->X, a->G, a->X + (size_t)a->N * mat, a->U, a->N, a->B));
+    if (a->graft)
+        DASH_TRY(dash_graft_update(c, a->G, a->U, a->graft_acc, a->theta, a->N, a->B, a->beta_g, a->eps_g, a->lr, nullptr));
+    return DASH_OK;
+}
+
+}  // extern "C"

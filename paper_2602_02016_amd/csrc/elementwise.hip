@@ -1,0 +1,238 @@
+// HBM-bound kernels of the path: per-block Frobenius norm / trace (paper Section 3.4),
+// the closed-form first Newton-DB iterate and the Chebyshev start terms (Section 3.3,
+// Appendix A.2), and block-wise Adam grafting (Section 2.3).
+//
+// All of them stream the stack once with 16-byte accesses, 256 threads per workgroup,
+// one workgroup per row slab of a block so that even a short stack gives the 256 CUs
+// enough workgroups.  Per-block reductions are two-stage (slab partials, then a fixed
+// order sum) so results do not depend on scheduling; no atomics are used.
+#include "kernels.h"
+
+namespace dash {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int NT = 256;
+
+int norm_slabs(int B) { return B >= 256 ? 32 : 8; }   // B is a multiple of 64, so both divide B
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// sum over the workgroup; result valid in thread 0
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (lane == 0) sh[w] = v;
+    __syncthreads();
+    float r = 0.f;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < NT / 64; ++i) r += sh[i];
+    }
+    __syncthreads();
+    return r;
+}
+
+// grid = (P, nblocks): slab q of block b
+__global__ __launch_bounds__(NT) void norm_partials_kernel(const float* __restrict__ A, int B, int P,
+                                                          float eps, int mode, float* __restrict__ partial) {
+    __shared__ float sh[NT / 64];
+    const int q = blockIdx.x;
+    const int64_t b = blockIdx.y;
+    const int rows = B / P, r0 = q * rows;
+    const float* __restrict__ Ab = A + (size_t)b * B * B;
+    float acc = 0.f;
+    if (mode == 0) {
+        const int qpr = B / 4;   // float4 per row
+        for (int f = threadIdx.x; f < rows * qpr; f += NT) {
+            const int r = r0 + f / qpr, c = 4 * (f % qpr);
+            v4f v = *reinterpret_cast<const v4f*>(Ab + (size_t)r * B + c);
+            if (r >= c && r < c + 4) v[r - c] += eps;
+            acc += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+        }
+    } else {
+        for (int r = r0 + threadIdx.x; r < r0 + rows; r += NT) acc += Ab[(size_t)r * B + r] + eps;
+    }
+    const float tot = block_sum(acc, sh);
+    if (threadIdx.x == 0) partial[b * P + q] = tot;
+}
+
+__global__ void finalize_scale_kernel(const float* __restrict__ partial, int64_t n, int P, int mode, int p,
+                                      float* s, float* inv_s, float* unscale) {
+    const int64_t b = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (b >= n) return;
+    float sv = 1.f;
+    if (mode != 2) {
+        float t = 0.f;
+        for (int q = 0; q < P; ++q) t += partial[b * P + q];
+        sv = mode == 0 ? sqrtf(t) : t;
+    }
+    if (s) s[b] = sv;
+    if (inv_s) inv_s[b] = 1.f / sv;
+    if (unscale) unscale[b] = p == 2 ? 1.f / sqrtf(sv) : 1.f / sqrtf(sqrtf(sv));
+}
+
+// grid = (B*B/4/NT per block ..., nblocks) flattened over blockIdx.x within a block
+__global__ __launch_bounds__(NT) void scale_shift_kernel(const float* __restrict__ in, int B, float eps,
+                                                        const float* __restrict__ mult, float a1, float g1,
+                                                        float* __restrict__ out1, float a2, float g2,
+                                                        float* __restrict__ out2, int32_t* nonfinite) {
+    const int64_t b = blockIdx.y;
+    const int f = blockIdx.x * NT + threadIdx.x;     // float4 index inside the block
+    const int qpr = B / 4;
+    if (f >= B * qpr) return;
+    const int r = f / qpr, c = 4 * (f % qpr);
+    const size_t off = (size_t)b * B * B + (size_t)r * B + c;
+    const float m = mult ? mult[b] : 1.f;
+    v4f v = *reinterpret_cast<const v4f*>(in + off);
+    const int d = r - c;                              // diagonal position inside this float4, if 0..3
+    if (d >= 0 && d < 4) v[d] += eps;
+    v4f o1, o2;
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o1[i] = a1 * (v[i] * m) + (i == d ? g1 : 0.f);
+        o2[i] = a2 * o1[i] + (i == d ? g2 : 0.f);
+        bad |= !(fabsf(o1[i]) <= 3.0e38f);
+    }
+    *reinterpret_cast<v4f*>(out1 + off) = o1;
+    if (out2) *reinterpret_cast<v4f*>(out2 + off) = o2;
+    if (nonfinite && bad) nonfinite[b] = 1;
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
+    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// grid = (P, nblocks)
+__global__ __launch_bounds__(NT) void graft_partials_kernel(const float* __restrict__ G, const float* __restrict__ U,
+                                                           float* __restrict__ Acc, int B, int P, float beta_g,
+                                                           float eps_g, float* __restrict__ partial) {
+    __shared__ float sh[NT / 64];
+    const int q = blockIdx.x;
+    const int64_t b = blockIdx.y;
+    const size_t per = (size_t)B * B / P;             // contiguous floats per slab
+    const size_t base = (size_t)b * B * B + (size_t)q * per;
+    float sp = 0.f, su = 0.f;
+    for (size_t f = threadIdx.x; f < per / 4; f += NT) {
+        const size_t off = base + 4 * f;
+        const v4f g = *reinterpret_cast<const v4f*>(G + off);
+        const v4f u = *reinterpret_cast<const v4f*>(U + off);
+        v4f a = *reinterpret_cast<const v4f*>(Acc + off);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i] = beta_g * a[i] + (1.f - beta_g) * g[i] * g[i];
+            const float pv = g[i] / (eps_g + sqrtf(a[i]));
+            sp += pv * pv;
+            su += u[i] * u[i];
+        }
+        *reinterpret_cast<v4f*>(Acc + off) = a;
+    }
+    const float tp = block_sum(sp, sh);
+    const float tu = block_sum(su, sh);
+    if (threadIdx.x == 0) {
+        partial[(b * P + q) * 2 + 0] = tp;
+        partial[(b * P + q) * 2 + 1] = tu;
+    }
+}
+
+// grid = (P, nblocks)
+__global__ __launch_bounds__(NT) void graft_apply_kernel(const float* __restrict__ U, float* __restrict__ theta,
+                                                        const float* __restrict__ partial, int B, int P, float lr,
+                                                        float* __restrict__ s_out) {
+    const int q = blockIdx.x;
+    const int64_t b = blockIdx.y;
+    float tp = 0.f, tu = 0.f;
+    for (int i = 0; i < P; ++i) {
+        tp += partial[(b * P + i) * 2 + 0];
+        tu += partial[(b * P + i) * 2 + 1];
+    }
+    const float s = sqrtf(tp) / sqrtf(tu);
+    if (s_out && q == 0 && threadIdx.x == 0) s_out[b] = s;
+    if (!theta) return;
+    const float k = lr * s;
+    const size_t per = (size_t)B * B / P;
+    const size_t base = (size_t)b * B * B + (size_t)q * per;
+    for (size_t f = threadIdx.x; f < per / 4; f += NT) {
+        const size_t off = base + 4 * f;
+        const v4f u = *reinterpret_cast<const v4f*>(U + off);
+        v4f t = *reinterpret_cast<v4f*>(theta + off);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] -= k * u[i];
+        *reinterpret_cast<v4f*>(theta + off) = t;
+    }
+}
+
+// ---- launchers ------------------------------------------------------------------------
+
+
+hipError_t launch_norm_partials(const float* A, int64_t nblocks, int B, float eps, int mode, float* partial,
+                                hipStream_t stream) {
+    const int P = norm_slabs(B);
+    for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
+        const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
+        hipLaunchKernelGGL(norm_partials_kernel, dim3(P, (unsigned)nb), dim3(NT), 0, stream,
+                           A + (size_t)b0 * B * B, B, P, eps, mode, partial + b0 * P);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, int mode, int p, float* s,
+                                 float* inv_s, float* unscale, hipStream_t stream) {
+    if (nblocks <= 0) return hipSuccess;
+    hipLaunchKernelGGL(finalize_scale_kernel, dim3((unsigned)((nblocks + 255) / 256)), dim3(256), 0, stream,
+                       partial, nblocks, P, mode, p, s, inv_s, unscale);
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult, float a1,
+                              float g1, float* out1, float a2, float g2, float* out2, int32_t* nonfinite,
+                              hipStream_t stream) {
+    const unsigned gx = (unsigned)(((size_t)B * B / 4 + NT - 1) / NT);
+    for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
+        const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
+        const size_t o = (size_t)b0 * B * B;
+        hipLaunchKernelGGL(scale_shift_kernel, dim3(gx, (unsigned)nb), dim3(NT), 0, stream, in + o, B, eps,
+                           mult ? mult + b0 : nullptr, a1, g1, out1 + o, a2, g2, out2 ? out2 + o : nullptr,
+                           nonfinite ? nonfinite + b0 : nullptr);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_graft_partials(const float* G, const float* U, float* Acc, int64_t nblocks, int B,
+                                 float beta_g, float eps_g, float* partial, hipStream_t stream) {
+    const int P = norm_slabs(B);
+    for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
+        const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
+        const size_t o = (size_t)b0 * B * B;
+        hipLaunchKernelGGL(graft_partials_kernel, dim3(P, (unsigned)nb), dim3(NT), 0, stream, G + o, U + o,
+                           Acc + o, B, P, beta_g, eps_g, partial + b0 * P * 2);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_graft_apply(const float* U, float* theta, const float* partial, int64_t nblocks, int B,
+                              float lr, float* s_out, hipStream_t stream) {
+    const int P = norm_slabs(B);
+    for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
+        const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
+        const size_t o = (size_t)b0 * B * B;
+        hipLaunchKernelGGL(graft_apply_kernel, dim3(P, (unsigned)nb), dim3(NT), 0, stream, U + o,
+                           theta ? theta + o : nullptr, partial + b0 * P * 2, B, P, lr,
+                           s_out ? s_out + b0 : nullptr);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace dash

@@ -1,0 +1,246 @@
+// Strided-batched B x B x B matmul over a block stack with a fused epilogue, for gfx950.
+//
+// This is the primitive the paper calls `bmm` (Sections 3.1, 4.1): every step of the
+// hot path -- factor accumulation (Algorithm 1), the Newton-DB updates (Section 3.3),
+// the Clenshaw recurrence (Appendix A.2) and the preconditioned update -- is this
+// product with a different epilogue:
+//     C_b = mult_b * (alpha * op(A_b) op(B_b) + beta * D_b + gamma * I)
+//
+// Design (CDNA4): one workgroup of 256 threads (four 64-wide wavefronts in a 2 x 2
+// arrangement) owns one TM x TN output tile of one block.  K is walked in slabs of 16
+// that are staged through LDS (double buffered, one barrier per slab) while the next
+// slab is already in flight from global memory into registers.  Each wavefront
+// accumulates its (TM/2) x (TN/2) sub-tile with v_mfma_f32_32x32x2_f32.
+//
+// Operand staging.  An MFMA operand wants, per lane, the element (row = lane%32,
+// k = lane/32).  Depending on which index is contiguous in global memory a slab is
+// kept in one of two LDS layouts, both filled with 16-byte stores straight from
+// 16-byte global loads:
+//   KC  [row][k]  (k contiguous; row pitch 20 floats): one 16-byte LDS read gives a lane
+//       its operand for four consecutive MFMAs (k = 4*(lane/32) + s, s = 0..3);
+//   RC  [k][row]  (row contiguous; k pitch TILE+8 floats): four 4-byte reads, one per
+//       MFMA, lanes reading consecutive addresses.
+// Both layouts use the same k <-> (lane half, step) assignment, so any combination of
+// transposed / non-transposed operands contracts over matching k.
+//
+// Grid.  1-D, one workgroup per (block, product, tile).  Hardware hands consecutive
+// workgroup ids to the 8 XCDs round-robin; the id is remapped so that each XCD works
+// through a contiguous range of blocks and the tiles of one block (which share the
+// A and B panels) meet in one XCD's L2.
+#include "kernels.h"
+
+namespace dash {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int BK = 16;         // K slab
+constexpr int KC_PITCH = 20;   // floats per row in the k-contiguous layout (16 + 4 pad)
+constexpr int NTHREADS = 256;
+constexpr int NUM_XCD = 8;
+
+template <int TILE>
+struct Lds {
+    static constexpr int RC_PITCH = TILE + 8;
+    static constexpr int KC_SIZE = TILE * KC_PITCH;
+    static constexpr int RC_SIZE = BK * RC_PITCH;
+    static constexpr int SIZE = KC_SIZE > RC_SIZE ? KC_SIZE : RC_SIZE;  // floats per operand slab
+};
+
+// ---- global -> registers ------------------------------------------------------------
+// A slab holds TILE*BK floats = TILE*4 float4; each thread carries TILE*4/256 of them.
+template <int TILE, bool KC>
+__device__ __forceinline__ void load_slab(const float* __restrict__ base, int ld, int row0, int k0,
+                                          v4f (&r)[TILE * 4 / NTHREADS]) {
+    constexpr int NV = TILE * 4 / NTHREADS;
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int f = t + NTHREADS * u;
+        if (KC) {   // element (row, k) at base[row*ld + k]
+            const int row = f >> 2, kq = f & 3;
+            r[u] = *reinterpret_cast<const v4f*>(base + (size_t)(row0 + row) * ld + k0 + 4 * kq);
+        } else {    // element (row, k) at base[k*ld + row]
+            constexpr int QPR = TILE / 4;   // float4 per k-line
+            const int k = f / QPR, rq = f % QPR;
+            r[u] = *reinterpret_cast<const v4f*>(base + (size_t)(k0 + k) * ld + row0 + 4 * rq);
+        }
+    }
+}
+
+// ---- registers -> LDS ----------------------------------------------------------------
+template <int TILE, bool KC>
+__device__ __forceinline__ void store_slab(float* __restrict__ s, const v4f (&r)[TILE * 4 / NTHREADS]) {
+    constexpr int NV = TILE * 4 / NTHREADS;
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int f = t + NTHREADS * u;
+        if (KC) {
+            const int row = f >> 2, kq = f & 3;
+            *reinterpret_cast<v4f*>(s + row * KC_PITCH + 4 * kq) = r[u];
+        } else {
+            constexpr int QPR = TILE / 4;
+            const int k = f / QPR, rq = f % QPR;
+            *reinterpret_cast<v4f*>(s + k * Lds<TILE>::RC_PITCH + 4 * rq) = r[u];
+        }
+    }
+}
+
+// ---- LDS -> MFMA operand fragments for one chunk of 8 k --------------------------------
+// Returns, for the 32-row sub-tile starting at r0, the four operand values this lane
+// feeds to MFMA steps s = 0..3 of chunk c: element (r0 + lane%32, 8c + 4*(lane/32) + s).
+template <int TILE, bool KC>
+__device__ __forceinline__ v4f read_frag(const float* __restrict__ s, int r0, int c, int lane) {
+    const int rr = r0 + (lane & 31), kh = 8 * c + 4 * (lane >> 5);
+    if (KC) {
+        return *reinterpret_cast<const v4f*>(s + rr * KC_PITCH + kh);
+    } else {
+        constexpr int P = Lds<TILE>::RC_PITCH;
+        v4f v;
+        v[0] = s[(kh + 0) * P + rr];
+        v[1] = s[(kh + 1) * P + rr];
+        v[2] = s[(kh + 2) * P + rr];
+        v[3] = s[(kh + 3) * P + rr];
+        return v;
+    }
+}
+
+// TILE x TILE output tile per workgroup; each of the 4 waves owns (TILE/2) x (TILE/2),
+// i.e. MT x MT MFMA tiles of 32 x 32 with MT = TILE/64.
+template <int TILE, bool TA, bool TB>
+__global__ __launch_bounds__(NTHREADS, 2) void gemm_f32_kernel(GemmLaunch g) {
+    constexpr int MT = TILE / 64;
+    constexpr bool A_KC = !TA;   // op(A)(i,k): k contiguous unless transposed
+    constexpr bool B_KC = TB;    // op(B)(k,j): j contiguous unless transposed
+    constexpr int NV = TILE * 4 / NTHREADS;
+    constexpr int SLAB = Lds<TILE>::SIZE;
+
+    __shared__ __attribute__((aligned(16))) float lds[2 * 2 * SLAB];
+
+    // ---- which tile am I (XCD-aware remap of the 1-D grid) ----
+    const int64_t W = gridDim.x;
+    const int64_t bid = blockIdx.x;
+    const int64_t xcd = bid % NUM_XCD, local = bid / NUM_XCD;
+    const int64_t per = W / NUM_XCD, rem = W % NUM_XCD;
+    const int64_t lid = xcd * per + (xcd < rem ? xcd : rem) + local;
+
+    const int B = g.B;
+    const int tiles = B / TILE;
+    const int T = tiles * tiles;
+    const int64_t blk = lid / ((int64_t)g.nprob * T);
+    const int r1 = (int)(lid % ((int64_t)g.nprob * T));
+    const int pi = r1 / T;
+    const int tile = r1 % T;
+    const int row0 = (tile / tiles) * TILE;
+    const int col0 = (tile % tiles) * TILE;
+
+    const GemmProblem& P = g.prob[pi];
+    const size_t boff = (size_t)blk * B * B;
+    const float* __restrict__ Ab = P.A + boff;
+    const float* __restrict__ Bb = P.B + boff;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
+
+    v16f acc[MT][MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    v4f ra[NV], rb[NV];
+    load_slab<TILE, A_KC>(Ab, B, row0, 0, ra);
+    load_slab<TILE, B_KC>(Bb, B, col0, 0, rb);
+    store_slab<TILE, A_KC>(lds, ra);
+    store_slab<TILE, B_KC>(lds + SLAB, rb);
+    __syncthreads();
+
+    const int KT = B / BK;
+    for (int kt = 0; kt < KT; ++kt) {
+        const float* sa = lds + (kt & 1) * 2 * SLAB;
+        const float* sb = sa + SLAB;
+        const bool more = kt + 1 < KT;
+        if (more) {
+            load_slab<TILE, A_KC>(Ab, B, row0, (kt + 1) * BK, ra);
+            load_slab<TILE, B_KC>(Bb, B, col0, (kt + 1) * BK, rb);
+        }
+#pragma unroll
+        for (int c = 0; c < BK / 8; ++c) {
+            v4f fa[MT], fb[MT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) fa[i] = read_frag<TILE, A_KC>(sa, wm + 32 * i, c, lane);
+#pragma unroll
+            for (int j = 0; j < MT; ++j) fb[j] = read_frag<TILE, B_KC>(sb, wn + 32 * j, c, lane);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < MT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][s], fb[j][s], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            float* da = lds + ((kt + 1) & 1) * 2 * SLAB;
+            store_slab<TILE, A_KC>(da, ra);
+            store_slab<TILE, B_KC>(da + SLAB, rb);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: C = mult * (alpha*acc + beta*D + gamma*I) ----
+    // 32x32 accumulator layout: register r of lane l holds
+    //   row = 8*(r/4) + 4*(l/32) + r%4, col = l%32 of the MFMA tile.
+    const float mult = P.mult ? P.mult[blk] : 1.f;
+    const float alpha = P.alpha * mult, beta = P.beta * mult, gamma = P.gamma * mult;
+    const float* __restrict__ Db = P.D ? P.D + boff : nullptr;
+    float* __restrict__ Cb = P.C + boff;
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < MT; ++j) {
+            const int col = col0 + wn + 32 * j + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const size_t off = (size_t)row * B + col;
+                float v = alpha * acc[i][j][r];
+                if (Db) v += beta * Db[off];
+                if (row == col) v += gamma;
+                bad |= !(fabsf(v) <= 3.0e38f);
+                Cb[off] = v;
+            }
+        }
+    if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;
+}
+
+template <int TILE>
+static hipError_t launch_tile(const GemmLaunch& g, hipStream_t stream) {
+    const int tiles = g.B / TILE;
+    const int64_t W = g.nblocks * g.nprob * tiles * tiles;
+    if (W <= 0) return hipSuccess;
+    if (W > 0x7fffffffLL) return hipErrorInvalidValue;
+    // both products of a launch must use the same transpose flags (one kernel instance)
+    const int ta = g.prob[0].transA, tb = g.prob[0].transB;
+    dim3 grid((unsigned)W), block(NTHREADS);
+    if (!ta && !tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, false>), grid, block, 0, stream, g);
+    else if (!ta && tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, true>), grid, block, 0, stream, g);
+    else if (ta && !tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, true, false>), grid, block, 0, stream, g);
+    else hipLaunchKernelGGL((gemm_f32_kernel<TILE, true, true>), grid, block, 0, stream, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
+    if (g.nprob < 1 || g.nprob > 2 || g.B <= 0 || g.B % 64) return hipErrorInvalidValue;
+    if (g.nprob == 2 && (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
+        return hipErrorInvalidValue;
+    if (g.bf16) return hipErrorNotSupported;
+    // 128-wide tiles when they still give the chip enough workgroups, else 64-wide
+    const bool big = (g.B % 128 == 0) && (g.nblocks * g.nprob * (int64_t)(g.B / 128) * (g.B / 128) >= 256);
+    return big ? launch_tile<128>(g, stream) : launch_tile<64>(g, stream);
+}
+
+}  // namespace dash

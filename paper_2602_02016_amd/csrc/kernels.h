@@ -1,0 +1,62 @@
+// Internal launch interface between the host-side library (dash.hip) and the kernels.
+// Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dash {
+
+// One batched product  C_b = mult_b * (alpha * op(A_b) op(B_b) + beta * D_b + gamma * I).
+// mult (per-block factor, device array) may be null (= 1).  D may be null when beta == 0
+// and may equal C.
+struct GemmProblem {
+    const float* A;
+    const float* B;
+    const float* D;
+    float* C;
+    const float* mult;
+    float alpha, beta, gamma;
+    int transA, transB;
+};
+
+// Up to two products over the same block range in one launch (Newton-DB computes
+// Y E and E Z together; accumulate computes G G^T and G^T G together).
+struct GemmLaunch {
+    GemmProblem prob[2];
+    int nprob;
+    int B;                 // block edge
+    int64_t nblocks;       // blocks in this launch
+    int32_t* nonfinite;    // per-block flag for prob[0]'s output, or null
+    int bf16;              // 0: fp32 MFMA operands, 1: operands rounded to bf16
+};
+
+hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream);
+
+// partial[b*P + q] = sum over the q-th row slab of block b of (A + eps I)^2 (mode 0)
+// or of the diagonal of (A + eps I) (mode 1).  P = norm_slabs(B).
+int norm_slabs(int B);
+hipError_t launch_norm_partials(const float* A, int64_t nblocks, int B, float eps, int mode,
+                                float* partial, hipStream_t stream);
+// s = sqrt(sum partial) (mode 0) | sum partial (mode 1) | 1 (mode 2);
+// writes s[b], inv_s[b] = 1/s, unscale[b] = s^(-1/p) (any of the three may be null).
+hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, int mode, int p,
+                                 float* s, float* inv_s, float* unscale, hipStream_t stream);
+
+// t = (in + eps I) * mult_b ; out1 = a1 * t + g1 * I ; out2 = a2 * out1 + g2 * I.
+// mult, out2 may be null.  out1 may be null only if out2 is null too... (out1 required).
+hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult,
+                              float a1, float g1, float* out1, float a2, float g2, float* out2,
+                              int32_t* nonfinite, hipStream_t stream);
+
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
+
+// grafting: Acc <- beta_g Acc + (1-beta_g) G.G ; partial sums of P^2 and U^2 per slab
+hipError_t launch_graft_partials(const float* G, const float* U, float* Acc, int64_t nblocks, int B,
+                                 float beta_g, float eps_g, float* partial /* [n][P][2] */,
+                                 hipStream_t stream);
+// s_b = sqrt(sum P^2 / sum U^2); theta -= lr * s_b * U (theta may be null); s_out may be null
+hipError_t launch_graft_apply(const float* U, float* theta, const float* partial, int64_t nblocks,
+                              int B, float lr, float* s_out, hipStream_t stream);
+
+}  // namespace dash

@@ -1,0 +1,148 @@
+"""Parity of dash_step and dash_graft_update (HIP, through the C ABI) with the float64
+oracle step of Algorithm 1 (eigendecomposition roots)."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import shampoo as oshampoo
+from oracle.evd import rel_frobenius_error
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dash():
+    from paper_2602_02016_amd import Dash
+    d = Dash(0)
+    yield d
+    d.close()
+
+
+def _to_gpu(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.mark.parametrize("N,B,warm", [(4, 128, 6), (3, 256, 4), (2, 512, 3)])
+def test_step_against_oracle(dash, N, B, warm):
+    """Factors are EMAs of seeded N(0, 1e-2^2) gradients (Wishart-like, well conditioned once
+    a few gradients are in); Newton-DB p=4 with k=12 is converged there, so the GPU step
+    must agree with the EVD-based oracle step to fp32 accuracy."""
+    import torch
+    print(f"step N={N} B={B}", flush=True)
+    beta, eps = 0.95, 1e-6
+    S = torch.zeros(2 * N, B, B, device="cuda")
+    X = torch.zeros_like(S)
+    U = torch.zeros(N, B, B, device="cuda")
+    nf = torch.ones(2 * N, dtype=torch.int32, device="cuda")
+    L64, R64 = np.zeros((N, B, B)), np.zeros((N, B, B))
+    for t in range(warm):
+        G = workloads.gradient_stack(N, B, 3000 + t)
+        dash.accumulate_factors(_to_gpu(G), S[:N], S[N:], beta)
+        L64, R64 = oshampoo.accumulate_factors(G, L64, R64, beta)
+    G = workloads.gradient_stack(N, B, 3000 + warm)
+    dash.step(_to_gpu(G), S, X, U, beta=beta, eps=eps, p=4, iters=12, nonfinite_out=nf)
+    ref = oshampoo.step(G, L64, R64, beta=beta, eps=eps, p=4)
+    torch.cuda.synchronize()
+    eS = rel_frobenius_error(S.cpu().numpy(), np.concatenate([ref["L"], ref["R"]])).max()
+    eX = rel_frobenius_error(X.cpu().numpy(), np.concatenate([ref["X_L"], ref["X_R"]])).max()
+    eU = rel_frobenius_error(U.cpu().numpy(), ref["U"]).max()
+    print(f"   factors {eS:.2e} roots {eX:.2e} update {eU:.2e}", flush=True)
+    assert eS < 1e-5
+    assert eX < 1e-4
+    assert eU < 1e-4
+    assert np.all(nf.cpu().numpy() == 0)
+
+    # non-refresh step (cached roots, Section 4.1): factors move on, X untouched, U uses old X
+    X_before = X.clone()
+    G2 = workloads.gradient_stack(N, B, 3900)
+    dash.step(_to_gpu(G2), S, X, U, beta=beta, eps=eps, p=4, iters=12, refresh=False)
+    L2, R2 = oshampoo.accumulate_factors(G2, ref["L"], ref["R"], beta)
+    assert torch.equal(X, X_before)
+    assert rel_frobenius_error(S.cpu().numpy(), np.concatenate([L2, R2])).max() < 1e-5
+    U_ref = oshampoo.precondition(ref["X_L"], G2, ref["X_R"])
+    assert rel_frobenius_error(U.cpu().numpy(), U_ref).max() < 1e-4
+
+
+def test_step_with_grafting_and_chunked_workspace(dash):
+    import torch
+    N, B = 5, 128
+    # scalar parameters cross the C ABI as float: the oracle gets the same rounded values
+    beta, eps, lr, beta_g, eps_g = 0.95, 1e-6, 1e-3, float(np.float32(0.999)), float(np.float32(1e-8))
+    S = torch.zeros(2 * N, B, B, device="cuda")
+    L64, R64 = np.zeros((N, B, B)), np.zeros((N, B, B))
+    for t in range(5):
+        G = workloads.gradient_stack(N, B, 3100 + t)
+        dash.accumulate_factors(_to_gpu(G), S[:N], S[N:], beta)
+        L64, R64 = oshampoo.accumulate_factors(G, L64, R64, beta)
+    G = workloads.gradient_stack(N, B, 3200)
+    theta0 = workloads.gradient_stack(N, B, 3300, std=1.0)
+    acc0 = (workloads.gradient_stack(N, B, 3400, std=1e-2) ** 2).astype(np.float32)
+    X = torch.zeros_like(S)
+    U = torch.zeros(N, B, B, device="cuda")
+    theta, acc = _to_gpu(theta0), _to_gpu(acc0)
+    S2, X2, U2, theta2, acc2 = S.clone(), X.clone(), U.clone(), theta.clone(), acc.clone()
+    dash.step(_to_gpu(G), S, X, U, beta=beta, eps=eps, p=4, iters=12, graft_acc=acc, theta=theta,
+              beta_g=beta_g, eps_g=eps_g, lr=lr)
+    ref = oshampoo.step(G, L64, R64, beta=beta, eps=eps, p=4,
+                        graft=dict(Acc=acc0, beta_g=beta_g, eps_g=eps_g), theta=theta0, lr=lr)
+    assert rel_frobenius_error(acc.cpu().numpy(), ref["Acc"]).max() < 1e-6
+    assert rel_frobenius_error(U.cpu().numpy(), ref["U"]).max() < 1e-4
+    # theta moved by lr * s * U: compare the movement, not theta itself
+    moved = theta0.astype(np.float64) - theta.cpu().numpy().astype(np.float64)
+    assert rel_frobenius_error(moved, lr * ref["s"][:, None, None] * ref["U"]).max() < 1e-3
+    # by construction ||s U||_F = ||P||_F per block
+    P = G.astype(np.float64) / (eps_g + np.sqrt(ref["Acc"]))
+    for i in range(N):
+        assert np.linalg.norm(moved[i]) / lr == pytest.approx(np.linalg.norm(P[i]), rel=1e-3)
+
+    # same step through a workspace that holds 3 of the 10 factor blocks: same bits
+    from paper_2602_02016_amd import Dash
+    d2 = Dash(0)
+    d2.step(_to_gpu(G), S2, X2, U2, beta=beta, eps=eps, p=4, iters=12, graft_acc=acc2, theta=theta2,
+            beta_g=beta_g, eps_g=eps_g, lr=lr, workspace_max_bytes=d2.workspace_bytes(3, B))
+    torch.cuda.synchronize()
+    assert torch.equal(X, X2) and torch.equal(U, U2) and torch.equal(theta, theta2) and torch.equal(acc, acc2)
+    d2.close()
+
+
+def test_graft_update_alone(dash):
+    import torch
+    N, B = 3, 256
+    G = workloads.gradient_stack(N, B, 3500)
+    Uh = workloads.gradient_stack(N, B, 3501, std=1.0)
+    acc0 = np.zeros((N, B, B), dtype=np.float32)
+    acc = _to_gpu(acc0)
+    s_out = torch.zeros(N, device="cuda")
+    beta_g, eps_g = float(np.float32(0.999)), float(np.float32(1e-8))   # as the float ABI receives them
+    dash.graft_update(_to_gpu(G), _to_gpu(Uh), acc, theta=None, beta_g=beta_g, eps_g=eps_g, s_out=s_out)
+    Acc_ref, s_ref = oshampoo.adam_graft(G, Uh, acc0, beta_g, eps_g)
+    assert np.allclose(acc.cpu().numpy(), Acc_ref, rtol=1e-6, atol=0)
+    assert np.allclose(s_out.cpu().numpy(), s_ref, rtol=1e-5)
+
+
+def test_step_chebyshev(dash):
+    """The step with the Chebyshev root: compared with the oracle step that uses the float64
+    Clenshaw evaluation of the same coefficients."""
+    import torch
+    from oracle import chebyshev as ocheb
+    from paper_2602_02016_amd import chebyshev_fit
+    N, B = 3, 128
+    beta, eps, d = 0.95, 1e-6, 24
+    S = torch.zeros(2 * N, B, B, device="cuda")
+    L64, R64 = np.zeros((N, B, B)), np.zeros((N, B, B))
+    for t in range(6):
+        G = workloads.gradient_stack(N, B, 3600 + t)
+        dash.accumulate_factors(_to_gpu(G), S[:N], S[N:], beta)
+        L64, R64 = oshampoo.accumulate_factors(G, L64, R64, beta)
+    G = workloads.gradient_stack(N, B, 3700)
+    a, b = 0.005, 0.2          # scaled Wishart-EMA spectra sit around 0.02 .. 0.15 at B = 128
+    coef = chebyshev_fit(4, d, a, b)
+    X = torch.zeros_like(S)
+    U = torch.zeros(N, B, B, device="cuda")
+    dash.step(_to_gpu(G), S, X, U, beta=beta, eps=eps, method="chebyshev", p=4, iters=d, cheb_coeffs=coef,
+              cheb_a=a, cheb_b=b)
+    ref = oshampoo.step(G, L64, R64, beta=beta, eps=eps, p=4,
+                        inverse_root=lambda S_, p_, e_: ocheb.inverse_root_chebyshev(S_, p_, np.array(coef), a, b, eps=e_))
+    assert rel_frobenius_error(X.cpu().numpy(), np.concatenate([ref["X_L"], ref["X_R"]])).max() < 1e-4
+    assert rel_frobenius_error(U.cpu().numpy(), ref["U"]).max() < 1e-4
