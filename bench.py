@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-diagonal Shampoo hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic gradient of the workload:
+  accumulate (Algorithm 1 EMA lines) -> inverse 4th roots of all damped factor blocks by
+  Newton-DB after Frobenius scaling (Sections 3.3, 3.4) -> preconditioned update.
+Workload = one 4096 x 4096 linear layer with B = 1024: 16 gradient blocks, 32 stacked
+1024 x 1024 factor blocks, gradient N(0, 1e-2^2), beta = 0.95, eps = 1e-6, p = 4, 10
+Newton-DB updates per call, factors warmed with 20 seeded gradients.
+
+Prints ONE JSON line.  `value` is factor blocks brought through the whole step per second
+(inputs resident in HBM).  `roofline` is for the batched matmul kernel, from HIP events
+recorded around each of its launches on the library's stream during the timed steps.
+`cpu_baseline` times the float64 oracle step on a bounded sample on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+# HBM bytes the matmul kernel moves per block product on this workload, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size
+# (profiles/gemm_f32_cfg2_hbm_traffic.txt); the algorithmic figure is 12*B^2 = 12.58e6.
+MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 16.07e6
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(sample_blocks: int, B: int, beta: float, eps: float, p: int, repeats: int = 3):
+    """Float64 oracle step (eigendecomposition roots) on `sample_blocks` gradient blocks."""
+    import numpy as np
+    import workloads
+    from oracle import shampoo as oshampoo
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    L = np.zeros((sample_blocks, B, B))
+    R = np.zeros((sample_blocks, B, B))
+    for t in range(2):
+        L, R = oshampoo.accumulate_factors(workloads.gradient_stack(sample_blocks, B, 9000 + t), L, R, beta)
+    G = workloads.gradient_stack(sample_blocks, B, 9002)
+    t0 = time.perf_counter()
+    for _ in range(repeats):
+        oshampoo.step(G, L, R, beta=beta, eps=eps, p=p)
+    dt = (time.perf_counter() - t0) / repeats
+    return dict(value=2 * sample_blocks / dt, unit="blocks/s", cores=int(threads), kind="oracle",
+                seconds_per_step=dt,
+                sample=f"{repeats} float64 oracle steps (accumulate, eigh roots of {2 * sample_blocks} factor "
+                       f"blocks, precondition) on {sample_blocks} of the 16 gradient blocks, B={B}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-blocks", type=int, default=16)
+    ap.add_argument("--cpu-repeats", type=int, default=3)
+    ap.add_argument("--root-only-reps", type=int, default=-1,
+                    help="extra timed calls of the inverse root alone (default steps/2; 0 = none)")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="for rocprofv3 --pmc: one device copy of known size, then three launches of the "
+                         "matmul kernel on the workload's 32-block stack; prints nothing else")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over blocks; see DESIGN.md); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    from paper_2602_02016_amd import Dash
+
+    c = workloads.CFG2
+    B, beta, eps, p, k = c["B"], c["beta"], c["eps"], c["p"], c["ndb_iters"]
+    N = workloads.cfg2_num_blocks()            # 16 gradient blocks -> 32 factor blocks
+    dev = torch.device("cuda", 0)
+    dash = Dash(0)
+
+    if args.pmc_probe:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1)
+        A = torch.randn(2 * N, B, B, device=dev, generator=gen)
+        Bm = torch.randn(2 * N, B, B, device=dev, generator=gen)
+        Cm = torch.empty_like(A)
+        torch.cuda.synchronize()
+        Cm.copy_(A)                             # reference: reads 128 MiB, writes 128 MiB
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dash.gemm_batched(A, Bm, Cm)        # algorithmic: reads 256 MiB, writes 128 MiB
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": "copy of %d bytes then 3 matmul launches" % (A.numel() * 4)}))
+        return
+
+    S = torch.zeros(2 * N, B, B, device=dev)
+    X = torch.empty_like(S)
+    U = torch.empty(N, B, B, device=dev)
+    nf = torch.zeros(2 * N, dtype=torch.int32, device=dev)
+
+    # warm the factors with the seeded gradients of the workload recipe
+    for t in range(c["warm_steps"]):
+        G = torch.from_numpy(workloads.gradient_stack(N, B, c["seed_base"] + t, c["grad_std"])).to(dev)
+        dash.accumulate_factors(G, S[:N], S[N:], beta)
+    torch.cuda.synchronize()
+
+    # gradients of the warm-up and timed steps, resident in HBM before timing starts
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(c["seed_base"] + 1000)
+    total = args.warmup + args.steps
+    grads = [torch.randn(N, B, B, device=dev, generator=gen) * c["grad_std"] for _ in range(min(total, 8))]
+
+    def one_step(i):
+        dash.step(grads[i % len(grads)], S, X, U, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf)
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+
+    dash.reset_stats()
+    dash.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st = dash.get_stats()
+    dash.set_timing(False)
+    assert int(nf.sum().item()) == 0, "non-finite root in the benchmark workload"
+
+    # the inverse roots alone (same stack, same call the step makes), timed the same way
+    reps = args.root_only_reps if args.root_only_reps >= 0 else max(1, args.steps // 2)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(reps):
+        dash.inverse_root(S, X, p=p, iters=k, eps=eps, nonfinite_out=nf)
+    torch.cuda.synchronize()
+    root_ms = (time.perf_counter() - t1) * 1e3 / max(reps, 1)
+
+    ms_per_step = dt * 1e3 / args.steps
+    blocks_per_s = 2 * N * args.steps / dt
+
+    # matmul kernel: algorithmic flops per launch / mean launch duration
+    flop_per_product = 2.0 * B ** 3
+    # dominant kernel = the non-transposed instance (all Newton-DB and precondition products)
+    mm_ms = st["variant_ms"][0]
+    launches = st["variant_launches"][0]
+    achieved_tflops = flop_per_product * st["variant_block_products"][0] / (mm_ms * 1e-3) / 1e12 if mm_ms > 0 else 0.0
+    roofline = dict(bound="mfma", kernel="dash::gemm_f32_kernel<128, false, false>",
+                    achieved=achieved_tflops, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
+                    frac=achieved_tflops / PEAK_FP32_MFMA_TFLOPS,
+                    traffic=MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT * st["variant_block_products"][0] / max(launches, 1),
+                    traffic_note="HBM bytes per mean launch = rocprofv3 FETCH_SIZE+WRITE_SIZE per block product "
+                                 "(measured offline, scaled by a copy kernel) x block products per launch of this run",
+                    algorithmic_bytes=12.0 * B * B * st["variant_block_products"][0] / max(launches, 1),
+                    launches_per_step=launches / args.steps,
+                    mean_launch_ms=mm_ms / max(launches, 1),
+                    matmul_share_of_step=mm_ms / (dt * 1e3))
+
+    # the paper's own matmul count for the root (3k-2 per call, two calls) prices the
+    # inverse root alone: what the headline "blocks/s at B=1024" would be without the
+    # accumulate and precondition products of the step
+    paper_products_root = 2 * (3 * k - 2)
+    exec_products_root = 2 * (3 * k - 3)
+    out = {
+        "metric": "inverse-4th-root blocks/sec at B=1024 (Newton-DB), whole optimizer step",
+        "value": blocks_per_s,
+        "unit": "blocks/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "cfg2: one Shampoo step of a 4096x4096 layer, B=1024, 16 gradient blocks / 32 factor "
+                               "blocks, Newton-DB p=4 with 10 updates per call, Frobenius scaling, beta=0.95, "
+                               "eps=1e-6, factors warmed with 20 seeded gradients",
+                   "N_gradient_blocks": N, "N_factor_blocks": 2 * N, "B": B, "p": p, "ndb_iters": k},
+        "roofline": roofline,
+        "step_mfma_frac_paper_count": (2 * N * paper_products_root + 4 * N) * flop_per_product
+                                      / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+        "step_mfma_frac_executed": (2 * N * exec_products_root + 4 * N) * flop_per_product
+                                   / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+        "inverse_root_only": None if reps == 0 else {"blocks_per_s": 2 * N / (root_ms * 1e-3), "ms": root_ms,
+                              "mfma_frac_paper_count": 2 * N * paper_products_root * flop_per_product
+                              / (root_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+                              "mfma_frac_executed": 2 * N * exec_products_root * flop_per_product
+                              / (root_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(min(args.cpu_sample_blocks, N), B, beta, eps, p, args.cpu_repeats)
+    log(f"step {ms_per_step:.2f} ms, {blocks_per_s:.0f} factor blocks/s, matmul kernel {achieved_tflops:.1f} TFLOP/s "
+        f"({100 * roofline['frac']:.1f}% of fp32 MFMA peak)")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -82,6 +82,11 @@ typedef struct {
     int64_t matmul_launches;   /* kernel launches of the batched matmul kernel          */
     double  matmul_block_products; /* sum over launches of products * blocks in launch  */
     double  matmul_ms;         /* summed event time of those launches (0 if timing off) */
+    /* the same three figures per kernel variant v = 2*transA + transB (0: A B, 1: A B^T,
+       2: A^T B, 3: A^T B^T) */
+    int64_t variant_launches[4];
+    double  variant_block_products[4];
+    double  variant_ms[4];
 } dash_stats;
 dash_status dash_reset_stats(dash_ctx* ctx);
 dash_status dash_set_timing(dash_ctx* ctx, int on);

@@ -33,7 +33,9 @@ class DashError(RuntimeError):
 
 class _Stats(C.Structure):
     _fields_ = [("matmul_products", C.c_int64), ("matmul_launches", C.c_int64),
-                ("matmul_block_products", C.c_double), ("matmul_ms", C.c_double)]
+                ("matmul_block_products", C.c_double), ("matmul_ms", C.c_double),
+                ("variant_launches", C.c_int64 * 4), ("variant_block_products", C.c_double * 4),
+                ("variant_ms", C.c_double * 4)]
 
 
 class _StepArgs(C.Structure):
@@ -190,7 +192,9 @@ class Dash:
         s = _Stats()
         self._check(self.lib.dash_get_stats(self.h, C.byref(s)))
         return dict(matmul_products=s.matmul_products, matmul_launches=s.matmul_launches,
-                    matmul_block_products=s.matmul_block_products, matmul_ms=s.matmul_ms)
+                    matmul_block_products=s.matmul_block_products, matmul_ms=s.matmul_ms,
+                    variant_launches=list(s.variant_launches),
+                    variant_block_products=list(s.variant_block_products), variant_ms=list(s.variant_ms))
 
     # ---- the calls of dash.h -------------------------------------------------------------
     def gemm_batched(self, A, Bm, C_out, D=None, transA=False, transB=False, alpha=1.0, beta=0.0, gamma=0.0,

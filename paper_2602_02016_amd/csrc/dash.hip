@@ -27,8 +27,12 @@ struct dash_ctx {
     double mm_block_products = 0.0;
     bool timing = false;
     std::vector<hipEvent_t> ev_pool;   // start/stop pairs
+    std::vector<int> ev_variant;       // kernel variant of each pair
     size_t ev_used = 0;
     double ms_done = 0.0;
+    int64_t var_launches[4] = {0, 0, 0, 0};
+    double var_block_products[4] = {0, 0, 0, 0};
+    double var_ms[4] = {0, 0, 0, 0};
 };
 
 namespace {
@@ -80,6 +84,7 @@ size_t per_block_bytes(int B, dash_method m, dash_precision prec) {
 dash_status run_gemm(dash_ctx* c, const GemmLaunch& g) {
     if (g.nblocks <= 0) return DASH_OK;
     hipEvent_t e0 = nullptr, e1 = nullptr;
+    const int variant = 2 * (g.prob[0].transA ? 1 : 0) + (g.prob[0].transB ? 1 : 0);
     if (c->timing) {
         if (c->ev_used + 2 > c->ev_pool.size()) {
             for (int i = 0; i < 2; ++i) {
@@ -90,6 +95,8 @@ dash_status run_gemm(dash_ctx* c, const GemmLaunch& g) {
         }
         e0 = c->ev_pool[c->ev_used];
         e1 = c->ev_pool[c->ev_used + 1];
+        if (c->ev_variant.size() < c->ev_pool.size() / 2) c->ev_variant.resize(c->ev_pool.size() / 2);
+        c->ev_variant[c->ev_used / 2] = variant;
         c->ev_used += 2;
         HIP_TRY(c, hipEventRecord(e0, c->stream));
     }
@@ -98,6 +105,8 @@ dash_status run_gemm(dash_ctx* c, const GemmLaunch& g) {
     c->mm_products += g.nprob;
     c->mm_launches += 1;
     c->mm_block_products += (double)g.nprob * (double)g.nblocks;
+    c->var_launches[variant] += 1;
+    c->var_block_products[variant] += (double)g.nprob * (double)g.nblocks;
     return DASH_OK;
 }
 
@@ -108,6 +117,7 @@ dash_status collect_events(dash_ctx* c) {
         float ms = 0.f;
         HIP_TRY(c, hipEventElapsedTime(&ms, c->ev_pool[i], c->ev_pool[i + 1]));
         c->ms_done += ms;
+        c->var_ms[c->ev_variant[i / 2]] += ms;
     }
     c->ev_used = 0;
     return DASH_OK;
@@ -308,6 +318,7 @@ dash_status dash_reset_stats(dash_ctx* c) {
     c->mm_products = c->mm_launches = 0;
     c->mm_block_products = 0.0;
     c->ms_done = 0.0;
+    for (int v = 0; v < 4; ++v) { c->var_launches[v] = 0; c->var_block_products[v] = 0.0; c->var_ms[v] = 0.0; }
     return DASH_OK;
 }
 
@@ -325,6 +336,11 @@ dash_status dash_get_stats(dash_ctx* c, dash_stats* out) {
     out->matmul_launches = c->mm_launches;
     out->matmul_block_products = c->mm_block_products;
     out->matmul_ms = c->ms_done;
+    for (int v = 0; v < 4; ++v) {
+        out->variant_launches[v] = c->var_launches[v];
+        out->variant_block_products[v] = c->var_block_products[v];
+        out->variant_ms[v] = c->var_ms[v];
+    }
     return DASH_OK;
 }
 
