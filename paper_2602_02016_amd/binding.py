@@ -200,6 +200,10 @@ class Dash:
     def gemm_batched(self, A, Bm, C_out, D=None, transA=False, transB=False, alpha=1.0, beta=0.0, gamma=0.0,
                      precision="fp32"):
         n, b = A.shape[0], A.shape[1]
+        if _enum(_PRECISIONS, precision) == BF16_ACC32 and n > 0:
+            need = n * b * b * 4                      # two bf16 operand stacks
+            if self._ws is None or self._ws.numel() < need:
+                self.set_workspace_bytes(need)
         self._check(self.lib.dash_gemm_batched(
             self.h, int(transA), int(transB), self._stack(A, "A"), self._stack(Bm, "B", n, b),
             self._stack(D, "D", n, b) if D is not None else C.c_void_p(None), self._stack(C_out, "C", n, b),

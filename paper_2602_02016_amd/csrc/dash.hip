@@ -37,6 +37,8 @@ struct dash_ctx {
 
 namespace {
 
+typedef unsigned short bf16_t;   // host side only ever moves bf16 buffers around
+
 constexpr size_t SCALARS_PER_BLOCK = 512;   // bytes of per-block scalars (slab partials, s, 1/s, s^(-1/p))
 constexpr size_t WS_ALIGN = 256;
 
@@ -71,13 +73,22 @@ bool overlap(const void* a, const void* b, size_t bytes) {
     return x < y + bytes && y < x + bytes;
 }
 
-int buffers_needed(dash_method m) { return m == DASH_NEWTON_DB ? 5 : 3; }
+// fp32 and bf16 [B][B] buffers per block each method keeps in the workspace:
+//   fp32 path: Newton-DB 5 fp32 (Y, Z ping-pong, E), Clenshaw 3 fp32 (S and two rotating B_k);
+//   bf16 path: Newton-DB 5 bf16 (same roles) + 1 fp32 (the Y handed from call 1 to call 2),
+//              Clenshaw 2 fp32 (rotating B_k) + 3 bf16 (S and the operand copies of B_k).
+int f32_buffers(dash_method m, dash_precision prec) {
+    if (prec == DASH_BF16_ACC32) return m == DASH_NEWTON_DB ? 1 : 2;
+    return m == DASH_NEWTON_DB ? 5 : 3;
+}
+int bf16_buffers(dash_method m, dash_precision prec) {
+    if (prec != DASH_BF16_ACC32) return 0;
+    return m == DASH_NEWTON_DB ? 5 : 3;
+}
 
 size_t per_block_bytes(int B, dash_method m, dash_precision prec) {
     size_t mat = (size_t)B * B * sizeof(float);
-    size_t n = (size_t)buffers_needed(m) * mat + SCALARS_PER_BLOCK;
-    if (prec == DASH_BF16_ACC32) n += (size_t)buffers_needed(m) * mat / 2;   // bf16 operand copies
-    return n;
+    return (size_t)f32_buffers(m, prec) * mat + (size_t)bf16_buffers(m, prec) * (mat / 2) + SCALARS_PER_BLOCK;
 }
 
 // ---- matmul launch with statistics / optional event timing ------------------------------
@@ -126,22 +137,31 @@ dash_status collect_events(dash_ctx* c) {
 GemmProblem problem(const float* A, const float* B, const float* D, float* C, const float* mult, float alpha,
                     float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = A; p.B = B; p.D = D; p.C = C; p.mult = mult;
+    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
 
-dash_status gemm1(dash_ctx* c, const GemmProblem& p, int64_t n, int B, int32_t* nonfinite = nullptr) {
+// bf16 operands Ah, Bh; result to C (fp32, may be null) and Ch (bf16, may be null)
+GemmProblem problem_h(const bf16_t* Ah, const bf16_t* Bh, const float* D, float* C, bf16_t* Ch, const float* mult,
+                      float alpha, float beta, float gamma, int ta = 0, int tb = 0) {
+    GemmProblem p;
+    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.mult = mult;
+    p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
+    return p;
+}
+
+dash_status gemm1(dash_ctx* c, const GemmProblem& p, int64_t n, int B, int32_t* nonfinite = nullptr, int bf16 = 0) {
     GemmLaunch g;
     memset(&g, 0, sizeof(g));
-    g.prob[0] = p; g.prob[1] = p; g.nprob = 1; g.B = B; g.nblocks = n; g.nonfinite = nonfinite; g.bf16 = 0;
+    g.prob[0] = p; g.prob[1] = p; g.nprob = 1; g.B = B; g.nblocks = n; g.nonfinite = nonfinite; g.bf16 = bf16;
     return run_gemm(c, g);
 }
 
-dash_status gemm2(dash_ctx* c, const GemmProblem& p0, const GemmProblem& p1, int64_t n, int B) {
+dash_status gemm2(dash_ctx* c, const GemmProblem& p0, const GemmProblem& p1, int64_t n, int B, int bf16 = 0) {
     GemmLaunch g;
     memset(&g, 0, sizeof(g));
-    g.prob[0] = p0; g.prob[1] = p1; g.nprob = 2; g.B = B; g.nblocks = n; g.nonfinite = nullptr; g.bf16 = 0;
+    g.prob[0] = p0; g.prob[1] = p1; g.nprob = 2; g.B = B; g.nblocks = n; g.nonfinite = nullptr; g.bf16 = bf16;
     return run_gemm(c, g);
 }
 
@@ -177,11 +197,11 @@ dash_status ndb_call(dash_ctx* c, float* buf[5], int mi, int64_t n, int B, int i
     if (m_needs_init) {
         // first call: M = (A + eps I)/s -> buf[y]; E_1 = 1.5 I - 0.5 M -> buf[z]
         y = grab(); z = grab();
-        HIP_TRY(c, launch_scale_shift(A_in, n, B, eps, inv_s, 1.f, 0.f, buf[y], -0.5f, 1.5f, buf[z], nullptr, st));
+        HIP_TRY(c, launch_scale_shift(A_in, n, B, eps, inv_s, 1.f, 0.f, buf[y], -0.5f, 1.5f, buf[z], nullptr, nullptr, nullptr, st));
     } else {
         // chained call: M is buf[mi] as it stands; E_1 = 1.5 I - 0.5 M
         used[mi] = true; y = mi; z = grab();
-        HIP_TRY(c, launch_scale_shift(buf[y], n, B, 0.f, nullptr, -0.5f, 1.5f, buf[z], 0.f, 0.f, nullptr, nullptr, st));
+        HIP_TRY(c, launch_scale_shift(buf[y], n, B, 0.f, nullptr, -0.5f, 1.5f, buf[z], 0.f, 0.f, nullptr, nullptr, nullptr, nullptr, st));
     }
     if (iters == 1) {
         if (keepY) {
@@ -190,7 +210,7 @@ dash_status ndb_call(dash_ctx* c, float* buf[5], int mi, int64_t n, int B, int i
             *out_idx = y1;
         } else if (final_out) {
             // X = unscale * Z_1: no product at all
-            HIP_TRY(c, launch_scale_shift(buf[z], n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nonfinite, st));
+            HIP_TRY(c, launch_scale_shift(buf[z], n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nullptr, nullptr, nonfinite, st));
         } else {
             *out_idx = z;
         }
@@ -227,6 +247,108 @@ dash_status ndb_call(dash_ctx* c, float* buf[5], int mi, int64_t n, int B, int i
     return DASH_OK;
 }
 
+// ---- Newton-DB with bf16 operands (Appendix A.3 recipe applied to Section 3.3) ------------
+// Every iterate is consumed only as a matmul operand, i.e. only after rounding to bf16, so
+// the iterates live in the workspace as the bf16 values the next product reads; the fp32
+// value is kept where something else reads it: the Y that call 1 hands to call 2 (its
+// closed-form E_1 is formed from the fp32 Y) and the final Z (the result).  Accumulation
+// and every epilogue (1.5 I - 0.5 Z Y, un-scaling) are fp32.
+// hb: five bf16 buffers; fy: one fp32 buffer.  mi: index in hb of the bf16 copy of M when
+// the call is chained (then fy holds M in fp32).
+dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], float* fy, int mi, int64_t n, int B, int iters, bool keepY,
+                          bool m_needs_init, const float* A_in, float eps, const float* inv_s, float* final_out,
+                          const float* unscale, int32_t* nonfinite, int* out_idx) {
+    hipStream_t st = c->stream;
+    bool used[5] = {false, false, false, false, false};
+    auto grab = [&]() { for (int i = 0; i < 5; ++i) if (!used[i]) { used[i] = true; return i; } return -1; };
+    int y, z;
+    if (m_needs_init) {
+        y = grab(); z = grab();
+        // M = (A + eps I)/s -> bf16 hb[y]; E_1 = 1.5 I - 0.5 M (fp32) -> bf16 hb[z]; when E_1 itself is
+        // the result (iters == 1, p == 2) its fp32 value goes to fy
+        HIP_TRY(c, launch_scale_shift(A_in, n, B, eps, inv_s, 1.f, 0.f, nullptr, -0.5f, 1.5f,
+                                      (iters == 1 && !keepY) ? fy : nullptr, hb[y], hb[z], nullptr, st));
+    } else {
+        used[mi] = true; y = mi; z = grab();
+        if (iters == 1 && !keepY && final_out) {
+            // X = unscale * (1.5 I - 0.5 Y): two elementwise passes, no product
+            HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, nullptr, -0.5f, 1.5f, final_out, 0.f, 0.f, nullptr, nullptr,
+                                          nullptr, nullptr, st));
+            HIP_TRY(c, launch_scale_shift(final_out, n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr,
+                                          nullptr, nullptr, nonfinite, st));
+            return DASH_OK;
+        }
+        HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, nullptr, -0.5f, 1.5f, nullptr, 0.f, 0.f, nullptr, hb[z], nullptr,
+                                      nullptr, st));
+    }
+    if (iters == 1) {
+        if (keepY) {
+            int y1 = grab();
+            DASH_TRY(gemm1(c, problem_h(hb[y], hb[z], nullptr, fy, hb[y1], nullptr, 1.f, 0.f, 0.f), n, B, nullptr, 1));
+            *out_idx = y1;
+        } else if (final_out) {
+            HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nullptr,
+                                          nullptr, nonfinite, st));
+        } else {
+            *out_idx = z;
+        }
+        return DASH_OK;
+    }
+    {
+        int y1 = grab();
+        DASH_TRY(gemm1(c, problem_h(hb[y], hb[z], nullptr, nullptr, hb[y1], nullptr, 1.f, 0.f, 0.f), n, B, nullptr, 1));
+        used[y] = false; y = y1;
+    }
+    for (int it = 2; it <= iters; ++it) {
+        const bool last = it == iters;
+        int e = grab();
+        DASH_TRY(gemm1(c, problem_h(hb[z], hb[y], nullptr, nullptr, hb[e], nullptr, -0.5f, 0.f, 1.5f), n, B, nullptr, 1));
+        if (!last) {
+            int y2 = grab(), z2 = grab();
+            DASH_TRY(gemm2(c, problem_h(hb[y], hb[e], nullptr, nullptr, hb[y2], nullptr, 1.f, 0.f, 0.f),
+                           problem_h(hb[e], hb[z], nullptr, nullptr, hb[z2], nullptr, 1.f, 0.f, 0.f), n, B, 1));
+            used[y] = used[z] = used[e] = false;
+            y = y2; z = z2;
+        } else if (keepY) {
+            int y2 = grab();
+            DASH_TRY(gemm1(c, problem_h(hb[y], hb[e], nullptr, fy, hb[y2], nullptr, 1.f, 0.f, 0.f), n, B, nullptr, 1));
+            *out_idx = y2;
+        } else if (final_out) {
+            DASH_TRY(gemm1(c, problem_h(hb[e], hb[z], nullptr, final_out, nullptr, unscale, 1.f, 0.f, 0.f), n, B,
+                           nonfinite, 1));
+        } else {
+            int z2 = grab();
+            DASH_TRY(gemm1(c, problem_h(hb[e], hb[z], nullptr, nullptr, hb[z2], nullptr, 1.f, 0.f, 0.f), n, B, nullptr, 1));
+            *out_idx = z2;
+        }
+    }
+    return DASH_OK;
+}
+
+// ---- Clenshaw with bf16 operands (paper Appendix A.3: B_k kept in fp32, S and the operand
+// copy of B_{k+1} in half precision, fp32 accumulation) ----------------------------------------
+dash_status clenshaw_chunk_bf16(dash_ctx* c, float* fb[2], bf16_t* hb[3], const float* A, float* X, int64_t n, int B,
+                                int d, const double* cf, double ca, double cb, float eps, const float* inv_s,
+                                const float* unscale, int32_t* nonfinite) {
+    hipStream_t st = c->stream;
+    bf16_t* Sh = hb[0];
+    float* b1 = fb[0]; bf16_t* h1 = hb[1];   // B_{k+1}: fp32 master and bf16 operand copy
+    float* b2 = fb[1]; bf16_t* h2 = hb[2];   // B_{k+2}
+    const float m1 = (float)(2.0 / (cb - ca)), m0 = (float)(-(ca + cb) / (cb - ca));
+    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, m1, m0, nullptr, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
+                                  Sh, h1, nullptr, st));
+    if (d == 2)
+        return gemm1(c, problem_h(Sh, h1, nullptr, X, nullptr, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B,
+                     nonfinite, 1);
+    DASH_TRY(gemm1(c, problem_h(Sh, h1, nullptr, b2, h2, nullptr, 2.f, 0.f, (float)(cf[d - 2] - cf[d])), n, B, nullptr, 1));
+    { float* t = b1; b1 = b2; b2 = t; bf16_t* u = h1; h1 = h2; h2 = u; }
+    for (int k = d - 3; k >= 1; --k) {
+        DASH_TRY(gemm1(c, problem_h(Sh, h1, b2, b2, h2, nullptr, 2.f, -1.f, (float)cf[k]), n, B, nullptr, 1));
+        float* t = b1; b1 = b2; b2 = t; bf16_t* u = h1; h1 = h2; h2 = u;
+    }
+    return gemm1(c, problem_h(Sh, h1, b2, X, nullptr, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite, 1);
+}
+
 // ---- Clenshaw on one chunk (paper Appendix A.2, reduced form, d-1 products) --------------
 dash_status clenshaw_chunk(dash_ctx* c, float* buf[3], const float* A, float* X, int64_t n, int B, int d,
                            const double* cf, double ca, double cb, float eps, const float* inv_s,
@@ -239,7 +361,7 @@ dash_status clenshaw_chunk(dash_ctx* c, float* buf[3], const float* A, float* X,
     // S = (2 A_s - (a+b) I)/(b-a);  B_{d-1} = 2 c_d S + c_{d-1} I.  B_d = c_d I is never stored:
     // it only enters B_{d-2} through "- B_d + c_{d-2} I" = (c_{d-2} - c_d) I.
     HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, m1, m0, S, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
-                                  nullptr, st));
+                                  nullptr, nullptr, nullptr, st));
     if (d == 2) {
         // result = S B_1 - B_2 + c_0 I with B_2 = c_2 I
         return gemm1(c, problem(S, b1, nullptr, X, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B, nonfinite);
@@ -352,12 +474,29 @@ dash_status dash_gemm_batched(dash_ctx* c, int transA, int transB, const float* 
     if (N == 0) return DASH_OK;
     if (!A || !Bm || !C) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     if (!D && beta != 0.f) return fail(c, DASH_ERR_INVALID_ARG, "beta != 0 needs D");
-    if (precision != DASH_FP32) return fail(c, DASH_ERR_UNSUPPORTED, "bf16 operands not built yet");
+    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32) return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
     const size_t bytes = (size_t)N * B * B * sizeof(float);
     if (overlap(C, A, bytes) || overlap(C, Bm, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "C overlaps an operand");
     if (D && D != C && overlap(C, D, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "D must equal C or be disjoint from it");
     HIP_TRY(c, hipSetDevice(c->device));
-    return gemm1(c, problem(A, Bm, D, C, nullptr, alpha, beta, gamma, transA ? 1 : 0, transB ? 1 : 0), N, B);
+    if (precision == DASH_FP32)
+        return gemm1(c, problem(A, Bm, D, C, nullptr, alpha, beta, gamma, transA ? 1 : 0, transB ? 1 : 0), N, B);
+    // bf16 operands: round both operand stacks into the workspace (two bf16 stacks per chunk), then multiply
+    const size_t mat = (size_t)B * B, per = 2 * mat * sizeof(bf16_t);
+    if (!c->ws || c->ws_bytes < per) return fail(c, DASH_ERR_WORKSPACE, "workspace holds %zu bytes, one block needs %zu", c->ws_bytes, per);
+    int64_t chunk = (int64_t)(c->ws_bytes / per);
+    if (chunk > N) chunk = N;
+    for (int64_t b0 = 0; b0 < N; b0 += chunk) {
+        const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
+        const size_t o = (size_t)b0 * mat;
+        bf16_t* Ah = (bf16_t*)c->ws;
+        bf16_t* Bh = Ah + (size_t)nb * mat;
+        HIP_TRY(c, launch_scale_shift(A + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Ah, nullptr, nullptr, c->stream));
+        HIP_TRY(c, launch_scale_shift(Bm + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Bh, nullptr, nullptr, c->stream));
+        DASH_TRY(gemm1(c, problem_h(Ah, Bh, D ? D + o : nullptr, C + o, nullptr, nullptr, alpha, beta, gamma,
+                                    transA ? 1 : 0, transB ? 1 : 0), nb, B, nullptr, 1));
+    }
+    return DASH_OK;
 }
 
 dash_status dash_accumulate_factors(dash_ctx* c, const float* G, float* L, float* R, int64_t N, int B, float beta,
@@ -438,7 +577,6 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     if (N == 0) return DASH_OK;
     if (!A || !X) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     if (overlap(A, X, (size_t)N * B * B * sizeof(float))) return fail(c, DASH_ERR_INVALID_ARG, "X overlaps A");
-    if (precision != DASH_FP32) return fail(c, DASH_ERR_UNSUPPORTED, "bf16 operands not built yet");
     HIP_TRY(c, hipSetDevice(c->device));
 
     const size_t per = per_block_bytes(B, method, precision);
@@ -450,7 +588,8 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
 
     const size_t mat = (size_t)B * B;
     const int P = norm_slabs(B);
-    const int nbuf = buffers_needed(method);
+    const int nbuf = f32_buffers(method, precision), nhbuf = bf16_buffers(method, precision);
+    const bool lowp = precision == DASH_BF16_ACC32;
     hipStream_t st = c->stream;
 
     for (int64_t b0 = 0; b0 < N; b0 += chunk) {
@@ -461,8 +600,10 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         float* inv_s = (float*)cv.take((size_t)nb * sizeof(float));
         float* unscale = (float*)cv.take((size_t)nb * sizeof(float));
         float* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+        bf16_t* hbuf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
         for (int i = 0; i < nbuf; ++i) buf[i] = (float*)cv.take((size_t)nb * mat * sizeof(float));
-        if (!partial || !s || !inv_s || !unscale || !buf[nbuf - 1])
+        for (int i = 0; i < nhbuf; ++i) hbuf[i] = (bf16_t*)cv.take((size_t)nb * mat * sizeof(bf16_t));
+        if (!partial || !s || !inv_s || !unscale || !buf[nbuf - 1] || (nhbuf && !hbuf[nhbuf - 1]))
             return fail(c, DASH_ERR_WORKSPACE, "internal: workspace carve failed");
 
         const float* Ac = A + (size_t)b0 * mat;
@@ -474,7 +615,18 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         if (scaling != DASH_SCALE_NONE) HIP_TRY(c, launch_norm_partials(Ac, nb, B, eps, (int)scaling, partial, st));
         HIP_TRY(c, launch_finalize_scale(partial, nb, P, (int)scaling, p, scale_out ? scale_out + b0 : s, inv_s, unscale, st));
 
-        if (method == DASH_NEWTON_DB) {
+        if (lowp && method == DASH_NEWTON_DB) {
+            int idx = -1;
+            if (p == 2) {
+                DASH_TRY(ndb_call_bf16(c, hbuf, buf[0], -1, nb, B, iters, false, true, Ac, eps, inv_s, Xc, unscale, nf, &idx));
+            } else {
+                DASH_TRY(ndb_call_bf16(c, hbuf, buf[0], -1, nb, B, iters, true, true, Ac, eps, inv_s, nullptr, nullptr, nullptr, &idx));
+                int idx2 = -1;
+                DASH_TRY(ndb_call_bf16(c, hbuf, buf[0], idx, nb, B, iters, false, false, nullptr, 0.f, nullptr, Xc, unscale, nf, &idx2));
+            }
+        } else if (lowp) {
+            DASH_TRY(clenshaw_chunk_bf16(c, buf, hbuf, Ac, Xc, nb, B, iters, cheb_coeffs, cheb_a, cheb_b, eps, inv_s, unscale, nf));
+        } else if (method == DASH_NEWTON_DB) {
             int idx = -1;
             if (p == 2) {
                 DASH_TRY(ndb_call(c, buf, -1, nb, B, iters, false, true, Ac, eps, inv_s, Xc, unscale, nf, &idx));

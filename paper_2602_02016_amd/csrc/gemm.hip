@@ -137,8 +137,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void gemm_f32_kernel(GemmLaunch g) {
 
     const GemmProblem& P = g.prob[pi];
     const size_t boff = (size_t)blk * B * B;
-    const float* __restrict__ Ab = P.A + boff;
-    const float* __restrict__ Bb = P.B + boff;
+    const float* __restrict__ Ab = static_cast<const float*>(P.A) + boff;
+    const float* __restrict__ Bb = static_cast<const float*>(P.B) + boff;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
@@ -237,7 +237,7 @@ hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
     if (g.nprob < 1 || g.nprob > 2 || g.B <= 0 || g.B % 64) return hipErrorInvalidValue;
     if (g.nprob == 2 && (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
         return hipErrorInvalidValue;
-    if (g.bf16) return hipErrorNotSupported;
+    if (g.bf16) return launch_gemm_bf16(g, stream);
     // 128-wide tiles when they still give the chip enough workgroups, else 64-wide
     const bool big = (g.B % 128 == 0) && (g.nblocks * g.nprob * (int64_t)(g.B / 128) * (g.B / 128) >= 256);
     return big ? launch_tile<128>(g, stream) : launch_tile<64>(g, stream);

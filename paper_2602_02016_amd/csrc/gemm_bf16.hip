@@ -1,0 +1,261 @@
+// Batched B x B x B matmul with bf16 operands and fp32 accumulation, for gfx950.
+//
+// Mixed-precision form of the same product as gemm.hip (paper Appendix A.3: iterates are
+// kept in fp32, the operands of each matmul are rounded to half precision, accumulation
+// is fp32 -- here with bf16 instead of fp16).  Operands arrive already rounded: the
+// epilogue of the product (or the elementwise kernel) that produced an iterate writes a
+// bf16 copy next to, or instead of, the fp32 value, so no separate cast pass exists.
+//     acc = op(A_b) op(B_b)                       (v_mfma_f32_32x32x16_bf16)
+//     v   = mult_b * (alpha * acc + beta * D_b + gamma * I)     (fp32)
+//     C_b = v (fp32, optional),  Ch_b = bf16(v) (optional)
+//
+// Same decomposition as the fp32 kernel: 256 threads, 2 x 2 wavefronts, TILE x TILE per
+// workgroup, K slabs of 32 double-buffered in LDS, next slab prefetched into registers,
+// XCD-aware 1-D grid.  An MFMA operand wants per lane eight consecutive k of one row:
+//   KC  [row][k]  k contiguous in global memory: rows of 32 bf16 (pitch 40), one 16-byte
+//       LDS read per MFMA operand;
+//   RC2 [k/2][row][2]  row contiguous in global memory: a thread loads the same eight
+//       columns of two consecutive k-lines, interleaves them into dwords {k even, k odd}
+//       and stores 32 contiguous bytes; an MFMA operand is four 4-byte reads at
+//       consecutive addresses across lanes (pitch TILE+8 dwords).
+#include "kernels.h"
+
+namespace dash {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8h __attribute__((ext_vector_type(8)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int HBK = 32;          // K slab (bf16 elements)
+constexpr int HKC_PITCH = 40;    // bf16 per row in the KC layout (32 + 8 pad) = 80 bytes
+constexpr int HNT = 256;
+constexpr int HNUM_XCD = 8;
+
+// 16-byte vectors a thread carries per operand slab (the RC2 path needs two per unit)
+template <int TILE>
+struct HRegs {
+    static constexpr int NV = TILE * 4 / HNT < 2 ? 2 : TILE * 4 / HNT;
+};
+
+template <int TILE>
+struct HLds {
+    static constexpr int RC_PITCH = TILE + 8;                 // dwords per k-pair line
+    static constexpr int KC_BYTES = TILE * HKC_PITCH * 2;
+    static constexpr int RC_BYTES = (HBK / 2) * RC_PITCH * 4;
+    static constexpr int BYTES = KC_BYTES > RC_BYTES ? KC_BYTES : RC_BYTES;
+};
+
+// A slab is TILE*32 bf16 = TILE*4 16-byte vectors; a thread carries TILE*4/256 of them.
+template <int TILE, bool KC>
+__device__ __forceinline__ void hload_slab(const __bf16* __restrict__ base, int ld, int row0, int k0,
+                                           v4u (&r)[HRegs<TILE>::NV]) {
+    constexpr int NV = TILE * 4 / HNT;
+    const int t = threadIdx.x;
+    if (KC) {           // element (row, k) at base[row*ld + k]: 4 vectors per row
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int f = t + HNT * u;
+            const int row = f >> 2, kq = f & 3;
+            r[u] = *reinterpret_cast<const v4u*>(base + (size_t)(row0 + row) * ld + k0 + 8 * kq);
+        }
+    } else {            // element (row, k) at base[k*ld + row]: unit = 2 k-lines x 8 rows
+        constexpr int GPL = TILE / 8;       // 8-row groups per k-line
+        constexpr int UNITS = (HBK / 2) * GPL;
+#pragma unroll
+        for (int u = 0; u < (UNITS + HNT - 1) / HNT; ++u) {
+            const int f = t + HNT * u;
+            if (f < UNITS) {
+                const int q = f / GPL, rg = f % GPL;
+                const __bf16* p = base + (size_t)(k0 + 2 * q) * ld + row0 + 8 * rg;
+                r[2 * u] = *reinterpret_cast<const v4u*>(p);
+                r[2 * u + 1] = *reinterpret_cast<const v4u*>(p + ld);
+            }
+        }
+    }
+}
+
+template <int TILE, bool KC>
+__device__ __forceinline__ void hstore_slab(char* __restrict__ s, const v4u (&r)[HRegs<TILE>::NV]) {
+    constexpr int NV = TILE * 4 / HNT;
+    const int t = threadIdx.x;
+    if (KC) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int f = t + HNT * u;
+            const int row = f >> 2, kq = f & 3;
+            *reinterpret_cast<v4u*>(s + (row * HKC_PITCH + 8 * kq) * 2) = r[u];
+        }
+    } else {
+        constexpr int GPL = TILE / 8;
+        constexpr int UNITS = (HBK / 2) * GPL;
+        constexpr int P = HLds<TILE>::RC_PITCH;
+#pragma unroll
+        for (int u = 0; u < (UNITS + HNT - 1) / HNT; ++u) {
+            const int f = t + HNT * u;
+            if (f >= UNITS) continue;
+            const int q = f / GPL, rg = f % GPL;
+            const v4u a = r[2 * u], b = r[2 * u + 1];   // k even line, k odd line; each dword = rows (2i, 2i+1)
+            v4u lo, hi;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                lo[2 * i] = (a[i] & 0xffffu) | (b[i] << 16);
+                lo[2 * i + 1] = (a[i] >> 16) | (b[i] & 0xffff0000u);
+                hi[2 * i] = (a[i + 2] & 0xffffu) | (b[i + 2] << 16);
+                hi[2 * i + 1] = (a[i + 2] >> 16) | (b[i + 2] & 0xffff0000u);
+            }
+            unsigned int* d = reinterpret_cast<unsigned int*>(s) + q * P + 8 * rg;
+            *reinterpret_cast<v4u*>(d) = lo;
+            *reinterpret_cast<v4u*>(d + 4) = hi;
+        }
+    }
+}
+
+// operand of MFMA step `st` (16 k each) for the 32-row sub-tile at r0:
+// element (r0 + lane%32, 16*st + 8*(lane/32) + 0..7)
+template <int TILE, bool KC>
+__device__ __forceinline__ v8h hread_frag(const char* __restrict__ s, int r0, int st, int lane) {
+    const int rr = r0 + (lane & 31), kh = 16 * st + 8 * (lane >> 5);
+    union { v4u u; v8h h; } x;
+    if (KC) {
+        x.u = *reinterpret_cast<const v4u*>(s + (rr * HKC_PITCH + kh) * 2);
+    } else {
+        constexpr int P = HLds<TILE>::RC_PITCH;
+        const unsigned int* d = reinterpret_cast<const unsigned int*>(s) + (kh >> 1) * P + rr;
+        x.u[0] = d[0];
+        x.u[1] = d[P];
+        x.u[2] = d[2 * P];
+        x.u[3] = d[3 * P];
+    }
+    return x.h;
+}
+
+template <int TILE, bool TA, bool TB>
+__global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
+    constexpr int MT = TILE / 64;
+    constexpr bool A_KC = !TA;
+    constexpr bool B_KC = TB;
+    constexpr int NV = HRegs<TILE>::NV;
+    constexpr int SLAB = HLds<TILE>::BYTES;
+
+    __shared__ __attribute__((aligned(16))) char lds[2 * 2 * SLAB];
+
+    const int64_t W = gridDim.x;
+    const int64_t bid = blockIdx.x;
+    const int64_t xcd = bid % HNUM_XCD, local = bid / HNUM_XCD;
+    const int64_t per = W / HNUM_XCD, rem = W % HNUM_XCD;
+    const int64_t lid = xcd * per + (xcd < rem ? xcd : rem) + local;
+
+    const int B = g.B;
+    const int tiles = B / TILE;
+    const int T = tiles * tiles;
+    const int64_t blk = lid / ((int64_t)g.nprob * T);
+    const int r1 = (int)(lid % ((int64_t)g.nprob * T));
+    const int pi = r1 / T;
+    const int tile = r1 % T;
+    const int row0 = (tile / tiles) * TILE;
+    const int col0 = (tile % tiles) * TILE;
+
+    const GemmProblem& P = g.prob[pi];
+    const size_t boff = (size_t)blk * B * B;
+    const __bf16* __restrict__ Ab = static_cast<const __bf16*>(P.A) + boff;
+    const __bf16* __restrict__ Bb = static_cast<const __bf16*>(P.B) + boff;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
+
+    v16f acc[MT][MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    v4u ra[NV], rb[NV];
+    hload_slab<TILE, A_KC>(Ab, B, row0, 0, ra);
+    hload_slab<TILE, B_KC>(Bb, B, col0, 0, rb);
+    hstore_slab<TILE, A_KC>(lds, ra);
+    hstore_slab<TILE, B_KC>(lds + SLAB, rb);
+    __syncthreads();
+
+    const int KT = B / HBK;
+    for (int kt = 0; kt < KT; ++kt) {
+        const char* sa = lds + (kt & 1) * 2 * SLAB;
+        const char* sb = sa + SLAB;
+        const bool more = kt + 1 < KT;
+        if (more) {
+            hload_slab<TILE, A_KC>(Ab, B, row0, (kt + 1) * HBK, ra);
+            hload_slab<TILE, B_KC>(Bb, B, col0, (kt + 1) * HBK, rb);
+        }
+#pragma unroll
+        for (int st = 0; st < HBK / 16; ++st) {
+            v8h fa[MT], fb[MT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) fa[i] = hread_frag<TILE, A_KC>(sa, wm + 32 * i, st, lane);
+#pragma unroll
+            for (int j = 0; j < MT; ++j) fb[j] = hread_frag<TILE, B_KC>(sb, wn + 32 * j, st, lane);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < MT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            char* da = lds + ((kt + 1) & 1) * 2 * SLAB;
+            hstore_slab<TILE, A_KC>(da, ra);
+            hstore_slab<TILE, B_KC>(da + SLAB, rb);
+        }
+        __syncthreads();
+    }
+
+    const float mult = P.mult ? P.mult[blk] : 1.f;
+    const float alpha = P.alpha * mult, beta = P.beta * mult, gamma = P.gamma * mult;
+    const float* __restrict__ Db = P.D ? P.D + boff : nullptr;
+    float* __restrict__ Cb = P.C ? P.C + boff : nullptr;
+    __bf16* __restrict__ Hb = P.Ch ? static_cast<__bf16*>(P.Ch) + boff : nullptr;
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < MT; ++j) {
+            const int col = col0 + wn + 32 * j + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const size_t off = (size_t)row * B + col;
+                float v = alpha * acc[i][j][r];
+                if (Db) v += beta * Db[off];
+                if (row == col) v += gamma;
+                bad |= !(fabsf(v) <= 3.0e38f);
+                if (Cb) Cb[off] = v;
+                if (Hb) Hb[off] = (__bf16)v;
+            }
+        }
+    if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;
+}
+
+template <int TILE>
+hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
+    const int tiles = g.B / TILE;
+    const int64_t W = g.nblocks * g.nprob * tiles * tiles;
+    if (W <= 0) return hipSuccess;
+    if (W > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int ta = g.prob[0].transA, tb = g.prob[0].transB;
+    dim3 grid((unsigned)W), block(HNT);
+    if (!ta && !tb) hipLaunchKernelGGL((gemm_bf16_kernel<TILE, false, false>), grid, block, 0, stream, g);
+    else if (!ta && tb) hipLaunchKernelGGL((gemm_bf16_kernel<TILE, false, true>), grid, block, 0, stream, g);
+    else if (ta && !tb) hipLaunchKernelGGL((gemm_bf16_kernel<TILE, true, false>), grid, block, 0, stream, g);
+    else hipLaunchKernelGGL((gemm_bf16_kernel<TILE, true, true>), grid, block, 0, stream, g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemm_bf16(const GemmLaunch& g, hipStream_t stream) {
+    const bool big = (g.B % 128 == 0) && (g.nblocks * g.nprob * (int64_t)(g.B / 128) * (g.B / 128) >= 256);
+    return big ? hlaunch_tile<128>(g, stream) : hlaunch_tile<64>(g, stream);
+}
+
+}  // namespace dash

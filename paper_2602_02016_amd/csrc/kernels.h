@@ -10,11 +10,16 @@ namespace dash {
 // One batched product  C_b = mult_b * (alpha * op(A_b) op(B_b) + beta * D_b + gamma * I).
 // mult (per-block factor, device array) may be null (= 1).  D may be null when beta == 0
 // and may equal C.
+// fp32 launches: A, B are fp32 stacks, Ch is ignored.
+// bf16 launches (GemmLaunch::bf16 = 1): A, B point to bf16 stacks (same [N][B][B] layout,
+// 2-byte elements); the result is written to C in fp32 (if C is not null) and, rounded
+// to bf16, to Ch (if Ch is not null); D stays fp32.
 struct GemmProblem {
-    const float* A;
-    const float* B;
+    const void* A;
+    const void* B;
     const float* D;
     float* C;
+    void* Ch;
     const float* mult;
     float alpha, beta, gamma;
     int transA, transB;
@@ -32,6 +37,7 @@ struct GemmLaunch {
 };
 
 hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream);
+hipError_t launch_gemm_bf16(const GemmLaunch& g, hipStream_t stream);   // gemm_bf16.hip
 
 // partial[b*P + q] = sum over the q-th row slab of block b of (A + eps I)^2 (mode 0)
 // or of the diagonal of (A + eps I) (mode 1).  P = norm_slabs(B).
@@ -43,11 +49,12 @@ hipError_t launch_norm_partials(const float* A, int64_t nblocks, int B, float ep
 hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, int mode, int p,
                                  float* s, float* inv_s, float* unscale, hipStream_t stream);
 
-// t = (in + eps I) * mult_b ; out1 = a1 * t + g1 * I ; out2 = a2 * out1 + g2 * I.
-// mult, out2 may be null.  out1 may be null only if out2 is null too... (out1 required).
+// t = (in + eps I) * mult_b ; o1 = a1 * t + g1 * I ; o2 = a2 * o1 + g2 * I.
+// o1 is written to out1 (fp32) and/or h1 (rounded to bf16), o2 to out2 and/or h2; any of
+// the four destinations and mult may be null.
 hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult,
                               float a1, float g1, float* out1, float a2, float g2, float* out2,
-                              int32_t* nonfinite, hipStream_t stream);
+                              void* h1, void* h2, int32_t* nonfinite, hipStream_t stream);
 
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
 

@@ -1,0 +1,69 @@
+"""Pins for the bf16-operand emulation (oracle/lowprec.py)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import lowprec
+from oracle import newton_db as ondb
+from oracle.evd import rel_frobenius_error
+
+
+def test_round_bf16_exact_facts():
+    # bf16 keeps 8 significand bits: spacing 2^-7 in [1, 2)
+    f = np.float32
+    assert lowprec.round_bf16(f(1.0)) == 1.0
+    assert lowprec.round_bf16(f(1.0 + 2.0 ** -7)) == f(1.0 + 2.0 ** -7)          # representable
+    assert lowprec.round_bf16(f(1.0 + 2.0 ** -8)) == 1.0                         # tie -> even (down)
+    assert lowprec.round_bf16(f(1.0 + 3 * 2.0 ** -8)) == f(1.0 + 2.0 ** -6)      # tie -> even (up)
+    assert lowprec.round_bf16(f(1.0 + 2.0 ** -8 + 2.0 ** -20)) == f(1.0 + 2.0 ** -7)   # above the tie
+    assert lowprec.round_bf16(f(-0.3)) == -lowprec.round_bf16(f(0.3))
+    assert np.isnan(lowprec.round_bf16(f(np.nan))) and np.isinf(lowprec.round_bf16(f(3.4e38)))
+    assert lowprec.round_bf16(f(0.0)) == 0.0
+
+
+def test_round_bf16_matches_torch_conversion():
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(20000), rng.standard_normal(2000) * 1e-20,
+                        rng.standard_normal(2000) * 1e20]).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(lowprec.round_bf16(x), ref)
+
+
+def test_matmul_bf16_on_representable_operands_is_exact():
+    rng = np.random.default_rng(1)
+    A = lowprec.round_bf16(rng.standard_normal((16, 16)).astype(np.float32))
+    B = lowprec.round_bf16(rng.standard_normal((16, 16)).astype(np.float32))
+    assert np.array_equal(lowprec.matmul_bf16(A, B), (A.astype(np.float64) @ B.astype(np.float64)).astype(np.float32))
+    # and rounding really is applied to operands that are not representable
+    C = rng.standard_normal((16, 16)).astype(np.float32)
+    assert not np.array_equal(lowprec.matmul_bf16(C, B), (C.astype(np.float64) @ B).astype(np.float32))
+
+
+@pytest.mark.parametrize("p", [2, 4])
+def test_without_rounding_it_is_the_float64_iteration(p):
+    A32, _, _ = workloads.spd_stack(2, 32, -1.0, 0.0, seed=3)
+    X = lowprec.inverse_root_ndb_lowprec(A32, p, 8, eps=1e-6, rounding=False)
+    X64 = ondb.inverse_root_ndb(A32.astype(np.float64), p, 8, eps=1e-6)
+    assert rel_frobenius_error(X, X64).max() < 5e-6
+
+
+def test_exactly_representable_iterates():
+    # A = I/2 scaled by its Frobenius norm: every iterate is a multiple of I; with B = 4 the scale
+    # is exactly 1 (||I/2||_F = 1) and the first iterates 1.25, 0.625*... are short binary fractions
+    A = 0.5 * np.eye(4, dtype=np.float32)
+    X1 = lowprec.inverse_root_ndb_lowprec(A, 2, 1)
+    assert np.array_equal(X1, np.float32(1.25) * np.eye(4, dtype=np.float32))   # Z_1 = 1.5 - 0.25
+    X2 = lowprec.inverse_root_ndb_lowprec(A, 2, 2)
+    y1, z1 = 0.5 * 1.25, 1.25
+    e2 = 1.5 - 0.5 * z1 * y1
+    assert np.allclose(np.diag(X2), e2 * z1, rtol=2e-3)       # operands 1.25, 0.625 exact; E_2 rounds to bf16
+
+
+def test_bf16_plateau_is_where_expected():
+    # well-conditioned block: bf16 operands stall around 1e-3..1e-2 while fp32/float64 converge
+    A32, Q, lam = workloads.spd_stack(1, 64, -1.0, 0.0, seed=5)
+    X_true = (Q[0] * lam[0] ** -0.25) @ Q[0].T
+    e_lo = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32[0], 4, 12), X_true)[0]
+    e_hi = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32[0], 4, 12, rounding=False), X_true)[0]
+    assert e_hi < 1e-5 and 1e-4 < e_lo < 5e-2
