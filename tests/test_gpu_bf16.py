@@ -65,7 +65,7 @@ def test_ndb_bf16_few_iterations_match_emulation(dash, p, k):
     # a bf16 rounding of an iterate can fall on the other side of a tie when the fp32 sum
     # differs in its last bit from the float64 sum: isolated 2^-8 relative flips, whose
     # Frobenius weight stays far below 2^-8
-    assert e < 2e-3
+    assert e < 2e-4
 
 
 def test_ndb_bf16_error_table_well_conditioned(dash):
