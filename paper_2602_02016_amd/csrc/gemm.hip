@@ -34,8 +34,12 @@ namespace dash {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 16;         // K slab
-constexpr int KC_PITCH = 20;   // floats per row in the k-contiguous layout (16 + 4 pad)
+#ifndef DASH_BK
+#define DASH_BK 16
+#endif
+constexpr int BK = DASH_BK;        // K slab (16 or 32)
+constexpr int KC_PITCH = BK + 4;   // floats per row in the k-contiguous layout (4 floats of padding)
+constexpr int KQ = BK / 4;         // float4 per row of a k-contiguous slab
 constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
 
@@ -48,17 +52,17 @@ struct Lds {
 };
 
 // ---- global -> registers ------------------------------------------------------------
-// A slab holds TILE*BK floats = TILE*4 float4; each thread carries TILE*4/256 of them.
+// A slab holds TILE*BK floats = TILE*KQ float4; each thread carries TILE*KQ/256 of them.
 template <int TILE, bool KC>
 __device__ __forceinline__ void load_slab(const float* __restrict__ base, int ld, int row0, int k0,
-                                          v4f (&r)[TILE * 4 / NTHREADS]) {
-    constexpr int NV = TILE * 4 / NTHREADS;
+                                          v4f (&r)[TILE * KQ / NTHREADS]) {
+    constexpr int NV = TILE * KQ / NTHREADS;
     const int t = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
         const int f = t + NTHREADS * u;
         if (KC) {   // element (row, k) at base[row*ld + k]
-            const int row = f >> 2, kq = f & 3;
+            const int row = f / KQ, kq = f % KQ;
             r[u] = *reinterpret_cast<const v4f*>(base + (size_t)(row0 + row) * ld + k0 + 4 * kq);
         } else {    // element (row, k) at base[k*ld + row]
             constexpr int QPR = TILE / 4;   // float4 per k-line
@@ -70,14 +74,14 @@ __device__ __forceinline__ void load_slab(const float* __restrict__ base, int ld
 
 // ---- registers -> LDS ----------------------------------------------------------------
 template <int TILE, bool KC>
-__device__ __forceinline__ void store_slab(float* __restrict__ s, const v4f (&r)[TILE * 4 / NTHREADS]) {
-    constexpr int NV = TILE * 4 / NTHREADS;
+__device__ __forceinline__ void store_slab(float* __restrict__ s, const v4f (&r)[TILE * KQ / NTHREADS]) {
+    constexpr int NV = TILE * KQ / NTHREADS;
     const int t = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
         const int f = t + NTHREADS * u;
         if (KC) {
-            const int row = f >> 2, kq = f & 3;
+            const int row = f / KQ, kq = f % KQ;
             *reinterpret_cast<v4f*>(s + row * KC_PITCH + 4 * kq) = r[u];
         } else {
             constexpr int QPR = TILE / 4;
@@ -109,11 +113,14 @@ __device__ __forceinline__ v4f read_frag(const float* __restrict__ s, int r0, in
 // TILE x TILE output tile per workgroup; each of the 4 waves owns (TILE/2) x (TILE/2),
 // i.e. MT x MT MFMA tiles of 32 x 32 with MT = TILE/64.
 template <int TILE, bool TA, bool TB>
-__global__ __launch_bounds__(NTHREADS, 2) void gemm_f32_kernel(GemmLaunch g) {
+#ifndef DASH_MIN_WG
+#define DASH_MIN_WG 2
+#endif
+__global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLaunch g) {
     constexpr int MT = TILE / 64;
     constexpr bool A_KC = !TA;   // op(A)(i,k): k contiguous unless transposed
     constexpr bool B_KC = TB;    // op(B)(k,j): j contiguous unless transposed
-    constexpr int NV = TILE * 4 / NTHREADS;
+    constexpr int NV = TILE * KQ / NTHREADS;
     constexpr int SLAB = Lds<TILE>::SIZE;
 
     __shared__ __attribute__((aligned(16))) float lds[2 * 2 * SLAB];
