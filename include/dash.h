@@ -87,10 +87,25 @@ typedef struct {
     int64_t variant_launches[4];
     double  variant_block_products[4];
     double  variant_ms[4];
+    /* flops of the output tiles actually computed (in symmetric mode a launch computes only
+       the tiles on or above the diagonal), in total and per variant */
+    double  matmul_flops;
+    double  variant_flops[4];
 } dash_stats;
 dash_status dash_reset_stats(dash_ctx* ctx);
 dash_status dash_set_timing(dash_ctx* ctx, int on);
 dash_status dash_get_stats(dash_ctx* ctx, dash_stats* out /* host */);
+
+/* Symmetric mode (default on).  The residual product Z Y of Newton-DB (E = 3/2 I - 1/2 Z Y)
+ * and every product of the Clenshaw recurrence are polynomials in the input block and
+ * therefore symmetric in exact arithmetic, and G G^T, G^T G are symmetric bit for bit.  With
+ * the mode on, those products compute only the output tiles on or above the diagonal (in the
+ * operand order the paper prints) and write every off-diagonal tile a second time transposed.
+ * The Newton-DB updates Y E and E Z are always computed in full: symmetrising them breaks the
+ * coupling between Y and Z and the iteration diverges on ill-conditioned blocks.  Off: every
+ * product is computed in full.  The preconditioned update and dash_gemm_batched always
+ * compute full products. */
+dash_status dash_set_symmetric(dash_ctx* ctx, int on);
 
 /* ---- the batched matmul primitive (the paper's `bmm`, Sections 3.1 and 4.1) ------ */
 

@@ -35,7 +35,7 @@ class _Stats(C.Structure):
     _fields_ = [("matmul_products", C.c_int64), ("matmul_launches", C.c_int64),
                 ("matmul_block_products", C.c_double), ("matmul_ms", C.c_double),
                 ("variant_launches", C.c_int64 * 4), ("variant_block_products", C.c_double * 4),
-                ("variant_ms", C.c_double * 4)]
+                ("variant_ms", C.c_double * 4), ("matmul_flops", C.c_double), ("variant_flops", C.c_double * 4)]
 
 
 class _StepArgs(C.Structure):
@@ -75,6 +75,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_status_string.restype = C.c_char_p
     lib.dash_reset_stats.argtypes = [vp]
     lib.dash_set_timing.argtypes = [vp, i32]
+    lib.dash_set_symmetric.argtypes = [vp, i32]
     lib.dash_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     lib.dash_gemm_batched.argtypes = [vp, i32, i32, vp, vp, vp, vp, i64, i32, f32, f32, f32, i32]
     lib.dash_accumulate_factors.argtypes = [vp, vp, vp, vp, i64, i32, f32, f32]
@@ -86,6 +87,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_graft_update.argtypes = [vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, vp]
     lib.dash_step.argtypes = [vp, C.POINTER(_StepArgs)]
     for name in ("dash_create", "dash_destroy", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
+                 "dash_set_symmetric",
                  "dash_get_stats", "dash_gemm_batched", "dash_accumulate_factors", "dash_block_norms",
                  "dash_inverse_root", "dash_chebyshev_fit", "dash_precondition", "dash_graft_update", "dash_step"):
         getattr(lib, name).restype = C.c_int
@@ -194,7 +196,12 @@ class Dash:
         return dict(matmul_products=s.matmul_products, matmul_launches=s.matmul_launches,
                     matmul_block_products=s.matmul_block_products, matmul_ms=s.matmul_ms,
                     variant_launches=list(s.variant_launches),
-                    variant_block_products=list(s.variant_block_products), variant_ms=list(s.variant_ms))
+                    variant_block_products=list(s.variant_block_products), variant_ms=list(s.variant_ms),
+                    matmul_flops=s.matmul_flops, variant_flops=list(s.variant_flops))
+
+    def set_symmetric(self, on: bool):
+        """Symmetric mode of the library (see dash_set_symmetric in dash.h); default on."""
+        self._check(self.lib.dash_set_symmetric(self.h, 1 if on else 0))
 
     # ---- the calls of dash.h -------------------------------------------------------------
     def gemm_batched(self, A, Bm, C_out, D=None, transA=False, transB=False, alpha=1.0, beta=0.0, gamma=0.0,

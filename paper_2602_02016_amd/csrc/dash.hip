@@ -33,6 +33,10 @@ struct dash_ctx {
     int64_t var_launches[4] = {0, 0, 0, 0};
     double var_block_products[4] = {0, 0, 0, 0};
     double var_ms[4] = {0, 0, 0, 0};
+    double mm_flops = 0.0;                       // flops of the tiles actually computed
+    double var_flops[4] = {0, 0, 0, 0};
+    // products that are symmetric in exact arithmetic compute only their upper triangle of tiles
+    bool symmetric = true;
 };
 
 namespace {
@@ -118,6 +122,9 @@ dash_status run_gemm(dash_ctx* c, const GemmLaunch& g) {
     c->mm_block_products += (double)g.nprob * (double)g.nblocks;
     c->var_launches[variant] += 1;
     c->var_block_products[variant] += (double)g.nprob * (double)g.nblocks;
+    const double fl = (double)g.nprob * (double)g.nblocks * 2.0 * g.B * (double)g.B * g.B * gemm_tile_fraction(g);
+    c->mm_flops += fl;
+    c->var_flops[variant] += fl;
     return DASH_OK;
 }
 
@@ -151,17 +158,23 @@ GemmProblem problem_h(const bf16_t* Ah, const bf16_t* Bh, const float* D, float*
     return p;
 }
 
-dash_status gemm1(dash_ctx* c, const GemmProblem& p, int64_t n, int B, int32_t* nonfinite = nullptr, int bf16 = 0) {
+// sym: the product is symmetric in exact arithmetic (see GemmLaunch::sym); honoured only while the
+// context's symmetric mode is on
+dash_status gemm1(dash_ctx* c, const GemmProblem& p, int64_t n, int B, int32_t* nonfinite = nullptr, int bf16 = 0,
+                  bool sym = false) {
     GemmLaunch g;
     memset(&g, 0, sizeof(g));
     g.prob[0] = p; g.prob[1] = p; g.nprob = 1; g.B = B; g.nblocks = n; g.nonfinite = nonfinite; g.bf16 = bf16;
+    g.sym = (sym && c->symmetric) ? 1 : 0;
     return run_gemm(c, g);
 }
 
-dash_status gemm2(dash_ctx* c, const GemmProblem& p0, const GemmProblem& p1, int64_t n, int B, int bf16 = 0) {
+dash_status gemm2(dash_ctx* c, const GemmProblem& p0, const GemmProblem& p1, int64_t n, int B, int bf16 = 0,
+                  bool sym = false) {
     GemmLaunch g;
     memset(&g, 0, sizeof(g));
     g.prob[0] = p0; g.prob[1] = p1; g.nprob = 2; g.B = B; g.nblocks = n; g.nonfinite = nullptr; g.bf16 = bf16;
+    g.sym = (sym && c->symmetric) ? 1 : 0;
     return run_gemm(c, g);
 }
 
@@ -179,6 +192,10 @@ struct Carve {
 };
 
 // ---- Newton-DB on one chunk (paper Section 3.3) -----------------------------------------
+// Symmetric mode touches only the residual product Z Y of E = 1.5 I - 0.5 Z Y.  The updates
+// Y E and E Z are always computed in full: mirroring them (or symmetrising them in any way)
+// breaks the coupling Y_k = A Z_k that keeps the iteration stable, and ill-conditioned
+// blocks then diverge a few iterations after convergence.
 // One call: from the input M (already scaled so that its spectrum lies in (0,1]) run
 // `iters` updates of (Y, Z); the first is the closed form E_1 = 3/2 I - 1/2 M, Z_1 = E_1,
 // Y_1 = M E_1.  keepY: the caller wants Y_k (first call of p = 4), otherwise Z_k.  The
@@ -225,7 +242,7 @@ dash_status ndb_call(dash_ctx* c, float* buf[5], int mi, int64_t n, int B, int i
         const bool last = it == iters;
         int e = grab();
         // E = 1.5 I - 0.5 Z Y
-        DASH_TRY(gemm1(c, problem(buf[z], buf[y], nullptr, buf[e], nullptr, -0.5f, 0.f, 1.5f), n, B));
+        DASH_TRY(gemm1(c, problem(buf[z], buf[y], nullptr, buf[e], nullptr, -0.5f, 0.f, 1.5f), n, B, nullptr, 0, true));
         if (!last) {
             int y2 = grab(), z2 = grab();
             DASH_TRY(gemm2(c, problem(buf[y], buf[e], nullptr, buf[y2], nullptr, 1.f, 0.f, 0.f),
@@ -302,7 +319,7 @@ dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], float* fy, int mi, int64_t
     for (int it = 2; it <= iters; ++it) {
         const bool last = it == iters;
         int e = grab();
-        DASH_TRY(gemm1(c, problem_h(hb[z], hb[y], nullptr, nullptr, hb[e], nullptr, -0.5f, 0.f, 1.5f), n, B, nullptr, 1));
+        DASH_TRY(gemm1(c, problem_h(hb[z], hb[y], nullptr, nullptr, hb[e], nullptr, -0.5f, 0.f, 1.5f), n, B, nullptr, 1, true));
         if (!last) {
             int y2 = grab(), z2 = grab();
             DASH_TRY(gemm2(c, problem_h(hb[y], hb[e], nullptr, nullptr, hb[y2], nullptr, 1.f, 0.f, 0.f),
@@ -339,14 +356,14 @@ dash_status clenshaw_chunk_bf16(dash_ctx* c, float* fb[2], bf16_t* hb[3], const 
                                   Sh, h1, nullptr, st));
     if (d == 2)
         return gemm1(c, problem_h(Sh, h1, nullptr, X, nullptr, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B,
-                     nonfinite, 1);
-    DASH_TRY(gemm1(c, problem_h(Sh, h1, nullptr, b2, h2, nullptr, 2.f, 0.f, (float)(cf[d - 2] - cf[d])), n, B, nullptr, 1));
+                     nonfinite, 1, true);
+    DASH_TRY(gemm1(c, problem_h(Sh, h1, nullptr, b2, h2, nullptr, 2.f, 0.f, (float)(cf[d - 2] - cf[d])), n, B, nullptr, 1, true));
     { float* t = b1; b1 = b2; b2 = t; bf16_t* u = h1; h1 = h2; h2 = u; }
     for (int k = d - 3; k >= 1; --k) {
-        DASH_TRY(gemm1(c, problem_h(Sh, h1, b2, b2, h2, nullptr, 2.f, -1.f, (float)cf[k]), n, B, nullptr, 1));
+        DASH_TRY(gemm1(c, problem_h(Sh, h1, b2, b2, h2, nullptr, 2.f, -1.f, (float)cf[k]), n, B, nullptr, 1, true));
         float* t = b1; b1 = b2; b2 = t; bf16_t* u = h1; h1 = h2; h2 = u;
     }
-    return gemm1(c, problem_h(Sh, h1, b2, X, nullptr, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite, 1);
+    return gemm1(c, problem_h(Sh, h1, b2, X, nullptr, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite, 1, true);
 }
 
 // ---- Clenshaw on one chunk (paper Appendix A.2, reduced form, d-1 products) --------------
@@ -364,18 +381,18 @@ dash_status clenshaw_chunk(dash_ctx* c, float* buf[3], const float* A, float* X,
                                   nullptr, nullptr, nullptr, st));
     if (d == 2) {
         // result = S B_1 - B_2 + c_0 I with B_2 = c_2 I
-        return gemm1(c, problem(S, b1, nullptr, X, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B, nonfinite);
+        return gemm1(c, problem(S, b1, nullptr, X, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B, nonfinite, 0, true);
     }
     // k = d-2: B_{d-2} = 2 S B_{d-1} + (c_{d-2} - c_d) I
-    DASH_TRY(gemm1(c, problem(S, b1, nullptr, b2, nullptr, 2.f, 0.f, (float)(cf[d - 2] - cf[d])), n, B));
+    DASH_TRY(gemm1(c, problem(S, b1, nullptr, b2, nullptr, 2.f, 0.f, (float)(cf[d - 2] - cf[d])), n, B, nullptr, 0, true));
     { float* t = b1; b1 = b2; b2 = t; }   // b1 = B_{d-2}, b2 = B_{d-1}
     for (int k = d - 3; k >= 1; --k) {
         // B_k = 2 S B_{k+1} - B_{k+2} + c_k I, written over B_{k+2}
-        DASH_TRY(gemm1(c, problem(S, b1, b2, b2, nullptr, 2.f, -1.f, (float)cf[k]), n, B));
+        DASH_TRY(gemm1(c, problem(S, b1, b2, b2, nullptr, 2.f, -1.f, (float)cf[k]), n, B, nullptr, 0, true));
         float* t = b1; b1 = b2; b2 = t;
     }
     // result = S B_1 - B_2 + c_0 I, un-scaled
-    return gemm1(c, problem(S, b1, b2, X, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite);
+    return gemm1(c, problem(S, b1, b2, X, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite, 0, true);
 }
 
 }  // namespace
@@ -440,7 +457,8 @@ dash_status dash_reset_stats(dash_ctx* c) {
     c->mm_products = c->mm_launches = 0;
     c->mm_block_products = 0.0;
     c->ms_done = 0.0;
-    for (int v = 0; v < 4; ++v) { c->var_launches[v] = 0; c->var_block_products[v] = 0.0; c->var_ms[v] = 0.0; }
+    for (int v = 0; v < 4; ++v) { c->var_launches[v] = 0; c->var_block_products[v] = 0.0; c->var_ms[v] = 0.0; c->var_flops[v] = 0.0; }
+    c->mm_flops = 0.0;
     return DASH_OK;
 }
 
@@ -448,6 +466,12 @@ dash_status dash_set_timing(dash_ctx* c, int on) {
     if (!c) return DASH_ERR_INVALID_ARG;
     DASH_TRY(collect_events(c));
     c->timing = on != 0;
+    return DASH_OK;
+}
+
+dash_status dash_set_symmetric(dash_ctx* c, int on) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    c->symmetric = on != 0;
     return DASH_OK;
 }
 
@@ -462,7 +486,9 @@ dash_status dash_get_stats(dash_ctx* c, dash_stats* out) {
         out->variant_launches[v] = c->var_launches[v];
         out->variant_block_products[v] = c->var_block_products[v];
         out->variant_ms[v] = c->var_ms[v];
+        out->variant_flops[v] = c->var_flops[v];
     }
+    out->matmul_flops = c->mm_flops;
     return DASH_OK;
 }
 
@@ -510,8 +536,9 @@ dash_status dash_accumulate_factors(dash_ctx* c, const float* G, float* L, float
         return fail(c, DASH_ERR_INVALID_ARG, "G, L, R must not overlap");
     HIP_TRY(c, hipSetDevice(c->device));
     // L = beta L + alpha G G^T ; R = beta R + alpha G^T G  (EMA fused in the epilogue)
-    DASH_TRY(gemm1(c, problem(G, G, L, L, nullptr, alpha, beta, 0.f, 0, 1), N, B));
-    DASH_TRY(gemm1(c, problem(G, G, R, R, nullptr, alpha, beta, 0.f, 1, 0), N, B));
+    // G G^T and G^T G are symmetric bit for bit (same products, same summation order for (i,j) and (j,i))
+    DASH_TRY(gemm1(c, problem(G, G, L, L, nullptr, alpha, beta, 0.f, 0, 1), N, B, nullptr, 0, true));
+    DASH_TRY(gemm1(c, problem(G, G, R, R, nullptr, alpha, beta, 0.f, 1, 0), N, B, nullptr, 0, true));
     return DASH_OK;
 }
 

@@ -134,13 +134,23 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
 
     const int B = g.B;
     const int tiles = B / TILE;
-    const int T = tiles * tiles;
+    const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles;
     const int64_t blk = lid / ((int64_t)g.nprob * T);
     const int r1 = (int)(lid % ((int64_t)g.nprob * T));
     const int pi = r1 / T;
     const int tile = r1 % T;
-    const int row0 = (tile / tiles) * TILE;
-    const int col0 = (tile % tiles) * TILE;
+    int ti, tj;
+    if (g.sym) {        // tiles of the upper triangle, row by row: (0,0..t-1), (1,1..t-1), ...
+        int left = tile, len = tiles;
+        ti = 0;
+        while (left >= len) { left -= len; --len; ++ti; }
+        tj = ti + left;
+    } else {
+        ti = tile / tiles;
+        tj = tile % tiles;
+    }
+    const int row0 = ti * TILE;
+    const int col0 = tj * TILE;
 
     const GemmProblem& P = g.prob[pi];
     const size_t boff = (size_t)blk * B * B;
@@ -204,6 +214,10 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     const float alpha = P.alpha * mult, beta = P.beta * mult, gamma = P.gamma * mult;
     const float* __restrict__ Db = P.D ? P.D + boff : nullptr;
     float* __restrict__ Cb = P.C + boff;
+    // symmetric mode: an off-diagonal tile (ti < tj) is also written transposed to (tj, ti).
+    // A lane holds four consecutive rows of one column, i.e. four consecutive elements of a
+    // row of the transposed tile: one 16-byte store each.
+    const bool mirror = g.sym && ti != tj;
     bool bad = false;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -211,14 +225,21 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
         for (int j = 0; j < MT; ++j) {
             const int col = col0 + wn + 32 * j + (lane & 31);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const size_t off = (size_t)row * B + col;
-                float v = alpha * acc[i][j][r];
-                if (Db) v += beta * Db[off];
-                if (row == col) v += gamma;
-                bad |= !(fabsf(v) <= 3.0e38f);
-                Cb[off] = v;
+            for (int q = 0; q < 4; ++q) {
+                const int rbase = row0 + wm + 32 * i + 8 * q + 4 * (lane >> 5);
+                v4f out;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int row = rbase + m;
+                    const size_t off = (size_t)row * B + col;
+                    float v = alpha * acc[i][j][4 * q + m];
+                    if (Db) v += beta * Db[off];
+                    if (row == col) v += gamma;
+                    bad |= !(fabsf(v) <= 3.0e38f);
+                    Cb[off] = v;
+                    out[m] = v;
+                }
+                if (mirror) *reinterpret_cast<v4f*>(Cb + (size_t)col * B + rbase) = out;
             }
         }
     if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;
@@ -227,7 +248,7 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
 template <int TILE>
 static hipError_t launch_tile(const GemmLaunch& g, hipStream_t stream) {
     const int tiles = g.B / TILE;
-    const int64_t W = g.nblocks * g.nprob * tiles * tiles;
+    const int64_t W = g.nblocks * g.nprob * (g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles);
     if (W <= 0) return hipSuccess;
     if (W > 0x7fffffffLL) return hipErrorInvalidValue;
     // both products of a launch must use the same transpose flags (one kernel instance)
@@ -245,9 +266,20 @@ hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
     if (g.nprob == 2 && (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
         return hipErrorInvalidValue;
     if (g.bf16) return launch_gemm_bf16(g, stream);
-    // 128-wide tiles when they still give the chip enough workgroups, else 64-wide
+    return gemm_tile_edge(g) == 128 ? launch_tile<128>(g, stream) : launch_tile<64>(g, stream);
+}
+
+// 128-wide tiles when they still give the chip enough workgroups, else 64-wide
+int gemm_tile_edge(const GemmLaunch& g) {
     const bool big = (g.B % 128 == 0) && (g.nblocks * g.nprob * (int64_t)(g.B / 128) * (g.B / 128) >= 256);
-    return big ? launch_tile<128>(g, stream) : launch_tile<64>(g, stream);
+    return big ? 128 : 64;
+}
+
+// fraction of the B x B output tiles a launch computes (1, or (t+1)/(2t) in symmetric mode)
+double gemm_tile_fraction(const GemmLaunch& g) {
+    if (!g.sym) return 1.0;
+    const int t = g.B / gemm_tile_edge(g);
+    return (double)(t + 1) / (2.0 * t);
 }
 
 }  // namespace dash

@@ -25,6 +25,8 @@ namespace dash {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8h __attribute__((ext_vector_type(8)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v4h __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -149,13 +151,23 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
 
     const int B = g.B;
     const int tiles = B / TILE;
-    const int T = tiles * tiles;
+    const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles;
     const int64_t blk = lid / ((int64_t)g.nprob * T);
     const int r1 = (int)(lid % ((int64_t)g.nprob * T));
     const int pi = r1 / T;
     const int tile = r1 % T;
-    const int row0 = (tile / tiles) * TILE;
-    const int col0 = (tile % tiles) * TILE;
+    int ti, tj;
+    if (g.sym) {        // tiles of the upper triangle, row by row
+        int left = tile, len = tiles;
+        ti = 0;
+        while (left >= len) { left -= len; --len; ++ti; }
+        tj = ti + left;
+    } else {
+        ti = tile / tiles;
+        tj = tile % tiles;
+    }
+    const int row0 = ti * TILE;
+    const int col0 = tj * TILE;
 
     const GemmProblem& P = g.prob[pi];
     const size_t boff = (size_t)blk * B * B;
@@ -215,6 +227,9 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
     const float* __restrict__ Db = P.D ? P.D + boff : nullptr;
     float* __restrict__ Cb = P.C ? P.C + boff : nullptr;
     __bf16* __restrict__ Hb = P.Ch ? static_cast<__bf16*>(P.Ch) + boff : nullptr;
+    // symmetric mode: an off-diagonal tile is also written transposed (four consecutive rows
+    // of one column = four consecutive elements of a row of the transposed tile)
+    const bool mirror = g.sym && ti != tj;
     bool bad = false;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -222,15 +237,28 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
         for (int j = 0; j < MT; ++j) {
             const int col = col0 + wn + 32 * j + (lane & 31);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const size_t off = (size_t)row * B + col;
-                float v = alpha * acc[i][j][r];
-                if (Db) v += beta * Db[off];
-                if (row == col) v += gamma;
-                bad |= !(fabsf(v) <= 3.0e38f);
-                if (Cb) Cb[off] = v;
-                if (Hb) Hb[off] = (__bf16)v;
+            for (int q = 0; q < 4; ++q) {
+                const int rbase = row0 + wm + 32 * i + 8 * q + 4 * (lane >> 5);
+                v4f out;
+                v4h outh;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int row = rbase + m;
+                    const size_t off = (size_t)row * B + col;
+                    float v = alpha * acc[i][j][4 * q + m];
+                    if (Db) v += beta * Db[off];
+                    if (row == col) v += gamma;
+                    bad |= !(fabsf(v) <= 3.0e38f);
+                    out[m] = v;
+                    outh[m] = (__bf16)v;
+                    if (Cb) Cb[off] = v;
+                    if (Hb) Hb[off] = outh[m];
+                }
+                if (mirror) {
+                    const size_t moff = (size_t)col * B + rbase;
+                    if (Cb) *reinterpret_cast<v4f*>(Cb + moff) = out;
+                    if (Hb) *reinterpret_cast<v4h*>(Hb + moff) = outh;
+                }
             }
         }
     if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;
@@ -239,7 +267,7 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
 template <int TILE>
 hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
     const int tiles = g.B / TILE;
-    const int64_t W = g.nblocks * g.nprob * tiles * tiles;
+    const int64_t W = g.nblocks * g.nprob * (g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles);
     if (W <= 0) return hipSuccess;
     if (W > 0x7fffffffLL) return hipErrorInvalidValue;
     const int ta = g.prob[0].transA, tb = g.prob[0].transB;
@@ -254,8 +282,7 @@ hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_gemm_bf16(const GemmLaunch& g, hipStream_t stream) {
-    const bool big = (g.B % 128 == 0) && (g.nblocks * g.nprob * (int64_t)(g.B / 128) * (g.B / 128) >= 256);
-    return big ? hlaunch_tile<128>(g, stream) : hlaunch_tile<64>(g, stream);
+    return gemm_tile_edge(g) == 128 ? hlaunch_tile<128>(g, stream) : hlaunch_tile<64>(g, stream);
 }
 
 }  // namespace dash

@@ -34,9 +34,13 @@ struct GemmLaunch {
     int64_t nblocks;       // blocks in this launch
     int32_t* nonfinite;    // per-block flag for prob[0]'s output, or null
     int bf16;              // 0: fp32 MFMA operands, 1: operands rounded to bf16
+    int sym;               // 1: every product of the launch is symmetric in exact arithmetic:
+                           //    only tiles on or above the diagonal are computed, the rest mirrored
 };
 
 hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream);
+int gemm_tile_edge(const GemmLaunch& g);          // tile edge launch_gemm picks (64 or 128)
+double gemm_tile_fraction(const GemmLaunch& g);   // share of output tiles actually computed
 hipError_t launch_gemm_bf16(const GemmLaunch& g, hipStream_t stream);   // gemm_bf16.hip
 
 // partial[b*P + q] = sum over the q-th row slab of block b of (A + eps I)^2 (mode 0)

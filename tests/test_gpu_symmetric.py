@@ -1,0 +1,147 @@
+"""Symmetric mode: the residual product Z Y of Newton-DB, every product of the Clenshaw
+recurrence and the factor accumulation compute only the tiles on or above the diagonal and
+mirror the rest.  Both modes must meet the same parity bars; mirrored results must be exactly
+symmetric outside the diagonal tiles; factor accumulation must not change by a single bit;
+Newton-DB must stay stable long after convergence (mirroring its Y/Z updates would not)."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import newton_db as ondb
+from oracle import chebyshev as ocheb
+from oracle import shampoo as oshampoo
+from oracle.evd import inverse_root_evd, rel_frobenius_error
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture()
+def dashes():
+    from paper_2602_02016_amd import Dash
+    sym, full = Dash(0), Dash(0)
+    full.set_symmetric(False)
+    yield sym, full
+    sym.close(); full.close()
+
+
+def _to_gpu(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _offdiag_tile_mask(B, tile):
+    t = np.arange(B) // tile
+    return t[:, None] != t[None, :]
+
+
+@pytest.mark.parametrize("N,B", [(3, 128), (2, 256), (5, 512), (33, 1024)])
+def test_accumulate_is_bit_identical(dashes, N, B):
+    import torch
+    sym, full = dashes
+    G = _to_gpu(workloads.gradient_stack(N, B, 81))
+    S1 = torch.zeros(2 * N, B, B, device="cuda"); S2 = torch.zeros_like(S1)
+    for _ in range(2):
+        sym.accumulate_factors(G, S1[:N], S1[N:], 0.95)
+        full.accumulate_factors(G, S2[:N], S2[N:], 0.95)
+    torch.cuda.synchronize()
+    assert torch.equal(S1, S2)
+    sym.reset_stats(); full.reset_stats()
+    sym.accumulate_factors(G, S1[:N], S1[N:], 0.95); full.accumulate_factors(G, S2[:N], S2[N:], 0.95)
+    fs, ff = sym.get_stats()["matmul_flops"], full.get_stats()["matmul_flops"]
+    assert ff == 2 * N * 2.0 * B ** 3 and fs < ff
+
+
+@pytest.mark.parametrize("p", [2, 4])
+@pytest.mark.parametrize("N,B,lo", [(4, 128, -3.0), (3, 256, -1.0), (2, 512, -2.0), (9, 1024, -1.0)])
+def test_ndb_both_modes_meet_the_same_bar(dashes, N, B, lo, p):
+    sym, full = dashes
+    k = 12
+    A32, _, _ = workloads.spd_stack(N, B, lo, 0.0, seed=83 + B, share_q=B >= 512)
+    A = _to_gpu(A32)
+    sym.reset_stats(); full.reset_stats()
+    Xs = sym.inverse_root(A, p=p, iters=k, eps=1e-6).cpu().numpy()
+    Xf = full.inverse_root(A, p=p, iters=k, eps=1e-6).cpu().numpy()
+    ss, sf = sym.get_stats(), full.get_stats()
+    assert ss["matmul_products"] == sf["matmul_products"]          # same products of the method ...
+    tile = 128 if (B % 128 == 0 and N * (B // 128) ** 2 >= 256) else 64
+    t = B // tile
+    calls = p // 2
+    n_res, n_all = calls * (k - 1), calls * (3 * k - 3)       # residual products / all products
+    expect = (n_all - n_res + n_res * (t + 1) / (2 * t)) * N * 2.0 * B ** 3
+    assert sf["matmul_flops"] == n_all * N * 2.0 * B ** 3
+    assert ss["matmul_flops"] == pytest.approx(expect, rel=1e-12)                                   # ... fewer tiles
+    sample = [0, N - 1]
+    X_same = ondb.inverse_root_ndb(A32[sample].astype(np.float64), p, k, eps=1e-6)
+    floor = 4.0 * max(1e-6, 0.1 * 10 ** (-lo) * 2.0 ** -24) * max(1.0, (B / 256.0) ** 0.5) * (2.5 if p == 2 else 1.0)
+    es, ef = rel_frobenius_error(Xs[sample], X_same).max(), rel_frobenius_error(Xf[sample], X_same).max()
+    print(f"ndb sym/full N={N} B={B} p={p}: vs float64 same-k  sym {es:.2e}  full {ef:.2e}", flush=True)
+    assert es < floor and ef < floor
+
+
+@pytest.mark.parametrize("p", [2, 4])
+def test_ndb_symmetric_mode_stays_stable_after_convergence(dashes, p):
+    """kappa = 1e4: converged by k ~ 16; 40 iterations must stay at the fp32 floor in both modes."""
+    sym, full = dashes
+    N, B = 4, 256
+    A32, _, _ = workloads.spd_stack(N, B, -4.0, 0.0, seed=89, share_q=True)
+    X_evd = inverse_root_evd(A32.astype(np.float64), p)
+    floor = 4.0 * 0.1 * 1e4 * 2.0 ** -24 * (2.5 if p == 2 else 1.0)
+    for k in (20, 40):
+        es = rel_frobenius_error(sym.inverse_root(_to_gpu(A32), p=p, iters=k).cpu().numpy(), X_evd).max()
+        ef = rel_frobenius_error(full.inverse_root(_to_gpu(A32), p=p, iters=k).cpu().numpy(), X_evd).max()
+        print(f"ndb stability p={p} k={k}: sym {es:.2e} full {ef:.2e}", flush=True)
+        assert es < floor and ef < floor
+
+
+def test_chebyshev_and_step_both_modes(dashes):
+    import torch
+    from paper_2602_02016_amd import chebyshev_fit
+    sym, full = dashes
+    N, B, p, d = 3, 256, 4, 16
+    A32, _, lam = workloads.spd_stack(N, B, -1.0, 0.0, seed=85)
+    s = np.sqrt((A32.astype(np.float64) ** 2).sum(axis=(1, 2)))
+    a, b = float((lam.min(axis=1) / s).min()) * 0.99, 1.0
+    coef = chebyshev_fit(p, d, a, b)
+    X64 = ocheb.inverse_root_chebyshev(A32.astype(np.float64), p, np.array(coef), a, b)
+    for dsh in (sym, full):
+        dsh.reset_stats()
+        X = dsh.inverse_root(_to_gpu(A32), method="chebyshev", p=p, iters=d, cheb_coeffs=coef, cheb_a=a, cheb_b=b)
+        X = X.cpu().numpy()
+        assert rel_frobenius_error(X, X64).max() < 1e-5
+        mask = _offdiag_tile_mask(B, 64)
+        if dsh is sym:      # mirrored tiles are exact transposes, and 10 of 16 tiles were computed
+            assert np.array_equal(X[0][mask], X[0].T[mask])
+            assert dsh.get_stats()["matmul_flops"] == pytest.approx((d - 1) * N * 2.0 * B ** 3 * 10 / 16)
+        else:               # the full product is only nearly symmetric
+            assert not np.array_equal(X[0], X[0].T)
+    # whole step
+    beta, eps = 0.95, 1e-6
+    L64, R64 = np.zeros((N, B, B)), np.zeros((N, B, B))
+    S = {id(sym): torch.zeros(2 * N, B, B, device="cuda"), id(full): torch.zeros(2 * N, B, B, device="cuda")}
+    for t in range(4):
+        G = workloads.gradient_stack(N, B, 8600 + t)
+        for dsh in (sym, full):
+            dsh.accumulate_factors(_to_gpu(G), S[id(dsh)][:N], S[id(dsh)][N:], beta)
+        L64, R64 = oshampoo.accumulate_factors(G, L64, R64, beta)
+    G = workloads.gradient_stack(N, B, 8700)
+    ref = oshampoo.step(G, L64, R64, beta=beta, eps=eps, p=4)
+    for dsh in (sym, full):
+        X = torch.zeros(2 * N, B, B, device="cuda"); U = torch.zeros(N, B, B, device="cuda")
+        dsh.step(_to_gpu(G), S[id(dsh)], X, U, beta=beta, eps=eps, p=4, iters=12)
+        assert rel_frobenius_error(X.cpu().numpy(), np.concatenate([ref["X_L"], ref["X_R"]])).max() < 1e-4
+        assert rel_frobenius_error(U.cpu().numpy(), ref["U"]).max() < 1e-4
+
+
+def test_bf16_both_modes(dashes):
+    from oracle import lowprec
+    sym, full = dashes
+    N, B = 3, 256
+    A32, _, _ = workloads.spd_stack(N, B, -1.0, 0.0, seed=87)
+    X_evd = inverse_root_evd(A32.astype(np.float64), 4, eps=1e-6)
+    for k in (2, 10):
+        Xs = sym.inverse_root(_to_gpu(A32), p=4, iters=k, eps=1e-6, precision="bf16").cpu().numpy()
+        Xf = full.inverse_root(_to_gpu(A32), p=4, iters=k, eps=1e-6, precision="bf16").cpu().numpy()
+        Xe = lowprec.inverse_root_ndb_lowprec(A32, 4, k, eps=1e-6)
+        es, ef, ee = (rel_frobenius_error(x, X_evd).max() for x in (Xs, Xf, Xe))
+        print(f"bf16 sym/full k={k}: vs EVD sym {es:.2e} full {ef:.2e} emulation {ee:.2e}", flush=True)
+        assert es < 2 * ee + 1e-3 and ef < 2 * ee + 1e-3
