@@ -84,20 +84,26 @@ def ndb_scalar_steps_to_tol(x: float, tol: float = 1e-10, max_iters: int = 200) 
     return max_iters + 1
 
 
-def block_scale(Ad: np.ndarray, scaling: str) -> float:
+def block_scale(Ad: np.ndarray, scaling: str, pi=None) -> float:
     """s with lambda_max(A_d) <= s: Frobenius norm (Section 3.4) or trace (valid for SPD
-    since lambda_max <= ||A||_F <= tr A); 'none' returns 1."""
+    since lambda_max <= ||A||_F <= tr A); 'none' returns 1.  'power_iteration' is the
+    paper's 2 * lambda_PI (Sections 3.4, 3.5) with pi = (V0, sweeps); it satisfies
+    lambda_max < 2 s' only once lambda_PI > lambda_max / 2, which a few sweeps give."""
     if scaling == "frobenius":
         return float(np.sqrt((Ad * Ad).sum()))
     if scaling == "trace":
         return float(np.trace(Ad))
     if scaling == "none":
         return 1.0
+    if scaling == "power_iteration":
+        from .power_iteration import multi_power_iteration
+        V0, sweeps = pi
+        return 2.0 * multi_power_iteration(Ad, V0, sweeps)[0]
     raise ValueError(scaling)
 
 
 def inverse_root_ndb(A, p: int, iters: int, eps: float = 0.0, scaling: str = "frobenius",
-                     counter: MatmulCounter | None = None):
+                     counter: MatmulCounter | None = None, pi=None):
     """X_i ~ (A_i + eps I)^(-1/p), p in {2,4}, by Newton-DB with `iters` updates per call.
 
     p=2: one call, keep Z.  p=4: first call keeps Y ~ A_s^{1/2}; a second call on that Y
@@ -112,7 +118,7 @@ def inverse_root_ndb(A, p: int, iters: int, eps: float = 0.0, scaling: str = "fr
     eye = np.eye(A.shape[1])
     for i in range(A.shape[0]):
         Ad = A[i] + eps * eye
-        s = block_scale(Ad, scaling)
+        s = block_scale(Ad, scaling, pi)
         As = Ad / s
         Y, Z = ndb_shortcut(As, iters, counter)
         if p == 4:
@@ -121,7 +127,7 @@ def inverse_root_ndb(A, p: int, iters: int, eps: float = 0.0, scaling: str = "fr
     return X[0] if single else X
 
 
-def inverse_root_ndb_model(A, p: int, iters: int, eps: float = 0.0, scaling: str = "frobenius"):
+def inverse_root_ndb_model(A, p: int, iters: int, eps: float = 0.0, scaling: str = "frobenius", pi=None):
     """The same result predicted through the spectrum: with A_d = Q diag(lam) Q^T every
     iterate is Q diag(g(lam/s)) Q^T where g is the scalar recurrence.  Used to separate
     truncation error (finite `iters`) from rounding error."""
@@ -133,7 +139,7 @@ def inverse_root_ndb_model(A, p: int, iters: int, eps: float = 0.0, scaling: str
     eye = np.eye(A.shape[1])
     for i in range(A.shape[0]):
         Ad = 0.5 * (A[i] + A[i].T) + eps * eye
-        s = block_scale(Ad, scaling)
+        s = block_scale(Ad, scaling, pi)
         lam, Q = np.linalg.eigh(Ad)
         y, z = ndb_scalar(lam / s, iters)
         if p == 4:

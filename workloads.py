@@ -120,3 +120,14 @@ def cfg3_num_gradient_blocks() -> int:
     c = CFG3
     per_layer = 4 * blocks_of_layer(c["d"], c["d"], c["B"]) + 3 * blocks_of_layer(c["d"], c["ffn"], c["B"])
     return c["layers"] * per_layer
+
+
+# ---------------------------------------------------------------------------
+# start vectors of the multi-Power-Iteration pool (random numbers the method draws)
+# ---------------------------------------------------------------------------
+
+
+def start_vectors(B: int, m: int, seed: int) -> np.ndarray:
+    """(B, m) float32 N(0,1) start vectors, one column per pool member."""
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((B, m)).astype(np.float32)
