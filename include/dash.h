@@ -44,7 +44,10 @@ typedef enum {
 } dash_status;
 
 typedef enum { DASH_NEWTON_DB = 0, DASH_CHEBYSHEV = 1 } dash_method;
-typedef enum { DASH_SCALE_FROBENIUS = 0, DASH_SCALE_TRACE = 1, DASH_SCALE_NONE = 2 } dash_scaling;
+/* DASH_SCALE_POWER_ITERATION: s = 2 * lambda_PI, the multi-Power-Iteration estimate of
+ * Sections 3.4 and 3.5 (configure it with dash_set_power_iteration first). */
+typedef enum { DASH_SCALE_FROBENIUS = 0, DASH_SCALE_TRACE = 1, DASH_SCALE_NONE = 2,
+               DASH_SCALE_POWER_ITERATION = 3 } dash_scaling;
 /* DASH_FP32: fp32 MFMA operands.  DASH_BF16_ACC32: iterates stored in fp32, every matmul
  * operand rounded to bf16 (round to nearest even), fp32 accumulation -- the recipe of
  * Appendix A.3 with bf16 in place of fp16, applied to both methods. */
@@ -107,6 +110,19 @@ dash_status dash_get_stats(dash_ctx* ctx, dash_stats* out /* host */);
  * compute full products. */
 dash_status dash_set_symmetric(dash_ctx* ctx, int on);
 
+/* Multi-Power-Iteration scaling (Sections 3.4, 3.5).  For every block, with A_d = A + eps I:
+ *   V_0 = start vectors, columns scaled to unit length; for t = 1..sweeps: W = A_d V_{t-1},
+ *   q_j = v_j . w_j (Rayleigh quotient of the unit vector v_j), V_t = W with unit columns;
+ *   lambda_PI = max_j q_j of the last sweep; the block is scaled by s = 2 * lambda_PI.
+ * pool: number of start vectors, 1..32 (the paper uses 16 or 32).  sweeps >= 1: passes over
+ * the block.  start_vectors: DEVICE pointer, row-major [rows][pool] fp32, rows >= the B of
+ * later calls (their first B rows are used), shared by all blocks; drawn by the caller
+ * (e.g. seeded N(0,1)); must stay valid while the setting is in use.  The block is read
+ * through its rows as if symmetric.  Since R_A(v) <= lambda_max, s can be below lambda_max
+ * when the pool has not converged: Newton-DB still converges as long as lambda_max < 2 s
+ * (its scalar map converges on (0, 3)), otherwise it diverges and the block is flagged. */
+dash_status dash_set_power_iteration(dash_ctx* ctx, int pool, int sweeps, const float* start_vectors, int rows);
+
 /* ---- the batched matmul primitive (the paper's `bmm`, Sections 3.1 and 4.1) ------ */
 
 /* C_i <- alpha * op(A_i) * op(B_i) + beta * D_i + gamma * I   for i in [0, N).
@@ -128,8 +144,8 @@ dash_status dash_accumulate_factors(dash_ctx* ctx, const float* G, float* L, flo
 
 /* ---- Section 3.4 scaling --------------------------------------------------------- */
 
-/* s_i = ||A_i + eps I||_F (Frobenius), tr(A_i + eps I) (trace) or 1 (none).
- * A: dev const [N][B][B]; s_out: dev [N]. */
+/* s_i = ||A_i + eps I||_F (Frobenius), tr(A_i + eps I) (trace), 1 (none) or 2 lambda_PI
+ * (power iteration).  A: dev const [N][B][B]; s_out: dev [N].  Needs a workspace. */
 dash_status dash_block_norms(dash_ctx* ctx, const float* A, int64_t N, int B, float eps,
                              dash_scaling scaling, float* s_out);
 

@@ -17,11 +17,12 @@ LIB_PATH = os.path.join(HERE, "libdash.so")
 # enums of dash.h
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 NEWTON_DB, CHEBYSHEV = 0, 1
-SCALE_FROBENIUS, SCALE_TRACE, SCALE_NONE = 0, 1, 2
+SCALE_FROBENIUS, SCALE_TRACE, SCALE_NONE, SCALE_POWER_ITERATION = 0, 1, 2, 3
 FP32, BF16_ACC32 = 0, 1
 
 _METHODS = {"newton_db": NEWTON_DB, "ndb": NEWTON_DB, "chebyshev": CHEBYSHEV, "cheb": CHEBYSHEV}
-_SCALINGS = {"frobenius": SCALE_FROBENIUS, "trace": SCALE_TRACE, "none": SCALE_NONE}
+_SCALINGS = {"frobenius": SCALE_FROBENIUS, "trace": SCALE_TRACE, "none": SCALE_NONE,
+             "power_iteration": SCALE_POWER_ITERATION, "pi": SCALE_POWER_ITERATION}
 _PRECISIONS = {"fp32": FP32, "bf16": BF16_ACC32}
 
 
@@ -76,6 +77,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_reset_stats.argtypes = [vp]
     lib.dash_set_timing.argtypes = [vp, i32]
     lib.dash_set_symmetric.argtypes = [vp, i32]
+    lib.dash_set_power_iteration.argtypes = [vp, i32, i32, vp, i32]
     lib.dash_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     lib.dash_gemm_batched.argtypes = [vp, i32, i32, vp, vp, vp, vp, i64, i32, f32, f32, f32, i32]
     lib.dash_accumulate_factors.argtypes = [vp, vp, vp, vp, i64, i32, f32, f32]
@@ -87,7 +89,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_graft_update.argtypes = [vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, vp]
     lib.dash_step.argtypes = [vp, C.POINTER(_StepArgs)]
     for name in ("dash_create", "dash_destroy", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
-                 "dash_set_symmetric",
+                 "dash_set_symmetric", "dash_set_power_iteration",
                  "dash_get_stats", "dash_gemm_batched", "dash_accumulate_factors", "dash_block_norms",
                  "dash_inverse_root", "dash_chebyshev_fit", "dash_precondition", "dash_graft_update", "dash_step"):
         getattr(lib, name).restype = C.c_int
@@ -199,6 +201,16 @@ class Dash:
                     variant_block_products=list(s.variant_block_products), variant_ms=list(s.variant_ms),
                     matmul_flops=s.matmul_flops, variant_flops=list(s.variant_flops))
 
+    def set_power_iteration(self, start_vectors, sweeps: int):
+        """Configures multi-Power-Iteration scaling: start_vectors is a contiguous float32 device
+        tensor [rows, pool]; it is kept alive by this object."""
+        torch = self._torch
+        v = start_vectors
+        if not (isinstance(v, torch.Tensor) and v.is_cuda and v.dtype == torch.float32 and v.is_contiguous() and v.dim() == 2):
+            raise DashError(ERR_INVALID_ARG, "start_vectors: need a contiguous float32 device tensor [rows, pool]")
+        self._pi_v0 = v
+        self._check(self.lib.dash_set_power_iteration(self.h, v.shape[1], sweeps, C.c_void_p(v.data_ptr()), v.shape[0]))
+
     def set_symmetric(self, on: bool):
         """Symmetric mode of the library (see dash_set_symmetric in dash.h); default on."""
         self._check(self.lib.dash_set_symmetric(self.h, 1 if on else 0))
@@ -229,7 +241,7 @@ class Dash:
         n, b = A.shape[0], A.shape[1]
         if out is None:
             out = torch.empty(n, dtype=torch.float32, device=self.device)
-        self.ensure_workspace(1, b)
+        self.ensure_workspace(max(n, 1), b, "chebyshev")
         self._check(self.lib.dash_block_norms(self.h, self._stack(A, "A"), n, b, eps, _enum(_SCALINGS, scaling),
                                               self._vec(out, "s_out", n, torch.float32)))
         return out

@@ -37,6 +37,9 @@ struct dash_ctx {
     double var_flops[4] = {0, 0, 0, 0};
     // products that are symmetric in exact arithmetic compute only their upper triangle of tiles
     bool symmetric = true;
+    // multi-Power-Iteration scaling: pool size, sweeps, start vectors [pi_rows][pi_pool] on the device
+    int pi_pool = 0, pi_sweeps = 0, pi_rows = 0;
+    const float* pi_v0 = nullptr;
 };
 
 namespace {
@@ -77,6 +80,12 @@ bool overlap(const void* a, const void* b, size_t bytes) {
     return x < y + bytes && y < x + bytes;
 }
 
+// per-block scratch of the scaling step: slab partials, s, 1/s, s^(-1/p), and the pool
+// vectors / products / quotients of the multi-Power-Iteration
+size_t scale_scratch_bytes(int B) {
+    return SCALARS_PER_BLOCK + (power_iteration_bytes_per_block(B) + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN;
+}
+
 // fp32 and bf16 [B][B] buffers per block each method keeps in the workspace:
 //   fp32 path: Newton-DB 5 fp32 (Y, Z ping-pong, E), Clenshaw 3 fp32 (S and two rotating B_k);
 //   bf16 path: Newton-DB 5 bf16 (same roles) + 1 fp32 (the Y handed from call 1 to call 2),
@@ -92,7 +101,7 @@ int bf16_buffers(dash_method m, dash_precision prec) {
 
 size_t per_block_bytes(int B, dash_method m, dash_precision prec) {
     size_t mat = (size_t)B * B * sizeof(float);
-    return (size_t)f32_buffers(m, prec) * mat + (size_t)bf16_buffers(m, prec) * (mat / 2) + SCALARS_PER_BLOCK;
+    return (size_t)f32_buffers(m, prec) * mat + (size_t)bf16_buffers(m, prec) * (mat / 2) + scale_scratch_bytes(B);
 }
 
 // ---- matmul launch with statistics / optional event timing ------------------------------
@@ -190,6 +199,39 @@ struct Carve {
         return r;
     }
 };
+
+// ---- scaling step (paper Sections 3.4, 3.5) on one chunk -----------------------------------
+struct ScaleScratch {
+    float *partial, *s, *inv_s, *unscale, *piV, *piW, *piq;
+    bool carve(Carve& cv, int64_t nb, int B) {
+        partial = (float*)cv.take((size_t)nb * norm_slabs(B) * sizeof(float));
+        s = (float*)cv.take((size_t)nb * sizeof(float));
+        inv_s = (float*)cv.take((size_t)nb * sizeof(float));
+        unscale = (float*)cv.take((size_t)nb * sizeof(float));
+        piV = (float*)cv.take((size_t)nb * B * 32 * sizeof(float));
+        piW = (float*)cv.take((size_t)nb * B * 32 * sizeof(float));
+        piq = (float*)cv.take((size_t)nb * 32 * sizeof(float));
+        return partial && s && inv_s && unscale && piV && piW && piq;
+    }
+};
+
+// s_b (to s_dst), 1/s_b and s_b^(-1/p) for the nb blocks at A
+dash_status compute_scales(dash_ctx* c, const float* A, int64_t nb, int B, float eps, dash_scaling scaling, int p,
+                           ScaleScratch& sc, float* s_dst) {
+    hipStream_t st = c->stream;
+    if (scaling == DASH_SCALE_POWER_ITERATION) {
+        if (!c->pi_v0 || c->pi_pool < 1 || c->pi_sweeps < 1)
+            return fail(c, DASH_ERR_INVALID_ARG, "power-iteration scaling needs dash_set_power_iteration first");
+        if (c->pi_rows < B)
+            return fail(c, DASH_ERR_INVALID_ARG, "start vectors have %d rows, blocks have %d", c->pi_rows, B);
+        HIP_TRY(c, launch_power_iteration(A, nb, B, eps, c->pi_v0, c->pi_pool, c->pi_sweeps, p, sc.piV, sc.piW, sc.piq,
+                                          s_dst, sc.inv_s, sc.unscale, st));
+        return DASH_OK;
+    }
+    if (scaling != DASH_SCALE_NONE) HIP_TRY(c, launch_norm_partials(A, nb, B, eps, (int)scaling, sc.partial, st));
+    HIP_TRY(c, launch_finalize_scale(sc.partial, nb, norm_slabs(B), (int)scaling, p, s_dst, sc.inv_s, sc.unscale, st));
+    return DASH_OK;
+}
 
 // ---- Newton-DB on one chunk (paper Section 3.3) -----------------------------------------
 // Symmetric mode touches only the residual product Z Y of E = 1.5 I - 0.5 Z Y.  The updates
@@ -475,6 +517,15 @@ dash_status dash_set_symmetric(dash_ctx* c, int on) {
     return DASH_OK;
 }
 
+dash_status dash_set_power_iteration(dash_ctx* c, int pool, int sweeps, const float* start_vectors, int rows) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (pool < 1 || pool > 32) return fail(c, DASH_ERR_INVALID_ARG, "pool must be in 1..32 (got %d)", pool);
+    if (sweeps < 1) return fail(c, DASH_ERR_INVALID_ARG, "sweeps must be >= 1");
+    if (!start_vectors || rows < 1) return fail(c, DASH_ERR_INVALID_ARG, "start vectors missing");
+    c->pi_pool = pool; c->pi_sweeps = sweeps; c->pi_v0 = start_vectors; c->pi_rows = rows;
+    return DASH_OK;
+}
+
 dash_status dash_get_stats(dash_ctx* c, dash_stats* out) {
     if (!c || !out) return DASH_ERR_INVALID_ARG;
     DASH_TRY(collect_events(c));
@@ -546,20 +597,21 @@ dash_status dash_block_norms(dash_ctx* c, const float* A, int64_t N, int B, floa
                              float* s_out) {
     if (!c) return DASH_ERR_INVALID_ARG;
     if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64");
-    if ((int)scaling < 0 || (int)scaling > 2) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
+    if ((int)scaling < 0 || (int)scaling > 3) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
     if (N == 0) return DASH_OK;
     if (!A || !s_out) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     HIP_TRY(c, hipSetDevice(c->device));
-    const int P = norm_slabs(B);
-    const size_t per = SCALARS_PER_BLOCK;
-    if (!c->ws || c->ws_bytes < per) return fail(c, DASH_ERR_WORKSPACE, "workspace needed (%zu bytes per block)", per);
-    const int64_t chunk = (int64_t)(c->ws_bytes / per);
+    const size_t per = scale_scratch_bytes(B), slack = 4 * WS_ALIGN * 16;
+    if (!c->ws || c->ws_bytes < per + slack)
+        return fail(c, DASH_ERR_WORKSPACE, "workspace holds %zu bytes, one block needs %zu", c->ws_bytes, per + slack);
+    int64_t chunk = (int64_t)((c->ws_bytes - slack) / per);
+    if (chunk > N) chunk = N;
     for (int64_t b0 = 0; b0 < N; b0 += chunk) {
         const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
-        float* partial = (float*)c->ws;
-        if (scaling != DASH_SCALE_NONE)
-            HIP_TRY(c, launch_norm_partials(A + (size_t)b0 * B * B, nb, B, eps, (int)scaling, partial, c->stream));
-        HIP_TRY(c, launch_finalize_scale(partial, nb, P, (int)scaling, 2, s_out + b0, nullptr, nullptr, c->stream));
+        Carve cv{c->ws, c->ws + c->ws_bytes};
+        ScaleScratch sc;
+        if (!sc.carve(cv, nb, B)) return fail(c, DASH_ERR_WORKSPACE, "internal: workspace carve failed");
+        DASH_TRY(compute_scales(c, A + (size_t)b0 * B * B, nb, B, eps, scaling, 2, sc, s_out + b0));
     }
     return DASH_OK;
 }
@@ -592,7 +644,7 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64 (N=%lld B=%d)", (long long)N, B);
     if (p != 2 && p != 4) return fail(c, DASH_ERR_INVALID_ARG, "p must be 2 or 4 (got %d)", p);
     if (method != DASH_NEWTON_DB && method != DASH_CHEBYSHEV) return fail(c, DASH_ERR_INVALID_ARG, "bad method");
-    if ((int)scaling < 0 || (int)scaling > 2) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
+    if ((int)scaling < 0 || (int)scaling > 3) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
     if (precision != DASH_FP32 && precision != DASH_BF16_ACC32) return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
     if (method == DASH_NEWTON_DB && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Newton-DB needs iters >= 1");
     if (method == DASH_CHEBYSHEV) {
@@ -622,15 +674,15 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     for (int64_t b0 = 0; b0 < N; b0 += chunk) {
         const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
         Carve cv{c->ws, c->ws + c->ws_bytes};
-        float* partial = (float*)cv.take((size_t)nb * P * sizeof(float));
-        float* s = (float*)cv.take((size_t)nb * sizeof(float));
-        float* inv_s = (float*)cv.take((size_t)nb * sizeof(float));
-        float* unscale = (float*)cv.take((size_t)nb * sizeof(float));
+        ScaleScratch sc;
+        const bool sc_ok = sc.carve(cv, nb, B);
+        float* inv_s = sc.inv_s;
+        float* unscale = sc.unscale;
         float* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
         bf16_t* hbuf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
         for (int i = 0; i < nbuf; ++i) buf[i] = (float*)cv.take((size_t)nb * mat * sizeof(float));
         for (int i = 0; i < nhbuf; ++i) hbuf[i] = (bf16_t*)cv.take((size_t)nb * mat * sizeof(bf16_t));
-        if (!partial || !s || !inv_s || !unscale || !buf[nbuf - 1] || (nhbuf && !hbuf[nhbuf - 1]))
+        if (!sc_ok || !buf[nbuf - 1] || (nhbuf && !hbuf[nhbuf - 1]))
             return fail(c, DASH_ERR_WORKSPACE, "internal: workspace carve failed");
 
         const float* Ac = A + (size_t)b0 * mat;
@@ -638,9 +690,8 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         int32_t* nf = nonfinite_out ? nonfinite_out + b0 : nullptr;
         if (nf) HIP_TRY(c, launch_fill_i32(nf, nb, 0, st));
 
-        // Section 3.4: s = ||A + eps I||_F (or trace), kept with 1/s and s^(-1/p)
-        if (scaling != DASH_SCALE_NONE) HIP_TRY(c, launch_norm_partials(Ac, nb, B, eps, (int)scaling, partial, st));
-        HIP_TRY(c, launch_finalize_scale(partial, nb, P, (int)scaling, p, scale_out ? scale_out + b0 : s, inv_s, unscale, st));
+        // Sections 3.4, 3.5: s = ||A + eps I||_F, trace, or 2 lambda_PI, kept with 1/s and s^(-1/p)
+        DASH_TRY(compute_scales(c, Ac, nb, B, eps, scaling, p, sc, scale_out ? scale_out + b0 : sc.s));
 
         if (lowp && method == DASH_NEWTON_DB) {
             int idx = -1;

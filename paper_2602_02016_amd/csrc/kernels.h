@@ -60,6 +60,14 @@ hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps
                               float a1, float g1, float* out1, float a2, float g2, float* out2,
                               void* h1, void* h2, int32_t* nonfinite, hipStream_t stream);
 
+// Multi-Power-Iteration scaling (power_iteration.hip): s_b = 2 * lambda_PI(A_b + eps I) from
+// `sweeps` passes over the block with a pool of `pool` (<= 32) start vectors V0 ([B][pool]
+// row-major, shared by all blocks).  V, W: scratch [n][B][32] each; q: scratch [n][32].
+size_t power_iteration_bytes_per_block(int B);
+hipError_t launch_power_iteration(const float* A, int64_t nblocks, int B, float eps, const float* V0, int pool,
+                                  int sweeps, int p, float* V, float* W, float* q, float* s, float* inv_s,
+                                  float* unscale, hipStream_t stream);
+
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
 
 // grafting: Acc <- beta_g Acc + (1-beta_g) G.G ; partial sums of P^2 and U^2 per slab
