@@ -43,7 +43,7 @@ typedef enum {
     DASH_ERR_HIP = 4          /* a HIP runtime call failed (no device, launch error, ...) */
 } dash_status;
 
-typedef enum { DASH_NEWTON_DB = 0, DASH_CHEBYSHEV = 1 } dash_method;
+typedef enum { DASH_NEWTON_DB = 0, DASH_CHEBYSHEV = 1, DASH_COUPLED_NEWTON = 2 } dash_method;
 /* DASH_SCALE_POWER_ITERATION: s = 2 * lambda_PI, the multi-Power-Iteration estimate of
  * Sections 3.4 and 3.5 (configure it with dash_set_power_iteration first). */
 typedef enum { DASH_SCALE_FROBENIUS = 0, DASH_SCALE_TRACE = 1, DASH_SCALE_NONE = 2,
@@ -162,6 +162,11 @@ dash_status dash_block_norms(dash_ctx* ctx, const float* A, int64_t N, int B, fl
  *          doubles (c_0..c_d, e.g. from dash_chebyshev_fit); the scaled block is mapped
  *          with S = (2 A_s - (a+b) I) / (b-a) for [a,b] = [cheb_a, cheb_b], then the
  *          reduced Clenshaw recurrence (d-1 matmuls) is evaluated.
+ *   DASH_COUPLED_NEWTON (Section 3.2): X_0 = I/c, M_0 = A_s/c^p, C_k = (1+1/p) I - M_k/p,
+ *          X_{k+1} = X_k C_k, M_{k+1} = C_k^p M_k with c = (1+p)^(-1/p); `iters` >= 1
+ *          iterations; fp32 operands only (DASH_ERR_UNSUPPORTED otherwise).  The scale must
+ *          be strictly above lambda_max (at a scaled eigenvalue of exactly 1 the iteration
+ *          is stuck at 0); Frobenius, trace and 2 lambda_PI are.
  *   A: dev const [N][B][B]; X: dev out [N][B][B], must not overlap A.
  *   scale_out: dev [N] receiving s_i, or NULL.  nonfinite_out: dev int32 [N], set to 1
  *   for every block whose result holds a NaN/Inf and to 0 otherwise, or NULL.

@@ -90,12 +90,14 @@ size_t scale_scratch_bytes(int B) {
 //   fp32 path: Newton-DB 5 fp32 (Y, Z ping-pong, E), Clenshaw 3 fp32 (S and two rotating B_k);
 //   bf16 path: Newton-DB 5 bf16 (same roles) + 1 fp32 (the Y handed from call 1 to call 2),
 //              Clenshaw 2 fp32 (rotating B_k) + 3 bf16 (S and the operand copies of B_k).
+//   Coupled-Newton (fp32 only): 9 fp32 (X', M ping-pong, three C, C^2, C^4).
 int f32_buffers(dash_method m, dash_precision prec) {
+    if (m == DASH_COUPLED_NEWTON) return 9;
     if (prec == DASH_BF16_ACC32) return m == DASH_NEWTON_DB ? 1 : 2;
     return m == DASH_NEWTON_DB ? 5 : 3;
 }
 int bf16_buffers(dash_method m, dash_precision prec) {
-    if (prec != DASH_BF16_ACC32) return 0;
+    if (prec != DASH_BF16_ACC32 || m == DASH_COUPLED_NEWTON) return 0;
     return m == DASH_NEWTON_DB ? 5 : 3;
 }
 
@@ -153,7 +155,7 @@ dash_status collect_events(dash_ctx* c) {
 GemmProblem problem(const float* A, const float* B, const float* D, float* C, const float* mult, float alpha,
                     float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.mult = mult;
+    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.C2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
@@ -162,7 +164,7 @@ GemmProblem problem(const float* A, const float* B, const float* D, float* C, co
 GemmProblem problem_h(const bf16_t* Ah, const bf16_t* Bh, const float* D, float* C, bf16_t* Ch, const float* mult,
                       float alpha, float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.mult = mult;
+    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.C2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
@@ -408,6 +410,59 @@ dash_status clenshaw_chunk_bf16(dash_ctx* c, float* fb[2], bf16_t* hb[3], const 
     return gemm1(c, problem_h(Sh, h1, b2, X, nullptr, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite, 1, true);
 }
 
+// ---- Coupled-Newton on one chunk (paper Section 3.2) ----------------------------------------
+//   X_0 = I/c, M_0 = A_s/c^p, C_k = (1+1/p) I - M_k/p, X_{k+1} = X_k C_k, M_{k+1} = C_k^p M_k,
+//   c = (1+p)^(-1/p) so that M_0 = (p+1) A_s.
+// The constant 1/c is carried in the final multiplier (X_k = (1/c) C_0 ... C_{k-1}), so the first
+// update X_1 needs no product; the last iteration computes only X (nobody reads its M), so k
+// iterations cost (k-1) * (3 or 4) products against the paper's k * (3 or 4).  C_{k+1} is written by
+// the epilogue of the M product.  Every product is computed in full whatever the symmetric mode says:
+// mirroring even only the powers C^2, C^4 makes X drift after convergence (measured at kappa = 1e4:
+// 3.7e-3 after 40 iterations, 9e-3 after 80, against a steady 9.4e-5 with full products).
+// buf: 9 fp32 buffers (X' x2, M x2, C x3, C^2, C^4).  s_b^(-1/p) / c is applied in the last epilogue.  C_k lives in Cb[k % 3]: the launch that reads C_k (and, for k = 1, C_0 in its role as X'_1)
+// writes C_{k+1} into the third buffer.
+dash_status cn_chunk(dash_ctx* c, float* buf[9], const float* A, float* X, int64_t n, int B, int p, int iters,
+                     float eps, const float* inv_s, const float* unscale, int32_t* nonfinite) {
+    hipStream_t st = c->stream;
+    const float a = 1.f + 1.f / p, ip = 1.f / p;
+    const float inv_c = (float)std::pow(1.0 + p, 1.0 / p);      // 1/c with c = (1+p)^(-1/p)
+    float* Xb[2] = {buf[0], buf[1]};
+    float* Mb[2] = {buf[2], buf[3]};
+    float* Cb[3] = {buf[4], buf[5], buf[6]};
+    float *P2 = buf[7], *P4 = buf[8];
+    // M_0 = (p+1) (A + eps I)/s ; C_0 = a I - M_0/p
+    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, Mb[0], -ip, a, Cb[0], nullptr, nullptr,
+                                  nullptr, st));
+    if (iters == 1) {   // X = s^(-1/p) (1/c) C_0, no product
+        HIP_TRY(c, launch_scale_shift(Cb[0], n, B, 0.f, unscale, inv_c, 0.f, X, 0.f, 0.f, nullptr, nullptr, nullptr,
+                                      nonfinite, st));
+        return DASH_OK;
+    }
+    const float* Xcur = Cb[0];          // X'_1 = C_0
+    for (int k = 0; k + 1 < iters; ++k) {
+        float* Ck = Cb[k % 3];
+        // C_k^p by repeated squaring
+        DASH_TRY(gemm1(c, problem(Ck, Ck, nullptr, P2, nullptr, 1.f, 0.f, 0.f), n, B));
+        const float* Pp = P2;
+        if (p == 4) {
+            DASH_TRY(gemm1(c, problem(P2, P2, nullptr, P4, nullptr, 1.f, 0.f, 0.f), n, B));
+            Pp = P4;
+        }
+        // M_{k+1} = C_k^p M_k with C_{k+1} = a I - M_{k+1}/p from the same epilogue
+        GemmProblem pm = problem(Pp, Mb[k % 2], nullptr, Mb[(k + 1) % 2], nullptr, 1.f, 0.f, 0.f);
+        pm.C2 = Cb[(k + 1) % 3]; pm.a2 = -ip; pm.g2 = a;
+        if (k == 0) {
+            DASH_TRY(gemm1(c, pm, n, B));                       // X'_1 = C_0 needs no product
+        } else {
+            float* Xn = Xb[k % 2];                              // X'_{k+1} = X'_k C_k in the same launch
+            DASH_TRY(gemm2(c, pm, problem(Xcur, Ck, nullptr, Xn, nullptr, 1.f, 0.f, 0.f), n, B));
+            Xcur = Xn;
+        }
+    }
+    // last update, un-scaled: X = s^(-1/p) (1/c) X'_{iters-1} C_{iters-1}
+    return gemm1(c, problem(Xcur, Cb[(iters - 1) % 3], nullptr, X, unscale, inv_c, 0.f, 0.f), n, B, nonfinite);
+}
+
 // ---- Clenshaw on one chunk (paper Appendix A.2, reduced form, d-1 products) --------------
 dash_status clenshaw_chunk(dash_ctx* c, float* buf[3], const float* A, float* X, int64_t n, int B, int d,
                            const double* cf, double ca, double cb, float eps, const float* inv_s,
@@ -643,7 +698,9 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     if (!c) return DASH_ERR_INVALID_ARG;
     if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64 (N=%lld B=%d)", (long long)N, B);
     if (p != 2 && p != 4) return fail(c, DASH_ERR_INVALID_ARG, "p must be 2 or 4 (got %d)", p);
-    if (method != DASH_NEWTON_DB && method != DASH_CHEBYSHEV) return fail(c, DASH_ERR_INVALID_ARG, "bad method");
+    if (method != DASH_NEWTON_DB && method != DASH_CHEBYSHEV && method != DASH_COUPLED_NEWTON)
+        return fail(c, DASH_ERR_INVALID_ARG, "bad method");
+    if (method == DASH_COUPLED_NEWTON && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Coupled-Newton needs iters >= 1");
     if ((int)scaling < 0 || (int)scaling > 3) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
     if (precision != DASH_FP32 && precision != DASH_BF16_ACC32) return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
     if (method == DASH_NEWTON_DB && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Newton-DB needs iters >= 1");
@@ -656,6 +713,8 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     if (N == 0) return DASH_OK;
     if (!A || !X) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     if (overlap(A, X, (size_t)N * B * B * sizeof(float))) return fail(c, DASH_ERR_INVALID_ARG, "X overlaps A");
+    if (method == DASH_COUPLED_NEWTON && precision != DASH_FP32)
+        return fail(c, DASH_ERR_UNSUPPORTED, "Coupled-Newton is built for fp32 operands only");
     HIP_TRY(c, hipSetDevice(c->device));
 
     const size_t per = per_block_bytes(B, method, precision);
@@ -678,7 +737,7 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         const bool sc_ok = sc.carve(cv, nb, B);
         float* inv_s = sc.inv_s;
         float* unscale = sc.unscale;
-        float* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+        float* buf[9] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
         bf16_t* hbuf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
         for (int i = 0; i < nbuf; ++i) buf[i] = (float*)cv.take((size_t)nb * mat * sizeof(float));
         for (int i = 0; i < nhbuf; ++i) hbuf[i] = (bf16_t*)cv.take((size_t)nb * mat * sizeof(bf16_t));
@@ -693,7 +752,9 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         // Sections 3.4, 3.5: s = ||A + eps I||_F, trace, or 2 lambda_PI, kept with 1/s and s^(-1/p)
         DASH_TRY(compute_scales(c, Ac, nb, B, eps, scaling, p, sc, scale_out ? scale_out + b0 : sc.s));
 
-        if (lowp && method == DASH_NEWTON_DB) {
+        if (method == DASH_COUPLED_NEWTON) {
+            DASH_TRY(cn_chunk(c, buf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf));
+        } else if (lowp && method == DASH_NEWTON_DB) {
             int idx = -1;
             if (p == 2) {
                 DASH_TRY(ndb_call_bf16(c, hbuf, buf[0], -1, nb, B, iters, false, true, Ac, eps, inv_s, Xc, unscale, nf, &idx));

@@ -214,6 +214,9 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     const float alpha = P.alpha * mult, beta = P.beta * mult, gamma = P.gamma * mult;
     const float* __restrict__ Db = P.D ? P.D + boff : nullptr;
     float* __restrict__ Cb = P.C + boff;
+    // optional second output C2 = a2 * C + g2 * I (Coupled-Newton: M' and C' = (1+1/p) I - M'/p at once)
+    float* __restrict__ C2b = P.C2 ? P.C2 + boff : nullptr;
+    const float a2 = P.a2, g2 = P.g2;
     // symmetric mode: an off-diagonal tile (ti < tj) is also written transposed to (tj, ti).
     // A lane holds four consecutive rows of one column, i.e. four consecutive elements of a
     // row of the transposed tile: one 16-byte store each.
@@ -227,7 +230,7 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int rbase = row0 + wm + 32 * i + 8 * q + 4 * (lane >> 5);
-                v4f out;
+                v4f out, out2;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const int row = rbase + m;
@@ -238,8 +241,15 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
                     bad |= !(fabsf(v) <= 3.0e38f);
                     Cb[off] = v;
                     out[m] = v;
+                    if (C2b) {
+                        out2[m] = a2 * v + (row == col ? g2 : 0.f);
+                        C2b[off] = out2[m];
+                    }
                 }
-                if (mirror) *reinterpret_cast<v4f*>(Cb + (size_t)col * B + rbase) = out;
+                if (mirror) {
+                    *reinterpret_cast<v4f*>(Cb + (size_t)col * B + rbase) = out;
+                    if (C2b) *reinterpret_cast<v4f*>(C2b + (size_t)col * B + rbase) = out2;
+                }
             }
         }
     if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;

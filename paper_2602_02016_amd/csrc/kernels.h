@@ -20,6 +20,8 @@ struct GemmProblem {
     const float* D;
     float* C;
     void* Ch;
+    float* C2;             // fp32 launches only: optional second output a2 * C + g2 * I
+    float a2, g2;
     const float* mult;
     float alpha, beta, gamma;
     int transA, transB;
