@@ -48,10 +48,11 @@ typedef enum { DASH_NEWTON_DB = 0, DASH_CHEBYSHEV = 1, DASH_COUPLED_NEWTON = 2 }
  * Sections 3.4 and 3.5 (configure it with dash_set_power_iteration first). */
 typedef enum { DASH_SCALE_FROBENIUS = 0, DASH_SCALE_TRACE = 1, DASH_SCALE_NONE = 2,
                DASH_SCALE_POWER_ITERATION = 3 } dash_scaling;
-/* DASH_FP32: fp32 MFMA operands.  DASH_BF16_ACC32: iterates stored in fp32, every matmul
- * operand rounded to bf16 (round to nearest even), fp32 accumulation -- the recipe of
- * Appendix A.3 with bf16 in place of fp16, applied to both methods. */
-typedef enum { DASH_FP32 = 0, DASH_BF16_ACC32 = 1 } dash_precision;
+/* DASH_FP32: fp32 MFMA operands.  DASH_FP16_ACC32 / DASH_BF16_ACC32: the recipe of
+ * Appendix A.3 -- iterates kept in fp32, every matmul operand rounded to fp16 / bf16 (round to
+ * nearest even), fp32 accumulation -- applied to Clenshaw (as in the paper) and to Newton-DB
+ * (which the paper reports unstable in half precision). */
+typedef enum { DASH_FP32 = 0, DASH_BF16_ACC32 = 1, DASH_FP16_ACC32 = 2 } dash_precision;
 
 /* ---- context ------------------------------------------------------------------- */
 
@@ -164,7 +165,8 @@ dash_status dash_block_norms(dash_ctx* ctx, const float* A, int64_t N, int B, fl
  *          reduced Clenshaw recurrence (d-1 matmuls) is evaluated.
  *   DASH_COUPLED_NEWTON (Section 3.2): X_0 = I/c, M_0 = A_s/c^p, C_k = (1+1/p) I - M_k/p,
  *          X_{k+1} = X_k C_k, M_{k+1} = C_k^p M_k with c = (1+p)^(-1/p); `iters` >= 1
- *          iterations; fp32 operands only (DASH_ERR_UNSUPPORTED otherwise).  The scale must
+ *          iterations; fp32, fp16 or bf16 operands (the paper runs it in fp32 and fp16 and
+ *          reports that bf16 diverges).  The scale must
  *          be strictly above lambda_max (at a scaled eigenvalue of exactly 1 the iteration
  *          is stuck at 0); Frobenius, trace and 2 lambda_PI are.
  *   A: dev const [N][B][B]; X: dev out [N][B][B], must not overlap A.

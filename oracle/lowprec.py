@@ -36,34 +36,92 @@ def round_bf16(x) -> np.ndarray:
     return out.reshape(x32.shape)
 
 
+def round_fp16(x) -> np.ndarray:
+    """Round-to-nearest-even from float32 to IEEE half precision (11 significand bits, with
+    subnormals, overflow to infinity), returned as float32 values."""
+    with np.errstate(over="ignore"):
+        return np.asarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def round_half(x, fmt: str) -> np.ndarray:
+    if fmt == "bf16":
+        return round_bf16(x)
+    if fmt == "fp16":
+        return round_fp16(x)
+    if fmt == "none":
+        return _f32(x)
+    raise ValueError(fmt)
+
+
 def _f32(x):
     return np.asarray(x, dtype=np.float32)
 
 
+def matmul_lowprec(A, B, fmt: str = "bf16") -> np.ndarray:
+    """float32( half(A) @ half(B) ) with the product summed in float64."""
+    a, b = round_half(A, fmt), round_half(B, fmt)
+    with np.errstate(over="ignore", invalid="ignore"):
+        return _f32(a.astype(np.float64) @ b.astype(np.float64))
+
+
 def matmul_bf16(A, B, rounding: bool = True) -> np.ndarray:
-    """float32( bf16(A) @ bf16(B) ) with the product summed in float64."""
-    a = round_bf16(A) if rounding else _f32(A)
-    b = round_bf16(B) if rounding else _f32(B)
-    return _f32(a.astype(np.float64) @ b.astype(np.float64))
+    return matmul_lowprec(A, B, "bf16" if rounding else "none")
 
 
-def ndb_call_lowprec(M32, iters: int, rounding: bool = True):
+def ndb_call_lowprec(M32, iters: int, rounding=True):
     """One Newton-DB call on a float32 matrix M (first update in closed form), every product
-    through matmul_bf16, every linear combination in float32.  Returns float32 (Y, Z)."""
+    through matmul_lowprec, every linear combination in float32.  `rounding` is True (bf16),
+    False (no rounding) or a format name.  Returns float32 (Y, Z)."""
+    fmt = rounding if isinstance(rounding, str) else ("bf16" if rounding else "none")
     n = M32.shape[0]
     I = np.eye(n, dtype=np.float32)
     E = _f32(np.float32(1.5) * I - np.float32(0.5) * M32)
-    Y, Z = matmul_bf16(M32, E, rounding), E
+    Y, Z = matmul_lowprec(M32, E, fmt), E
     for _ in range(iters - 1):
-        E = _f32(np.float32(1.5) * I - np.float32(0.5) * matmul_bf16(Z, Y, rounding))
-        Y, Z = matmul_bf16(Y, E, rounding), matmul_bf16(E, Z, rounding)
+        E = _f32(np.float32(1.5) * I - np.float32(0.5) * matmul_lowprec(Z, Y, fmt))
+        Y, Z = matmul_lowprec(Y, E, fmt), matmul_lowprec(E, Z, fmt)
     return Y, Z
 
 
+def inverse_root_cn_lowprec(A, p: int, iters: int, eps: float = 0.0, scaling: str = "frobenius",
+                            fmt: str = "fp16") -> np.ndarray:
+    """(A + eps I)^(-1/p) by Coupled-Newton (Section 3.2, c = (1+p)^(-1/p)) with half-rounded matmul
+    operands: M_0 = (p+1) A_s, C_k = (1+1/p) I - M_k/p in float32, X_{k+1} = X_k C_k,
+    M_{k+1} = C_k^p M_k (powers by repeated squaring), X un-scaled by s^(-1/p)."""
+    A = np.asarray(A, dtype=np.float32)
+    single = A.ndim == 2
+    if single:
+        A = A[None]
+    X = np.empty(A.shape, dtype=np.float32)
+    n = A.shape[1]
+    I = np.eye(n, dtype=np.float32)
+    a, ip = np.float32(1.0 + 1.0 / p), np.float32(1.0 / p)
+    inv_c = np.float32((1.0 + p) ** (1.0 / p))
+    for i in range(A.shape[0]):
+        Ad = _f32(A[i] + np.float32(eps) * I)
+        s = np.float32(block_scale(Ad.astype(np.float64), scaling))
+        M = _f32(np.float32(p + 1) * (Ad * (np.float32(1.0) / s)))
+        C = _f32(a * I - ip * M)
+        # X_k = (1/c) C_0 C_1 ... C_{k-1}: the scalar 1/c is applied once at the end, so the first
+        # update X_1 = C_0 / c needs no product and no rounding
+        Xk = None
+        for k in range(iters):
+            Xk = C if k == 0 else matmul_lowprec(Xk, C, fmt)        # X_{k+1} = X_k C_k
+            if k + 1 < iters:                                        # the last M is never read
+                P = matmul_lowprec(C, C, fmt)
+                if p == 4:
+                    P = matmul_lowprec(P, P, fmt)
+                M = matmul_lowprec(P, M, fmt)                        # M_{k+1} = C_k^p M_k
+                C = _f32(a * I - ip * M)
+        X[i] = _f32(Xk * (inv_c * np.float32(float(s) ** (-1.0 / p))))
+    return X[0] if single else X
+
+
 def inverse_root_ndb_lowprec(A, p: int, iters: int, eps: float = 0.0, scaling: str = "frobenius",
-                             rounding: bool = True) -> np.ndarray:
-    """(A + eps I)^(-1/p) by Newton-DB with bf16-rounded matmul operands; same damping,
-    scaling, chaining and un-scaling as oracle.newton_db.inverse_root_ndb."""
+                             rounding=True) -> np.ndarray:
+    """(A + eps I)^(-1/p) by Newton-DB with half-rounded matmul operands (bf16 when rounding is
+    True, or the named format); same damping, scaling, chaining and un-scaling as
+    oracle.newton_db.inverse_root_ndb."""
     A = np.asarray(A, dtype=np.float32)
     single = A.ndim == 2
     if single:

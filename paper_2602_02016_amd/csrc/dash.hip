@@ -37,6 +37,7 @@ struct dash_ctx {
     double var_flops[4] = {0, 0, 0, 0};
     // products that are symmetric in exact arithmetic compute only their upper triangle of tiles
     bool symmetric = true;
+    int half_kind = HALF_BF16;      // 16-bit operand format of the call in progress (HALF_BF16 / HALF_FP16)
     // multi-Power-Iteration scaling: pool size, sweeps, start vectors [pi_rows][pi_pool] on the device
     int pi_pool = 0, pi_sweeps = 0, pi_rows = 0;
     const float* pi_v0 = nullptr;
@@ -92,12 +93,13 @@ size_t scale_scratch_bytes(int B) {
 //              Clenshaw 2 fp32 (rotating B_k) + 3 bf16 (S and the operand copies of B_k).
 //   Coupled-Newton (fp32 only): 9 fp32 (X', M ping-pong, three C, C^2, C^4).
 int f32_buffers(dash_method m, dash_precision prec) {
-    if (m == DASH_COUPLED_NEWTON) return 9;
-    if (prec == DASH_BF16_ACC32) return m == DASH_NEWTON_DB ? 1 : 2;
+    if (m == DASH_COUPLED_NEWTON) return prec == DASH_FP32 ? 9 : 0;
+    if (prec != DASH_FP32) return m == DASH_NEWTON_DB ? 1 : 2;
     return m == DASH_NEWTON_DB ? 5 : 3;
 }
 int bf16_buffers(dash_method m, dash_precision prec) {
-    if (prec != DASH_BF16_ACC32 || m == DASH_COUPLED_NEWTON) return 0;
+    if (prec == DASH_FP32) return 0;
+    if (m == DASH_COUPLED_NEWTON) return 9;
     return m == DASH_NEWTON_DB ? 5 : 3;
 }
 
@@ -155,7 +157,7 @@ dash_status collect_events(dash_ctx* c) {
 GemmProblem problem(const float* A, const float* B, const float* D, float* C, const float* mult, float alpha,
                     float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.C2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
+    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.C2 = nullptr; p.C2h = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
@@ -164,7 +166,7 @@ GemmProblem problem(const float* A, const float* B, const float* D, float* C, co
 GemmProblem problem_h(const bf16_t* Ah, const bf16_t* Bh, const float* D, float* C, bf16_t* Ch, const float* mult,
                       float alpha, float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.C2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
+    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.C2 = nullptr; p.C2h = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
@@ -175,7 +177,7 @@ dash_status gemm1(dash_ctx* c, const GemmProblem& p, int64_t n, int B, int32_t* 
                   bool sym = false) {
     GemmLaunch g;
     memset(&g, 0, sizeof(g));
-    g.prob[0] = p; g.prob[1] = p; g.nprob = 1; g.B = B; g.nblocks = n; g.nonfinite = nonfinite; g.bf16 = bf16;
+    g.prob[0] = p; g.prob[1] = p; g.nprob = 1; g.B = B; g.nblocks = n; g.nonfinite = nonfinite; g.half = bf16 ? c->half_kind : HALF_NONE;
     g.sym = (sym && c->symmetric) ? 1 : 0;
     return run_gemm(c, g);
 }
@@ -184,7 +186,7 @@ dash_status gemm2(dash_ctx* c, const GemmProblem& p0, const GemmProblem& p1, int
                   bool sym = false) {
     GemmLaunch g;
     memset(&g, 0, sizeof(g));
-    g.prob[0] = p0; g.prob[1] = p1; g.nprob = 2; g.B = B; g.nblocks = n; g.nonfinite = nullptr; g.bf16 = bf16;
+    g.prob[0] = p0; g.prob[1] = p1; g.nprob = 2; g.B = B; g.nblocks = n; g.nonfinite = nullptr; g.half = bf16 ? c->half_kind : HALF_NONE;
     g.sym = (sym && c->symmetric) ? 1 : 0;
     return run_gemm(c, g);
 }
@@ -328,19 +330,19 @@ dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], float* fy, int mi, int64_t
         // M = (A + eps I)/s -> bf16 hb[y]; E_1 = 1.5 I - 0.5 M (fp32) -> bf16 hb[z]; when E_1 itself is
         // the result (iters == 1, p == 2) its fp32 value goes to fy
         HIP_TRY(c, launch_scale_shift(A_in, n, B, eps, inv_s, 1.f, 0.f, nullptr, -0.5f, 1.5f,
-                                      (iters == 1 && !keepY) ? fy : nullptr, hb[y], hb[z], nullptr, st));
+                                      (iters == 1 && !keepY) ? fy : nullptr, hb[y], hb[z], nullptr, st, c->half_kind));
     } else {
         used[mi] = true; y = mi; z = grab();
         if (iters == 1 && !keepY && final_out) {
             // X = unscale * (1.5 I - 0.5 Y): two elementwise passes, no product
             HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, nullptr, -0.5f, 1.5f, final_out, 0.f, 0.f, nullptr, nullptr,
-                                          nullptr, nullptr, st));
+                                          nullptr, nullptr, st, c->half_kind));
             HIP_TRY(c, launch_scale_shift(final_out, n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr,
-                                          nullptr, nullptr, nonfinite, st));
+                                          nullptr, nullptr, nonfinite, st, c->half_kind));
             return DASH_OK;
         }
         HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, nullptr, -0.5f, 1.5f, nullptr, 0.f, 0.f, nullptr, hb[z], nullptr,
-                                      nullptr, st));
+                                      nullptr, st, c->half_kind));
     }
     if (iters == 1) {
         if (keepY) {
@@ -349,7 +351,7 @@ dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], float* fy, int mi, int64_t
             *out_idx = y1;
         } else if (final_out) {
             HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nullptr,
-                                          nullptr, nonfinite, st));
+                                          nullptr, nonfinite, st, c->half_kind));
         } else {
             *out_idx = z;
         }
@@ -397,7 +399,7 @@ dash_status clenshaw_chunk_bf16(dash_ctx* c, float* fb[2], bf16_t* hb[3], const 
     float* b2 = fb[1]; bf16_t* h2 = hb[2];   // B_{k+2}
     const float m1 = (float)(2.0 / (cb - ca)), m0 = (float)(-(ca + cb) / (cb - ca));
     HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, m1, m0, nullptr, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
-                                  Sh, h1, nullptr, st));
+                                  Sh, h1, nullptr, st, c->half_kind));
     if (d == 2)
         return gemm1(c, problem_h(Sh, h1, nullptr, X, nullptr, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B,
                      nonfinite, 1, true);
@@ -461,6 +463,52 @@ dash_status cn_chunk(dash_ctx* c, float* buf[9], const float* A, float* X, int64
     }
     // last update, un-scaled: X = s^(-1/p) (1/c) X'_{iters-1} C_{iters-1}
     return gemm1(c, problem(Xcur, Cb[(iters - 1) % 3], nullptr, X, unscale, inv_c, 0.f, 0.f), n, B, nonfinite);
+}
+
+// Coupled-Newton with 16-bit operands (the paper's fastest configuration is Coupled-Newton in fp16,
+// Sections 2.3 and 5): every iterate is read only as a matmul operand (C_{k+1} is formed from the fp32
+// accumulator of the M product before rounding), so all nine buffers hold 16-bit values; accumulation,
+// the epilogue arithmetic and the result X are fp32.
+dash_status cn_chunk_half(dash_ctx* c, bf16_t* hb[9], const float* A, float* X, int64_t n, int B, int p, int iters,
+                          float eps, const float* inv_s, const float* unscale, int32_t* nonfinite, float* tmp_f32) {
+    hipStream_t st = c->stream;
+    const float a = 1.f + 1.f / p, ip = 1.f / p;
+    const float inv_c = (float)std::pow(1.0 + p, 1.0 / p);
+    bf16_t* Xb[2] = {hb[0], hb[1]};
+    bf16_t* Mb[2] = {hb[2], hb[3]};
+    bf16_t* Cb[3] = {hb[4], hb[5], hb[6]};
+    bf16_t *P2 = hb[7], *P4 = hb[8];
+    if (iters == 1) {   // X = s^(-1/p) (1/c) C_0 in fp32, no product: C_0 via the fp32 temporary X itself
+        HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, X, nullptr, nullptr,
+                                      nullptr, st, c->half_kind));
+        HIP_TRY(c, launch_scale_shift(X, n, B, 0.f, unscale, inv_c, 0.f, X, 0.f, 0.f, nullptr, nullptr, nullptr,
+                                      nonfinite, st, c->half_kind));
+        (void)tmp_f32;
+        return DASH_OK;
+    }
+    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, nullptr, Mb[0], Cb[0],
+                                  nullptr, st, c->half_kind));
+    const bf16_t* Xcur = Cb[0];
+    for (int k = 0; k + 1 < iters; ++k) {
+        bf16_t* Ck = Cb[k % 3];
+        DASH_TRY(gemm1(c, problem_h(Ck, Ck, nullptr, nullptr, P2, nullptr, 1.f, 0.f, 0.f), n, B, nullptr, 1));
+        const bf16_t* Pp = P2;
+        if (p == 4) {
+            DASH_TRY(gemm1(c, problem_h(P2, P2, nullptr, nullptr, P4, nullptr, 1.f, 0.f, 0.f), n, B, nullptr, 1));
+            Pp = P4;
+        }
+        GemmProblem pm = problem_h(Pp, Mb[k % 2], nullptr, nullptr, Mb[(k + 1) % 2], nullptr, 1.f, 0.f, 0.f);
+        pm.C2h = Cb[(k + 1) % 3]; pm.a2 = -ip; pm.g2 = a;
+        if (k == 0) {
+            DASH_TRY(gemm1(c, pm, n, B, nullptr, 1));
+        } else {
+            bf16_t* Xn = Xb[k % 2];
+            DASH_TRY(gemm2(c, pm, problem_h(Xcur, Ck, nullptr, nullptr, Xn, nullptr, 1.f, 0.f, 0.f), n, B, 1));
+            Xcur = Xn;
+        }
+    }
+    return gemm1(c, problem_h(Xcur, Cb[(iters - 1) % 3], nullptr, X, nullptr, unscale, inv_c, 0.f, 0.f), n, B,
+                 nonfinite, 1);
 }
 
 // ---- Clenshaw on one chunk (paper Appendix A.2, reduced form, d-1 products) --------------
@@ -606,7 +654,9 @@ dash_status dash_gemm_batched(dash_ctx* c, int transA, int transB, const float* 
     if (N == 0) return DASH_OK;
     if (!A || !Bm || !C) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     if (!D && beta != 0.f) return fail(c, DASH_ERR_INVALID_ARG, "beta != 0 needs D");
-    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32) return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
+    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32)
+        return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
+    c->half_kind = precision == DASH_FP16_ACC32 ? HALF_FP16 : HALF_BF16;
     const size_t bytes = (size_t)N * B * B * sizeof(float);
     if (overlap(C, A, bytes) || overlap(C, Bm, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "C overlaps an operand");
     if (D && D != C && overlap(C, D, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "D must equal C or be disjoint from it");
@@ -623,8 +673,8 @@ dash_status dash_gemm_batched(dash_ctx* c, int transA, int transB, const float* 
         const size_t o = (size_t)b0 * mat;
         bf16_t* Ah = (bf16_t*)c->ws;
         bf16_t* Bh = Ah + (size_t)nb * mat;
-        HIP_TRY(c, launch_scale_shift(A + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Ah, nullptr, nullptr, c->stream));
-        HIP_TRY(c, launch_scale_shift(Bm + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Bh, nullptr, nullptr, c->stream));
+        HIP_TRY(c, launch_scale_shift(A + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Ah, nullptr, nullptr, c->stream, c->half_kind));
+        HIP_TRY(c, launch_scale_shift(Bm + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Bh, nullptr, nullptr, c->stream, c->half_kind));
         DASH_TRY(gemm1(c, problem_h(Ah, Bh, D ? D + o : nullptr, C + o, nullptr, nullptr, alpha, beta, gamma,
                                     transA ? 1 : 0, transB ? 1 : 0), nb, B, nullptr, 1));
     }
@@ -702,7 +752,9 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         return fail(c, DASH_ERR_INVALID_ARG, "bad method");
     if (method == DASH_COUPLED_NEWTON && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Coupled-Newton needs iters >= 1");
     if ((int)scaling < 0 || (int)scaling > 3) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
-    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32) return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
+    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32)
+        return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
+    c->half_kind = precision == DASH_FP16_ACC32 ? HALF_FP16 : HALF_BF16;
     if (method == DASH_NEWTON_DB && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Newton-DB needs iters >= 1");
     if (method == DASH_CHEBYSHEV) {
         if (iters < 2) return fail(c, DASH_ERR_INVALID_ARG, "Chebyshev needs degree >= 2");
@@ -713,8 +765,6 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     if (N == 0) return DASH_OK;
     if (!A || !X) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     if (overlap(A, X, (size_t)N * B * B * sizeof(float))) return fail(c, DASH_ERR_INVALID_ARG, "X overlaps A");
-    if (method == DASH_COUPLED_NEWTON && precision != DASH_FP32)
-        return fail(c, DASH_ERR_UNSUPPORTED, "Coupled-Newton is built for fp32 operands only");
     HIP_TRY(c, hipSetDevice(c->device));
 
     const size_t per = per_block_bytes(B, method, precision);
@@ -727,7 +777,7 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     const size_t mat = (size_t)B * B;
     const int P = norm_slabs(B);
     const int nbuf = f32_buffers(method, precision), nhbuf = bf16_buffers(method, precision);
-    const bool lowp = precision == DASH_BF16_ACC32;
+    const bool lowp = precision != DASH_FP32;
     hipStream_t st = c->stream;
 
     for (int64_t b0 = 0; b0 < N; b0 += chunk) {
@@ -738,10 +788,10 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         float* inv_s = sc.inv_s;
         float* unscale = sc.unscale;
         float* buf[9] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-        bf16_t* hbuf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+        bf16_t* hbuf[9] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
         for (int i = 0; i < nbuf; ++i) buf[i] = (float*)cv.take((size_t)nb * mat * sizeof(float));
         for (int i = 0; i < nhbuf; ++i) hbuf[i] = (bf16_t*)cv.take((size_t)nb * mat * sizeof(bf16_t));
-        if (!sc_ok || !buf[nbuf - 1] || (nhbuf && !hbuf[nhbuf - 1]))
+        if (!sc_ok || (nbuf && !buf[nbuf - 1]) || (nhbuf && !hbuf[nhbuf - 1]))
             return fail(c, DASH_ERR_WORKSPACE, "internal: workspace carve failed");
 
         const float* Ac = A + (size_t)b0 * mat;
@@ -752,7 +802,9 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         // Sections 3.4, 3.5: s = ||A + eps I||_F, trace, or 2 lambda_PI, kept with 1/s and s^(-1/p)
         DASH_TRY(compute_scales(c, Ac, nb, B, eps, scaling, p, sc, scale_out ? scale_out + b0 : sc.s));
 
-        if (method == DASH_COUPLED_NEWTON) {
+        if (method == DASH_COUPLED_NEWTON && lowp) {
+            DASH_TRY(cn_chunk_half(c, hbuf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf, nullptr));
+        } else if (method == DASH_COUPLED_NEWTON) {
             DASH_TRY(cn_chunk(c, buf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf));
         } else if (lowp && method == DASH_NEWTON_DB) {
             int idx = -1;

@@ -11,7 +11,13 @@
 namespace dash {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
-typedef __bf16 v4h __attribute__((ext_vector_type(4)));
+typedef unsigned short v4s __attribute__((ext_vector_type(4)));
+
+// fp32 -> 16-bit operand format, round to nearest even
+__device__ __forceinline__ unsigned short to_half(float v, int half) {
+    if (half == HALF_FP16) { union { _Float16 h; unsigned short u; } x; x.h = (_Float16)v; return x.u; }
+    union { __bf16 h; unsigned short u; } x; x.h = (__bf16)v; return x.u;
+}
 
 constexpr int NT = 256;
 
@@ -81,8 +87,8 @@ __global__ void finalize_scale_kernel(const float* __restrict__ partial, int64_t
 __global__ __launch_bounds__(NT) void scale_shift_kernel(const float* __restrict__ in, int B, float eps,
                                                         const float* __restrict__ mult, float a1, float g1,
                                                         float* __restrict__ out1, float a2, float g2,
-                                                        float* __restrict__ out2, __bf16* __restrict__ h1,
-                                                        __bf16* __restrict__ h2, int32_t* nonfinite) {
+                                                        float* __restrict__ out2, unsigned short* __restrict__ h1,
+                                                        unsigned short* __restrict__ h2, int32_t* nonfinite, int half) {
     const int64_t b = blockIdx.y;
     const int f = blockIdx.x * NT + threadIdx.x;     // float4 index inside the block
     const int qpr = B / 4;
@@ -104,16 +110,16 @@ __global__ __launch_bounds__(NT) void scale_shift_kernel(const float* __restrict
     if (out1) *reinterpret_cast<v4f*>(out1 + off) = o1;
     if (out2) *reinterpret_cast<v4f*>(out2 + off) = o2;
     if (h1) {
-        v4h t;
+        v4s t;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] = (__bf16)o1[i];
-        *reinterpret_cast<v4h*>(h1 + off) = t;
+        for (int i = 0; i < 4; ++i) t[i] = to_half(o1[i], half);
+        *reinterpret_cast<v4s*>(h1 + off) = t;
     }
     if (h2) {
-        v4h t;
+        v4s t;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] = (__bf16)o2[i];
-        *reinterpret_cast<v4h*>(h2 + off) = t;
+        for (int i = 0; i < 4; ++i) t[i] = to_half(o2[i], half);
+        *reinterpret_cast<v4s*>(h2 + off) = t;
     }
     if (nonfinite && bad) nonfinite[b] = 1;
 }
@@ -206,15 +212,16 @@ hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, i
 
 hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult, float a1,
                               float g1, float* out1, float a2, float g2, float* out2, void* h1, void* h2,
-                              int32_t* nonfinite, hipStream_t stream) {
+                              int32_t* nonfinite, hipStream_t stream, int half) {
     const unsigned gx = (unsigned)(((size_t)B * B / 4 + NT - 1) / NT);
     for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
         const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
         const size_t o = (size_t)b0 * B * B;
         hipLaunchKernelGGL(scale_shift_kernel, dim3(gx, (unsigned)nb), dim3(NT), 0, stream, in + o, B, eps,
                            mult ? mult + b0 : nullptr, a1, g1, out1 ? out1 + o : nullptr, a2, g2,
-                           out2 ? out2 + o : nullptr, h1 ? static_cast<__bf16*>(h1) + o : nullptr,
-                           h2 ? static_cast<__bf16*>(h2) + o : nullptr, nonfinite ? nonfinite + b0 : nullptr);
+                           out2 ? out2 + o : nullptr, h1 ? static_cast<unsigned short*>(h1) + o : nullptr,
+                           h2 ? static_cast<unsigned short*>(h2) + o : nullptr, nonfinite ? nonfinite + b0 : nullptr,
+                           half);
     }
     return hipGetLastError();
 }

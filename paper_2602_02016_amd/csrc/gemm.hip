@@ -275,7 +275,7 @@ hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
     if (g.nprob < 1 || g.nprob > 2 || g.B <= 0 || g.B % 64) return hipErrorInvalidValue;
     if (g.nprob == 2 && (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
         return hipErrorInvalidValue;
-    if (g.bf16) return launch_gemm_bf16(g, stream);
+    if (g.half != HALF_NONE) return launch_gemm_half(g, stream);
     return gemm_tile_edge(g) == 128 ? launch_tile<128>(g, stream) : launch_tile<64>(g, stream);
 }
 

@@ -1,13 +1,14 @@
-// Batched B x B x B matmul with bf16 operands and fp32 accumulation, for gfx950.
+// Batched B x B x B matmul with 16-bit operands (bf16 or fp16) and fp32 accumulation, for gfx950.
 //
 // Mixed-precision form of the same product as gemm.hip (paper Appendix A.3: iterates are
 // kept in fp32, the operands of each matmul are rounded to half precision, accumulation
-// is fp32 -- here with bf16 instead of fp16).  Operands arrive already rounded: the
-// epilogue of the product (or the elementwise kernel) that produced an iterate writes a
-// bf16 copy next to, or instead of, the fp32 value, so no separate cast pass exists.
-//     acc = op(A_b) op(B_b)                       (v_mfma_f32_32x32x16_bf16)
+// is fp32; the paper uses fp16, the bf16 form is the one its Section 5 reports unstable for
+// Newton-DB).  Operands arrive already rounded: the epilogue of the product (or the
+// elementwise kernel) that produced an iterate writes a 16-bit copy next to, or instead of,
+// the fp32 value, so no separate cast pass exists.
+//     acc = op(A_b) op(B_b)             (v_mfma_f32_32x32x16_bf16 / v_mfma_f32_32x32x16_f16)
 //     v   = mult_b * (alpha * acc + beta * D_b + gamma * I)     (fp32)
-//     C_b = v (fp32, optional),  Ch_b = bf16(v) (optional)
+//     C_b = v (fp32, optional),  Ch_b = half(v) (optional),  C2h_b = half(a2 v + g2 I) (optional)
 //
 // Same decomposition as the fp32 kernel: 256 threads, 2 x 2 wavefronts, TILE x TILE per
 // workgroup, K slabs of 32 double-buffered in LDS, next slab prefetched into registers,
@@ -23,10 +24,32 @@
 namespace dash {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
-typedef __bf16 v8h __attribute__((ext_vector_type(8)));
+typedef unsigned short u16;      // a 16-bit operand element while it is only being moved
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
-typedef __bf16 v4h __attribute__((ext_vector_type(4)));
+typedef u16 v4s __attribute__((ext_vector_type(4)));
+
+// the two 16-bit operand formats: conversion from fp32 (round to nearest even) and the MFMA
+struct Bf16 {
+    typedef __bf16 v8 __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ u16 from_float(float v) {
+        union { __bf16 h; u16 u; } x; x.h = (__bf16)v; return x.u;
+    }
+    static __device__ __forceinline__ v16f mfma(v4u a, v4u b, v16f c) {
+        union { v4u u; v8 h; } x, y; x.u = a; y.u = b;
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.h, y.h, c, 0, 0, 0);
+    }
+};
+struct Fp16 {
+    typedef _Float16 v8 __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ u16 from_float(float v) {
+        union { _Float16 h; u16 u; } x; x.h = (_Float16)v; return x.u;
+    }
+    static __device__ __forceinline__ v16f mfma(v4u a, v4u b, v16f c) {
+        union { v4u u; v8 h; } x, y; x.u = a; y.u = b;
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(x.h, y.h, c, 0, 0, 0);
+    }
+};
 
 namespace {
 
@@ -51,7 +74,7 @@ struct HLds {
 
 // A slab is TILE*32 bf16 = TILE*4 16-byte vectors; a thread carries TILE*4/256 of them.
 template <int TILE, bool KC>
-__device__ __forceinline__ void hload_slab(const __bf16* __restrict__ base, int ld, int row0, int k0,
+__device__ __forceinline__ void hload_slab(const u16* __restrict__ base, int ld, int row0, int k0,
                                            v4u (&r)[HRegs<TILE>::NV]) {
     constexpr int NV = TILE * 4 / HNT;
     const int t = threadIdx.x;
@@ -70,7 +93,7 @@ __device__ __forceinline__ void hload_slab(const __bf16* __restrict__ base, int 
             const int f = t + HNT * u;
             if (f < UNITS) {
                 const int q = f / GPL, rg = f % GPL;
-                const __bf16* p = base + (size_t)(k0 + 2 * q) * ld + row0 + 8 * rg;
+                const u16* p = base + (size_t)(k0 + 2 * q) * ld + row0 + 8 * rg;
                 r[2 * u] = *reinterpret_cast<const v4u*>(p);
                 r[2 * u + 1] = *reinterpret_cast<const v4u*>(p + ld);
             }
@@ -117,24 +140,24 @@ __device__ __forceinline__ void hstore_slab(char* __restrict__ s, const v4u (&r)
 // operand of MFMA step `st` (16 k each) for the 32-row sub-tile at r0:
 // element (r0 + lane%32, 16*st + 8*(lane/32) + 0..7)
 template <int TILE, bool KC>
-__device__ __forceinline__ v8h hread_frag(const char* __restrict__ s, int r0, int st, int lane) {
+__device__ __forceinline__ v4u hread_frag(const char* __restrict__ s, int r0, int st, int lane) {
     const int rr = r0 + (lane & 31), kh = 16 * st + 8 * (lane >> 5);
-    union { v4u u; v8h h; } x;
+    v4u x;
     if (KC) {
-        x.u = *reinterpret_cast<const v4u*>(s + (rr * HKC_PITCH + kh) * 2);
+        x = *reinterpret_cast<const v4u*>(s + (rr * HKC_PITCH + kh) * 2);
     } else {
         constexpr int P = HLds<TILE>::RC_PITCH;
         const unsigned int* d = reinterpret_cast<const unsigned int*>(s) + (kh >> 1) * P + rr;
-        x.u[0] = d[0];
-        x.u[1] = d[P];
-        x.u[2] = d[2 * P];
-        x.u[3] = d[3 * P];
+        x[0] = d[0];
+        x[1] = d[P];
+        x[2] = d[2 * P];
+        x[3] = d[3 * P];
     }
-    return x.h;
+    return x;
 }
 
-template <int TILE, bool TA, bool TB>
-__global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
+template <typename H, int TILE, bool TA, bool TB>
+__global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
     constexpr int MT = TILE / 64;
     constexpr bool A_KC = !TA;
     constexpr bool B_KC = TB;
@@ -171,8 +194,8 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
 
     const GemmProblem& P = g.prob[pi];
     const size_t boff = (size_t)blk * B * B;
-    const __bf16* __restrict__ Ab = static_cast<const __bf16*>(P.A) + boff;
-    const __bf16* __restrict__ Bb = static_cast<const __bf16*>(P.B) + boff;
+    const u16* __restrict__ Ab = static_cast<const u16*>(P.A) + boff;
+    const u16* __restrict__ Bb = static_cast<const u16*>(P.B) + boff;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
@@ -203,7 +226,7 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
         }
 #pragma unroll
         for (int st = 0; st < HBK / 16; ++st) {
-            v8h fa[MT], fb[MT];
+            v4u fa[MT], fb[MT];
 #pragma unroll
             for (int i = 0; i < MT; ++i) fa[i] = hread_frag<TILE, A_KC>(sa, wm + 32 * i, st, lane);
 #pragma unroll
@@ -212,7 +235,7 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
             for (int i = 0; i < MT; ++i)
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = H::mfma(fa[i], fb[j], acc[i][j]);
         }
         if (more) {
             char* da = lds + ((kt + 1) & 1) * 2 * SLAB;
@@ -226,7 +249,9 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
     const float alpha = P.alpha * mult, beta = P.beta * mult, gamma = P.gamma * mult;
     const float* __restrict__ Db = P.D ? P.D + boff : nullptr;
     float* __restrict__ Cb = P.C ? P.C + boff : nullptr;
-    __bf16* __restrict__ Hb = P.Ch ? static_cast<__bf16*>(P.Ch) + boff : nullptr;
+    u16* __restrict__ Hb = P.Ch ? static_cast<u16*>(P.Ch) + boff : nullptr;
+    u16* __restrict__ H2b = P.C2h ? static_cast<u16*>(P.C2h) + boff : nullptr;
+    const float a2 = P.a2, g2 = P.g2;
     // symmetric mode: an off-diagonal tile is also written transposed (four consecutive rows
     // of one column = four consecutive elements of a row of the transposed tile)
     const bool mirror = g.sym && ti != tj;
@@ -240,7 +265,7 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
             for (int q = 0; q < 4; ++q) {
                 const int rbase = row0 + wm + 32 * i + 8 * q + 4 * (lane >> 5);
                 v4f out;
-                v4h outh;
+                v4s outh, outh2;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const int row = rbase + m;
@@ -250,21 +275,26 @@ __global__ __launch_bounds__(HNT, 2) void gemm_bf16_kernel(GemmLaunch g) {
                     if (row == col) v += gamma;
                     bad |= !(fabsf(v) <= 3.0e38f);
                     out[m] = v;
-                    outh[m] = (__bf16)v;
+                    outh[m] = H::from_float(v);
                     if (Cb) Cb[off] = v;
                     if (Hb) Hb[off] = outh[m];
+                    if (H2b) {
+                        outh2[m] = H::from_float(a2 * v + (row == col ? g2 : 0.f));
+                        H2b[off] = outh2[m];
+                    }
                 }
                 if (mirror) {
                     const size_t moff = (size_t)col * B + rbase;
                     if (Cb) *reinterpret_cast<v4f*>(Cb + moff) = out;
-                    if (Hb) *reinterpret_cast<v4h*>(Hb + moff) = outh;
+                    if (Hb) *reinterpret_cast<v4s*>(Hb + moff) = outh;
+                    if (H2b) *reinterpret_cast<v4s*>(H2b + moff) = outh2;
                 }
             }
         }
     if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;
 }
 
-template <int TILE>
+template <typename H, int TILE>
 hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
     const int tiles = g.B / TILE;
     const int64_t W = g.nblocks * g.nprob * (g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles);
@@ -272,17 +302,20 @@ hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
     if (W > 0x7fffffffLL) return hipErrorInvalidValue;
     const int ta = g.prob[0].transA, tb = g.prob[0].transB;
     dim3 grid((unsigned)W), block(HNT);
-    if (!ta && !tb) hipLaunchKernelGGL((gemm_bf16_kernel<TILE, false, false>), grid, block, 0, stream, g);
-    else if (!ta && tb) hipLaunchKernelGGL((gemm_bf16_kernel<TILE, false, true>), grid, block, 0, stream, g);
-    else if (ta && !tb) hipLaunchKernelGGL((gemm_bf16_kernel<TILE, true, false>), grid, block, 0, stream, g);
-    else hipLaunchKernelGGL((gemm_bf16_kernel<TILE, true, true>), grid, block, 0, stream, g);
+    if (!ta && !tb) hipLaunchKernelGGL((gemm_half_kernel<H, TILE, false, false>), grid, block, 0, stream, g);
+    else if (!ta && tb) hipLaunchKernelGGL((gemm_half_kernel<H, TILE, false, true>), grid, block, 0, stream, g);
+    else if (ta && !tb) hipLaunchKernelGGL((gemm_half_kernel<H, TILE, true, false>), grid, block, 0, stream, g);
+    else hipLaunchKernelGGL((gemm_half_kernel<H, TILE, true, true>), grid, block, 0, stream, g);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_gemm_bf16(const GemmLaunch& g, hipStream_t stream) {
-    return gemm_tile_edge(g) == 128 ? hlaunch_tile<128>(g, stream) : hlaunch_tile<64>(g, stream);
+hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream) {
+    const bool big = gemm_tile_edge(g) == 128;
+    if (g.half == HALF_BF16) return big ? hlaunch_tile<Bf16, 128>(g, stream) : hlaunch_tile<Bf16, 64>(g, stream);
+    if (g.half == HALF_FP16) return big ? hlaunch_tile<Fp16, 128>(g, stream) : hlaunch_tile<Fp16, 64>(g, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace dash

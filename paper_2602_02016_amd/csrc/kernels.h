@@ -10,17 +10,21 @@ namespace dash {
 // One batched product  C_b = mult_b * (alpha * op(A_b) op(B_b) + beta * D_b + gamma * I).
 // mult (per-block factor, device array) may be null (= 1).  D may be null when beta == 0
 // and may equal C.
-// fp32 launches: A, B are fp32 stacks, Ch is ignored.
-// bf16 launches (GemmLaunch::bf16 = 1): A, B point to bf16 stacks (same [N][B][B] layout,
-// 2-byte elements); the result is written to C in fp32 (if C is not null) and, rounded
-// to bf16, to Ch (if Ch is not null); D stays fp32.
+// fp32 launches: A, B are fp32 stacks, Ch and C2h are ignored.
+// 16-bit launches (GemmLaunch::half = HALF_BF16 or HALF_FP16): A, B point to bf16 / fp16 stacks
+// (same [N][B][B] layout, 2-byte elements); the result is written to C in fp32 (if C is not
+// null) and, rounded to the 16-bit format, to Ch (if Ch is not null); D stays fp32; C2 is
+// ignored and the second output goes, rounded, to C2h.
+enum { HALF_NONE = 0, HALF_BF16 = 1, HALF_FP16 = 2 };
+
 struct GemmProblem {
     const void* A;
     const void* B;
     const float* D;
     float* C;
     void* Ch;
-    float* C2;             // fp32 launches only: optional second output a2 * C + g2 * I
+    float* C2;             // fp32 launches: optional second output a2 * C + g2 * I
+    void* C2h;             // 16-bit launches: the same second output, rounded to the 16-bit format
     float a2, g2;
     const float* mult;
     float alpha, beta, gamma;
@@ -35,7 +39,7 @@ struct GemmLaunch {
     int B;                 // block edge
     int64_t nblocks;       // blocks in this launch
     int32_t* nonfinite;    // per-block flag for prob[0]'s output, or null
-    int bf16;              // 0: fp32 MFMA operands, 1: operands rounded to bf16
+    int half;              // HALF_NONE: fp32 MFMA operands; HALF_BF16 / HALF_FP16: 16-bit operands
     int sym;               // 1: every product of the launch is symmetric in exact arithmetic:
                            //    only tiles on or above the diagonal are computed, the rest mirrored
 };
@@ -43,7 +47,7 @@ struct GemmLaunch {
 hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream);
 int gemm_tile_edge(const GemmLaunch& g);          // tile edge launch_gemm picks (64 or 128)
 double gemm_tile_fraction(const GemmLaunch& g);   // share of output tiles actually computed
-hipError_t launch_gemm_bf16(const GemmLaunch& g, hipStream_t stream);   // gemm_bf16.hip
+hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream);   // gemm_half.hip
 
 // partial[b*P + q] = sum over the q-th row slab of block b of (A + eps I)^2 (mode 0)
 // or of the diagonal of (A + eps I) (mode 1).  P = norm_slabs(B).
@@ -56,11 +60,11 @@ hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, i
                                  float* s, float* inv_s, float* unscale, hipStream_t stream);
 
 // t = (in + eps I) * mult_b ; o1 = a1 * t + g1 * I ; o2 = a2 * o1 + g2 * I.
-// o1 is written to out1 (fp32) and/or h1 (rounded to bf16), o2 to out2 and/or h2; any of
-// the four destinations and mult may be null.
+// o1 is written to out1 (fp32) and/or h1 (rounded to the 16-bit format `half`), o2 to out2 and/or
+// h2; any of the four destinations and mult may be null.
 hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult,
                               float a1, float g1, float* out1, float a2, float g2, float* out2,
-                              void* h1, void* h2, int32_t* nonfinite, hipStream_t stream);
+                              void* h1, void* h2, int32_t* nonfinite, hipStream_t stream, int half = HALF_BF16);
 
 // Multi-Power-Iteration scaling (power_iteration.hip): s_b = 2 * lambda_PI(A_b + eps I) from
 // `sweeps` passes over the block with a pool of `pool` (<= 32) start vectors V0 ([B][pool]

@@ -67,3 +67,40 @@ def test_bf16_plateau_is_where_expected():
     e_lo = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32[0], 4, 12), X_true)[0]
     e_hi = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32[0], 4, 12, rounding=False), X_true)[0]
     assert e_hi < 1e-5 and 1e-4 < e_lo < 5e-2
+
+
+def test_round_fp16_exact_facts_and_library():
+    f = np.float32
+    assert lowprec.round_fp16(f(1.0 + 2.0 ** -10)) == f(1.0 + 2.0 ** -10)        # 11 significand bits
+    assert lowprec.round_fp16(f(1.0 + 2.0 ** -11)) == 1.0                        # tie -> even
+    assert lowprec.round_fp16(f(1.0 + 3 * 2.0 ** -11)) == f(1.0 + 2.0 ** -9)
+    assert lowprec.round_fp16(f(65504.0)) == 65504.0 and np.isinf(lowprec.round_fp16(f(70000.0)))
+    assert lowprec.round_fp16(f(2.0 ** -24)) == f(2.0 ** -24)                    # smallest subnormal
+    assert lowprec.round_fp16(f(2.0 ** -26)) == 0.0                              # underflows to zero
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.standard_normal(20000), rng.standard_normal(2000) * 1e-6]).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.float16).to(torch.float32).numpy()
+    assert np.array_equal(lowprec.round_fp16(x), ref)
+
+
+@pytest.mark.parametrize("p", [2, 4])
+def test_cn_emulation_without_rounding_is_the_paper_iteration(p):
+    from oracle import coupled_newton as ocn
+    A32, _, _ = workloads.spd_stack(2, 32, -1.0, 0.0, seed=7)
+    for k in (1, 2, 3, 9):
+        X = lowprec.inverse_root_cn_lowprec(A32, p, k, eps=1e-6, fmt="none")
+        X64 = ocn.inverse_root_cn(A32.astype(np.float64), p, k, eps=1e-6)
+        assert rel_frobenius_error(X, X64).max() < 2e-6
+
+
+def test_fp16_beats_bf16_on_a_well_conditioned_block():
+    # Sections 2.3 / 5: Coupled-Newton works in fp16 and diverges or degrades in bf16; Newton-DB
+    # plateaus higher with bf16's 8 significand bits than with fp16's 11
+    A32, Q, lam = workloads.spd_stack(1, 64, -1.0, 0.0, seed=9)
+    X_true = (Q[0] * lam[0] ** -0.25) @ Q[0].T
+    e = {}
+    for fmt in ("fp16", "bf16"):
+        e["cn", fmt] = rel_frobenius_error(lowprec.inverse_root_cn_lowprec(A32[0], 4, 25, fmt=fmt), X_true)[0]
+        e["ndb", fmt] = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32[0], 4, 12, rounding=fmt), X_true)[0]
+    assert e["cn", "fp16"] < 3e-3 and e["cn", "fp16"] < e["cn", "bf16"] / 3
+    assert e["ndb", "fp16"] < e["ndb", "bf16"] / 3
