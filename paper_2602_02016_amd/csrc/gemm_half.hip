@@ -53,15 +53,19 @@ struct Fp16 {
 
 namespace {
 
-constexpr int HBK = 32;          // K slab (bf16 elements)
-constexpr int HKC_PITCH = 40;    // bf16 per row in the KC layout (32 + 8 pad) = 80 bytes
+#ifndef DASH_HBK
+#define DASH_HBK 64
+#endif
+constexpr int HBK = DASH_HBK;         // K slab (16-bit elements): 32 or 64
+constexpr int HKC_PITCH = HBK + 8;    // elements per row in the KC layout (8 of padding)
+constexpr int HKQ = HBK / 8;          // 16-byte vectors per row of a KC slab
 constexpr int HNT = 256;
 constexpr int HNUM_XCD = 8;
 
 // 16-byte vectors a thread carries per operand slab (the RC2 path needs two per unit)
 template <int TILE>
 struct HRegs {
-    static constexpr int NV = TILE * 4 / HNT < 2 ? 2 : TILE * 4 / HNT;
+    static constexpr int NV = TILE * HKQ / HNT < 2 ? 2 : TILE * HKQ / HNT;
 };
 
 template <int TILE>
@@ -76,13 +80,13 @@ struct HLds {
 template <int TILE, bool KC>
 __device__ __forceinline__ void hload_slab(const u16* __restrict__ base, int ld, int row0, int k0,
                                            v4u (&r)[HRegs<TILE>::NV]) {
-    constexpr int NV = TILE * 4 / HNT;
+    constexpr int NV = TILE * HKQ / HNT;
     const int t = threadIdx.x;
     if (KC) {           // element (row, k) at base[row*ld + k]: 4 vectors per row
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
             const int f = t + HNT * u;
-            const int row = f >> 2, kq = f & 3;
+            const int row = f / HKQ, kq = f % HKQ;
             r[u] = *reinterpret_cast<const v4u*>(base + (size_t)(row0 + row) * ld + k0 + 8 * kq);
         }
     } else {            // element (row, k) at base[k*ld + row]: unit = 2 k-lines x 8 rows
@@ -103,13 +107,13 @@ __device__ __forceinline__ void hload_slab(const u16* __restrict__ base, int ld,
 
 template <int TILE, bool KC>
 __device__ __forceinline__ void hstore_slab(char* __restrict__ s, const v4u (&r)[HRegs<TILE>::NV]) {
-    constexpr int NV = TILE * 4 / HNT;
+    constexpr int NV = TILE * HKQ / HNT;
     const int t = threadIdx.x;
     if (KC) {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
             const int f = t + HNT * u;
-            const int row = f >> 2, kq = f & 3;
+            const int row = f / HKQ, kq = f % HKQ;
             *reinterpret_cast<v4u*>(s + (row * HKC_PITCH + 8 * kq) * 2) = r[u];
         }
     } else {
@@ -224,18 +228,26 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
             hload_slab<TILE, A_KC>(Ab, B, row0, (kt + 1) * HBK, ra);
             hload_slab<TILE, B_KC>(Bb, B, col0, (kt + 1) * HBK, rb);
         }
+        // operand fragments of step st+1 are requested from LDS before the MFMAs of step st issue
+        v4u fa[2][MT], fb[2][MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) fa[0][i] = hread_frag<TILE, A_KC>(sa, wm + 32 * i, 0, lane);
+#pragma unroll
+        for (int j = 0; j < MT; ++j) fb[0][j] = hread_frag<TILE, B_KC>(sb, wn + 32 * j, 0, lane);
 #pragma unroll
         for (int st = 0; st < HBK / 16; ++st) {
-            v4u fa[MT], fb[MT];
+            const int cur = st & 1, nxt = cur ^ 1;
+            if (st + 1 < HBK / 16) {
 #pragma unroll
-            for (int i = 0; i < MT; ++i) fa[i] = hread_frag<TILE, A_KC>(sa, wm + 32 * i, st, lane);
+                for (int i = 0; i < MT; ++i) fa[nxt][i] = hread_frag<TILE, A_KC>(sa, wm + 32 * i, st + 1, lane);
 #pragma unroll
-            for (int j = 0; j < MT; ++j) fb[j] = hread_frag<TILE, B_KC>(sb, wn + 32 * j, st, lane);
+                for (int j = 0; j < MT; ++j) fb[nxt][j] = hread_frag<TILE, B_KC>(sb, wn + 32 * j, st + 1, lane);
+            }
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
-                    acc[i][j] = H::mfma(fa[i], fb[j], acc[i][j]);
+                    acc[i][j] = H::mfma(fa[cur][i], fb[cur][j], acc[i][j]);
         }
         if (more) {
             char* da = lds + ((kt + 1) & 1) * 2 * SLAB;

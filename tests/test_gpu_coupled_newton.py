@@ -88,13 +88,19 @@ def test_stability_and_no_mirroring(dash):
     full.close()
 
 
-def test_bf16_is_refused_cleanly(dash):
-    import torch
-    from paper_2602_02016_amd import DashError
-    A = torch.eye(128, device="cuda").repeat(2, 1, 1).contiguous()
-    with pytest.raises(DashError) as ei:
-        dash.inverse_root(A, method="cn", p=2, iters=5, precision="bf16")
-    assert ei.value.status == 2
+def test_half_precision_one_iteration_and_workspace(dash):
+    """iters = 1 needs no product in any precision (X = s^(-1/p) C_0 / c), and the half-precision
+    workspace (nine 16-bit buffers per block) is smaller than the fp32 one (nine fp32 buffers)."""
+    from oracle import lowprec
+    N, B = 2, 128
+    A32, _, _ = workloads.spd_stack(N, B, -1.0, 0.0, seed=117)
+    for prec in ("fp16", "bf16"):
+        dash.reset_stats()
+        X = dash.inverse_root(_to_gpu(A32), method="cn", p=4, iters=1, eps=1e-6, precision=prec).cpu().numpy()
+        assert dash.get_stats()["matmul_products"] == 0
+        X_ref = lowprec.inverse_root_cn_lowprec(A32, 4, 1, eps=1e-6, fmt=prec)
+        assert rel_frobenius_error(X, X_ref).max() < 1e-6
+    assert dash.workspace_bytes(8, 1024, "cn", 4, "fp16") < 0.6 * dash.workspace_bytes(8, 1024, "cn", 4, "fp32")
 
 
 def test_step_with_coupled_newton(dash):
