@@ -51,8 +51,11 @@ typedef enum { DASH_SCALE_FROBENIUS = 0, DASH_SCALE_TRACE = 1, DASH_SCALE_NONE =
 /* DASH_FP32: fp32 MFMA operands.  DASH_FP16_ACC32 / DASH_BF16_ACC32: the recipe of
  * Appendix A.3 -- iterates kept in fp32, every matmul operand rounded to fp16 / bf16 (round to
  * nearest even), fp32 accumulation -- applied to Clenshaw (as in the paper) and to Newton-DB
- * (which the paper reports unstable in half precision). */
-typedef enum { DASH_FP32 = 0, DASH_BF16_ACC32 = 1, DASH_FP16_ACC32 = 2 } dash_precision;
+ * (which the paper reports unstable in half precision).  DASH_BF16X3 (Newton-DB only): every
+ * operand is carried as two bf16 planes, x ~ hi + lo with hi = bf16(x), lo = bf16(x - hi), and a
+ * product is A_lo B_hi + A_hi B_lo + A_hi B_hi accumulated in fp32 -- about 16 significand bits
+ * per operand at three bf16 MFMA products, which keeps Newton-DB stable where plain bf16 is not. */
+typedef enum { DASH_FP32 = 0, DASH_BF16_ACC32 = 1, DASH_FP16_ACC32 = 2, DASH_BF16X3 = 3 } dash_precision;
 
 /* ---- context ------------------------------------------------------------------- */
 

@@ -1,6 +1,7 @@
 """Emulation of the mixed-precision recipe of the paper's Appendix A.3 (operands of each
 matmul rounded to half precision, accumulation and everything else in single precision),
-with bf16 as the half format, applied to Newton-DB (Section 3.3) and to Clenshaw.
+with fp16 (the paper's format), bf16, or split bf16 operands (two bf16 planes per operand,
+three products), applied to Newton-DB (Section 3.3) and Coupled-Newton (Section 3.2).
 
 TEST INFRASTRUCTURE (see oracle/__init__.py).
 
@@ -57,8 +58,22 @@ def _f32(x):
     return np.asarray(x, dtype=np.float32)
 
 
+def split_bf16(x):
+    """x ~ hi + lo with hi = bf16(x), lo = bf16(x - hi) (both as float32 values)."""
+    hi = round_bf16(x)
+    with np.errstate(invalid="ignore"):
+        lo = round_bf16(_f32(x) - hi)
+    return hi, lo
+
+
 def matmul_lowprec(A, B, fmt: str = "bf16") -> np.ndarray:
-    """float32( half(A) @ half(B) ) with the product summed in float64."""
+    """float32( half(A) @ half(B) ) with the product summed in float64.  fmt = 'bf16x3': both operands
+    split into two bf16 planes, product = A_lo B_hi + A_hi B_lo + A_hi B_hi (lo*lo dropped)."""
+    if fmt == "bf16x3":
+        ah, al = (t.astype(np.float64) for t in split_bf16(A))
+        bh, bl = (t.astype(np.float64) for t in split_bf16(B))
+        with np.errstate(over="ignore", invalid="ignore"):
+            return _f32(al @ bh + ah @ bl + ah @ bh)
     a, b = round_half(A, fmt), round_half(B, fmt)
     with np.errstate(over="ignore", invalid="ignore"):
         return _f32(a.astype(np.float64) @ b.astype(np.float64))

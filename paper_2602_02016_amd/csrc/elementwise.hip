@@ -19,6 +19,11 @@ __device__ __forceinline__ unsigned short to_half(float v, int half) {
     union { __bf16 h; unsigned short u; } x; x.h = (__bf16)v; return x.u;
 }
 
+__device__ __forceinline__ float from_half(unsigned short u, int half) {
+    if (half == HALF_FP16) { union { _Float16 h; unsigned short u; } x; x.u = u; return (float)x.h; }
+    union { __bf16 h; unsigned short u; } x; x.u = u; return (float)x.h;
+}
+
 constexpr int NT = 256;
 
 int norm_slabs(int B) { return B >= 256 ? 32 : 8; }   // B is a multiple of 64, so both divide B
@@ -88,7 +93,9 @@ __global__ __launch_bounds__(NT) void scale_shift_kernel(const float* __restrict
                                                         const float* __restrict__ mult, float a1, float g1,
                                                         float* __restrict__ out1, float a2, float g2,
                                                         float* __restrict__ out2, unsigned short* __restrict__ h1,
-                                                        unsigned short* __restrict__ h2, int32_t* nonfinite, int half) {
+                                                        unsigned short* __restrict__ h2, int32_t* nonfinite, int half,
+                                                        unsigned short* __restrict__ l1,
+                                                        unsigned short* __restrict__ l2) {
     const int64_t b = blockIdx.y;
     const int f = blockIdx.x * NT + threadIdx.x;     // float4 index inside the block
     const int qpr = B / 4;
@@ -120,6 +127,19 @@ __global__ __launch_bounds__(NT) void scale_shift_kernel(const float* __restrict
 #pragma unroll
         for (int i = 0; i < 4; ++i) t[i] = to_half(o2[i], half);
         *reinterpret_cast<v4s*>(h2 + off) = t;
+    }
+    // low planes of the split representation x ~ hi + lo, lo = round(x - hi)
+    if (l1) {
+        v4s t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = to_half(o1[i] - from_half(to_half(o1[i], half), half), half);
+        *reinterpret_cast<v4s*>(l1 + off) = t;
+    }
+    if (l2) {
+        v4s t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = to_half(o2[i] - from_half(to_half(o2[i], half), half), half);
+        *reinterpret_cast<v4s*>(l2 + off) = t;
     }
     if (nonfinite && bad) nonfinite[b] = 1;
 }
@@ -212,7 +232,7 @@ hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, i
 
 hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult, float a1,
                               float g1, float* out1, float a2, float g2, float* out2, void* h1, void* h2,
-                              int32_t* nonfinite, hipStream_t stream, int half) {
+                              int32_t* nonfinite, hipStream_t stream, int half, void* l1, void* l2) {
     const unsigned gx = (unsigned)(((size_t)B * B / 4 + NT - 1) / NT);
     for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
         const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
@@ -221,7 +241,8 @@ hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps
                            mult ? mult + b0 : nullptr, a1, g1, out1 ? out1 + o : nullptr, a2, g2,
                            out2 ? out2 + o : nullptr, h1 ? static_cast<unsigned short*>(h1) + o : nullptr,
                            h2 ? static_cast<unsigned short*>(h2) + o : nullptr, nonfinite ? nonfinite + b0 : nullptr,
-                           half);
+                           half, l1 ? static_cast<unsigned short*>(l1) + o : nullptr,
+                           l2 ? static_cast<unsigned short*>(l2) + o : nullptr);
     }
     return hipGetLastError();
 }

@@ -35,6 +35,9 @@ struct Bf16 {
     static __device__ __forceinline__ u16 from_float(float v) {
         union { __bf16 h; u16 u; } x; x.h = (__bf16)v; return x.u;
     }
+    static __device__ __forceinline__ float to_float(u16 u) {
+        union { __bf16 h; u16 u; } x; x.u = u; return (float)x.h;
+    }
     static __device__ __forceinline__ v16f mfma(v4u a, v4u b, v16f c) {
         union { v4u u; v8 h; } x, y; x.u = a; y.u = b;
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.h, y.h, c, 0, 0, 0);
@@ -44,6 +47,9 @@ struct Fp16 {
     typedef _Float16 v8 __attribute__((ext_vector_type(8)));
     static __device__ __forceinline__ u16 from_float(float v) {
         union { _Float16 h; u16 u; } x; x.h = (_Float16)v; return x.u;
+    }
+    static __device__ __forceinline__ float to_float(u16 u) {
+        union { _Float16 h; u16 u; } x; x.u = u; return (float)x.h;
     }
     static __device__ __forceinline__ v16f mfma(v4u a, v4u b, v16f c) {
         union { v4u u; v8 h; } x, y; x.u = a; y.u = b;
@@ -198,8 +204,14 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
 
     const GemmProblem& P = g.prob[pi];
     const size_t boff = (size_t)blk * B * B;
-    const u16* __restrict__ Ab = static_cast<const u16*>(P.A) + boff;
-    const u16* __restrict__ Bb = static_cast<const u16*>(P.B) + boff;
+    // Split-operand mode (A2, B2 given): every operand is the sum of a high and a low 16-bit plane
+    // (x ~ hi + lo, hi = round(x), lo = round(x - hi)) and the product is A_lo B_hi + A_hi B_lo + A_hi B_hi,
+    // i.e. one product whose K runs over three segments with different plane pairs (lo*lo is dropped).
+    const int nseg = P.A2 ? 3 : 1;
+    const u16* __restrict__ Ahi = static_cast<const u16*>(P.A) + boff;
+    const u16* __restrict__ Bhi = static_cast<const u16*>(P.B) + boff;
+    const u16* __restrict__ Alo = P.A2 ? static_cast<const u16*>(P.A2) + boff : Ahi;
+    const u16* __restrict__ Blo = P.B2 ? static_cast<const u16*>(P.B2) + boff : Bhi;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
@@ -212,22 +224,27 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    const int KS = B / HBK;             // slabs per segment
+    const int KT = nseg * KS;           // slabs in all
     v4u ra[NV], rb[NV];
-    hload_slab<TILE, A_KC>(Ab, B, row0, 0, ra);
-    hload_slab<TILE, B_KC>(Bb, B, col0, 0, rb);
+    // slab kk belongs to segment kk / KS; the small terms are summed first
+    auto load = [&](int kk) {
+        const int seg = nseg == 1 ? 2 : kk / KS, k0 = (kk % KS) * HBK;
+        const u16* __restrict__ Ab = seg == 0 ? Alo : Ahi;
+        const u16* __restrict__ Bb = seg == 1 ? Blo : Bhi;
+        hload_slab<TILE, A_KC>(Ab, B, row0, k0, ra);
+        hload_slab<TILE, B_KC>(Bb, B, col0, k0, rb);
+    };
+    load(0);
     hstore_slab<TILE, A_KC>(lds, ra);
     hstore_slab<TILE, B_KC>(lds + SLAB, rb);
     __syncthreads();
 
-    const int KT = B / HBK;
     for (int kt = 0; kt < KT; ++kt) {
         const char* sa = lds + (kt & 1) * 2 * SLAB;
         const char* sb = sa + SLAB;
         const bool more = kt + 1 < KT;
-        if (more) {
-            hload_slab<TILE, A_KC>(Ab, B, row0, (kt + 1) * HBK, ra);
-            hload_slab<TILE, B_KC>(Bb, B, col0, (kt + 1) * HBK, rb);
-        }
+        if (more) load(kt + 1);
         // operand fragments of step st+1 are requested from LDS before the MFMAs of step st issue
         v4u fa[2][MT], fb[2][MT];
 #pragma unroll
@@ -263,6 +280,7 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
     float* __restrict__ Cb = P.C ? P.C + boff : nullptr;
     u16* __restrict__ Hb = P.Ch ? static_cast<u16*>(P.Ch) + boff : nullptr;
     u16* __restrict__ H2b = P.C2h ? static_cast<u16*>(P.C2h) + boff : nullptr;
+    u16* __restrict__ Lb = P.Cl ? static_cast<u16*>(P.Cl) + boff : nullptr;    // low plane of the result
     const float a2 = P.a2, g2 = P.g2;
     // symmetric mode: an off-diagonal tile is also written transposed (four consecutive rows
     // of one column = four consecutive elements of a row of the transposed tile)
@@ -277,7 +295,7 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
             for (int q = 0; q < 4; ++q) {
                 const int rbase = row0 + wm + 32 * i + 8 * q + 4 * (lane >> 5);
                 v4f out;
-                v4s outh, outh2;
+                v4s outh, outh2, outl;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const int row = rbase + m;
@@ -290,6 +308,10 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
                     outh[m] = H::from_float(v);
                     if (Cb) Cb[off] = v;
                     if (Hb) Hb[off] = outh[m];
+                    if (Lb) {
+                        outl[m] = H::from_float(v - H::to_float(outh[m]));
+                        Lb[off] = outl[m];
+                    }
                     if (H2b) {
                         outh2[m] = H::from_float(a2 * v + (row == col ? g2 : 0.f));
                         H2b[off] = outh2[m];
@@ -299,6 +321,7 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
                     const size_t moff = (size_t)col * B + rbase;
                     if (Cb) *reinterpret_cast<v4f*>(Cb + moff) = out;
                     if (Hb) *reinterpret_cast<v4s*>(Hb + moff) = outh;
+                    if (Lb) *reinterpret_cast<v4s*>(Lb + moff) = outl;
                     if (H2b) *reinterpret_cast<v4s*>(H2b + moff) = outh2;
                 }
             }

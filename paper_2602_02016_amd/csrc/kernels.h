@@ -25,6 +25,11 @@ struct GemmProblem {
     void* Ch;
     float* C2;             // fp32 launches: optional second output a2 * C + g2 * I
     void* C2h;             // 16-bit launches: the same second output, rounded to the 16-bit format
+    // 16-bit launches, split-operand mode: A, B are the high planes, A2, B2 the low planes (null =
+    // plain 16-bit product); Cl receives the low plane of the result (Ch the high plane)
+    const void* A2;
+    const void* B2;
+    void* Cl;
     float a2, g2;
     const float* mult;
     float alpha, beta, gamma;
@@ -64,7 +69,8 @@ hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, i
 // h2; any of the four destinations and mult may be null.
 hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult,
                               float a1, float g1, float* out1, float a2, float g2, float* out2,
-                              void* h1, void* h2, int32_t* nonfinite, hipStream_t stream, int half = HALF_BF16);
+                              void* h1, void* h2, int32_t* nonfinite, hipStream_t stream, int half = HALF_BF16,
+                              void* l1 = nullptr, void* l2 = nullptr);   // l1, l2: low planes of o1, o2 (split mode)
 
 // Multi-Power-Iteration scaling (power_iteration.hip): s_b = 2 * lambda_PI(A_b + eps I) from
 // `sweeps` passes over the block with a pool of `pool` (<= 32) start vectors V0 ([B][pool]

@@ -104,3 +104,33 @@ def test_fp16_beats_bf16_on_a_well_conditioned_block():
         e["ndb", fmt] = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32[0], 4, 12, rounding=fmt), X_true)[0]
     assert e["cn", "fp16"] < 3e-3 and e["cn", "fp16"] < e["cn", "bf16"] / 3
     assert e["ndb", "fp16"] < e["ndb", "bf16"] / 3
+
+
+def test_split_bf16_planes():
+    # hi + lo reproduces x to ~2^-16 relative (two 8-bit significands), hi is the plain bf16 rounding
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(20000).astype(np.float32)
+    hi, lo = lowprec.split_bf16(x)
+    assert np.array_equal(hi, lowprec.round_bf16(x))
+    assert np.all(np.abs(lo) <= np.abs(x) * 2.0 ** -8)
+    rel = np.abs((hi.astype(np.float64) + lo) - x) / np.abs(x)
+    assert rel.max() <= 2.0 ** -16 and rel.max() > 2.0 ** -20
+    # values with at most 16 significant bits split exactly
+    y = (np.arange(1, 4097, dtype=np.float32) * np.float32(2.0 ** -12))
+    hi, lo = lowprec.split_bf16(y)
+    assert np.array_equal(hi + lo, y)
+
+
+def test_split_product_is_far_closer_than_plain_bf16():
+    rng = np.random.default_rng(4)
+    A = rng.standard_normal((64, 64)).astype(np.float32)
+    B = rng.standard_normal((64, 64)).astype(np.float32)
+    exact = A.astype(np.float64) @ B.astype(np.float64)
+    e3 = rel_frobenius_error(lowprec.matmul_lowprec(A, B, "bf16x3"), exact)[0]
+    e1 = rel_frobenius_error(lowprec.matmul_lowprec(A, B, "bf16"), exact)[0]
+    assert e3 < 2e-5 and e1 > 1e-3
+    # the three-term form is exactly hi*hi + hi*lo + lo*hi: adding lo*lo gives the product of the sums
+    ah, al = lowprec.split_bf16(A); bh, bl = lowprec.split_bf16(B)
+    full = (ah.astype(np.float64) + al) @ (bh.astype(np.float64) + bl)
+    three = lowprec.matmul_lowprec(A, B, "bf16x3").astype(np.float64)
+    assert np.allclose(three + al.astype(np.float64) @ bl, full, rtol=0, atol=1e-5)
