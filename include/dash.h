@@ -146,6 +146,43 @@ dash_status dash_gemm_batched(dash_ctx* ctx, int transA, int transB,
 dash_status dash_accumulate_factors(dash_ctx* ctx, const float* G, float* L, float* R,
                                     int64_t N, int B, float beta, float alpha);
 
+/* ---- ragged blocks and 1-D parameters (Section 4.1) ----------------------------------- */
+
+/* block() of Section 4.1 for one row-major layer W [m][n] with block size B: with Nm = m / B,
+ * Nn = n / B (integer division), rm = m mod B, rn = n mod B the layer splits into
+ *   full     [Nm*Nn][B][B]   block (i, j) at index i*Nn + j, W rows i*B.., columns j*B..
+ *   row_rest [Nn][rm][B]     the last rm rows            (the paper's G_rest for the embedding)
+ *   col_rest [Nm][B][rn]     the last rn columns         (the classification head's case)
+ *   corner   [1][rm][rn]
+ * A pointer may be null when its group is empty.  Bit-exact copies; any m, n, B (16-byte
+ * accesses when n, B, rn are multiples of 4).  dash_unblock_layer is the inverse (stack -> W).
+ * All pointers: device. */
+dash_status dash_block_layer(dash_ctx* ctx, const float* W, int64_t m, int64_t n, int B,
+                             float* full, float* row_rest, float* col_rest, float* corner);
+dash_status dash_unblock_layer(dash_ctx* ctx, float* W, int64_t m, int64_t n, int B,
+                               const float* full, const float* row_rest, const float* col_rest,
+                               const float* corner);
+
+/* A layer whose dimensions are not multiples of B leaves "rest" gradient blocks of shape Bm x Bn
+ * (the paper's example: (2, 256, 1024) with L_rest (2, 256, 256) and R_rest (2, 1024, 1024)).
+ *   L_i <- beta L_i + alpha G_i G_i^T,  R_i <- beta R_i + alpha G_i^T G_i
+ * G: dev const [N][Bm][Bn]; L: dev in/out [N][Bm][Bm]; R: dev in/out [N][Bn][Bn]; Bm, Bn multiples
+ * of 64.  The roots of L and R are ordinary square stacks for dash_inverse_root. */
+dash_status dash_accumulate_factors_rect(dash_ctx* ctx, const float* G, float* L, float* R,
+                                         int64_t N, int Bm, int Bn, float beta, float alpha);
+/* U_i <- Linv_i G_i Rinv_i with Linv [N][Bm][Bm], G and U [N][Bm][Bn], Rinv [N][Bn][Bn].
+ * Needs workspace for one [N][Bm][Bn] temporary (or chunks of it). */
+dash_status dash_precondition_rect(dash_ctx* ctx, const float* Linv, const float* G, const float* Rinv,
+                                   float* U, int64_t N, int Bm, int Bn);
+
+/* Normalisation layers: N vectors of B entries each (a layer of size E gives E/B of them); only
+ * the left factor exists.  L_i <- beta L_i + alpha g_i g_i^T;  u_i <- Linv_i g_i (the paper uses
+ * the inverse square root, p = 2, here).  g, u: dev [N][B]; L, Linv: dev [N][B][B]. */
+dash_status dash_accumulate_vector(dash_ctx* ctx, const float* g, float* L, int64_t N, int B,
+                                   float beta, float alpha);
+dash_status dash_precondition_vector(dash_ctx* ctx, const float* Linv, const float* g, float* u,
+                                     int64_t N, int B);
+
 /* ---- Section 3.4 scaling --------------------------------------------------------- */
 
 /* s_i = ||A_i + eps I||_F (Frobenius), tr(A_i + eps I) (trace), 1 (none) or 2 lambda_PI

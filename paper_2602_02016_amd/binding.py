@@ -82,6 +82,12 @@ def load_library(path: str = LIB_PATH):
     lib.dash_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     lib.dash_gemm_batched.argtypes = [vp, i32, i32, vp, vp, vp, vp, i64, i32, f32, f32, f32, i32]
     lib.dash_accumulate_factors.argtypes = [vp, vp, vp, vp, i64, i32, f32, f32]
+    lib.dash_accumulate_factors_rect.argtypes = [vp, vp, vp, vp, i64, i32, i32, f32, f32]
+    lib.dash_precondition_rect.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32]
+    lib.dash_accumulate_vector.argtypes = [vp, vp, vp, i64, i32, f32, f32]
+    lib.dash_precondition_vector.argtypes = [vp, vp, vp, vp, i64, i32]
+    lib.dash_block_layer.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.dash_unblock_layer.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.dash_block_norms.argtypes = [vp, vp, i64, i32, f32, i32, vp]
     lib.dash_inverse_root.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, f32, i32, i32,
                                       C.POINTER(f64), f64, f64, vp, vp]
@@ -90,7 +96,9 @@ def load_library(path: str = LIB_PATH):
     lib.dash_graft_update.argtypes = [vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, vp]
     lib.dash_step.argtypes = [vp, C.POINTER(_StepArgs)]
     for name in ("dash_create", "dash_destroy", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
-                 "dash_set_symmetric", "dash_set_power_iteration",
+                 "dash_set_symmetric", "dash_set_power_iteration", "dash_accumulate_factors_rect",
+                 "dash_block_layer", "dash_unblock_layer",
+                 "dash_precondition_rect", "dash_accumulate_vector", "dash_precondition_vector",
                  "dash_get_stats", "dash_gemm_batched", "dash_accumulate_factors", "dash_block_norms",
                  "dash_inverse_root", "dash_chebyshev_fit", "dash_precondition", "dash_graft_update", "dash_step"):
         getattr(lib, name).restype = C.c_int
@@ -106,6 +114,13 @@ def chebyshev_fit(p: int, degree: int, a: float, b: float, n_points: int = 10000
     if st != OK:
         raise DashError(st, lib.dash_status_string(st).decode())
     return list(out)
+
+
+def layer_plan(m: int, n: int, B: int) -> dict:
+    """Stack shapes block() gives for a [m, n] layer (host arithmetic only; see dash_block_layer)."""
+    Nm, Nn, rm, rn = m // B, n // B, m % B, n % B
+    return dict(full=(Nm * Nn, B, B), row_rest=(Nn if rm else 0, rm, B), col_rest=(Nm if rn else 0, B, rn),
+                corner=(1 if rm and rn else 0, rm, rn))
 
 
 def _enum(table, v):
@@ -156,6 +171,13 @@ class Dash:
             raise DashError(ERR_INVALID_ARG, f"{name}: need a contiguous float32 device tensor of shape [N,B,B]")
         if n is not None and (t.shape[0] != n or t.shape[1] != b):
             raise DashError(ERR_INVALID_ARG, f"{name}: shape {tuple(t.shape)} does not match [{n},{b},{b}]")
+        return C.c_void_p(t.data_ptr())
+
+    def _dense(self, t, name: str, shape):
+        torch = self._torch
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+                and tuple(t.shape) == tuple(shape)):
+            raise DashError(ERR_INVALID_ARG, f"{name}: need a contiguous float32 device tensor of shape {list(shape)}")
         return C.c_void_p(t.data_ptr())
 
     def _vec(self, t, name: str, n: int, dtype):
@@ -236,6 +258,67 @@ class Dash:
         n, b = G.shape[0], G.shape[1]
         self._check(self.lib.dash_accumulate_factors(self.h, self._stack(G, "G"), self._stack(L, "L", n, b),
                                                      self._stack(R, "R", n, b), n, b, beta, alpha))
+
+    def block_layer(self, W, B: int):
+        """block() of a [m, n] layer: returns dict(full, row_rest, col_rest, corner) of device stacks
+        (None for an empty group)."""
+        torch = self._torch
+        m, n = W.shape
+        shapes = layer_plan(m, n, B)
+        out = {k: (torch.empty(sh, dtype=torch.float32, device=self.device) if sh[0] * sh[1] * sh[2] > 0 else None)
+               for k, sh in shapes.items()}
+        ptr = lambda t: C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(None)
+        self._check(self.lib.dash_block_layer(self.h, self._dense(W, "W", (m, n)), m, n, B, ptr(out["full"]),
+                                              ptr(out["row_rest"]), ptr(out["col_rest"]), ptr(out["corner"])))
+        return out
+
+    def unblock_layer(self, W, B: int, groups: dict):
+        m, n = W.shape
+        shapes = layer_plan(m, n, B)
+        ptrs = []
+        for k in ("full", "row_rest", "col_rest", "corner"):
+            sh, t = shapes[k], groups.get(k)
+            ptrs.append(self._dense(t, k, sh) if sh[0] * sh[1] * sh[2] > 0 else C.c_void_p(None))
+        self._check(self.lib.dash_unblock_layer(self.h, self._dense(W, "W", (m, n)), m, n, B, *ptrs))
+        return W
+
+    def accumulate_factors_rect(self, G, L, R, beta: float, alpha: Optional[float] = None):
+        """Ragged blocks: G [N,Bm,Bn], L [N,Bm,Bm], R [N,Bn,Bn]."""
+        if alpha is None:
+            alpha = 1.0 - beta
+        n, bm, bn = G.shape
+        self._check(self.lib.dash_accumulate_factors_rect(
+            self.h, self._dense(G, "G", (n, bm, bn)), self._dense(L, "L", (n, bm, bm)), self._dense(R, "R", (n, bn, bn)),
+            n, bm, bn, beta, alpha))
+
+    def precondition_rect(self, Linv, G, Rinv, U=None):
+        torch = self._torch
+        n, bm, bn = G.shape
+        if U is None:
+            U = torch.empty_like(G)
+        if n > 0 and (self._ws is None or self._ws.numel() < n * bm * bn * 4):
+            self.set_workspace_bytes(n * bm * bn * 4)
+        self._check(self.lib.dash_precondition_rect(
+            self.h, self._dense(Linv, "Linv", (n, bm, bm)), self._dense(G, "G", (n, bm, bn)),
+            self._dense(Rinv, "Rinv", (n, bn, bn)), self._dense(U, "U", (n, bm, bn)), n, bm, bn))
+        return U
+
+    def accumulate_vector(self, g, L, beta: float, alpha: Optional[float] = None):
+        """1-D parameters: g [N,B], L [N,B,B]."""
+        if alpha is None:
+            alpha = 1.0 - beta
+        n, b = g.shape
+        self._check(self.lib.dash_accumulate_vector(self.h, self._dense(g, "g", (n, b)), self._dense(L, "L", (n, b, b)),
+                                                    n, b, beta, alpha))
+
+    def precondition_vector(self, Linv, g, u=None):
+        torch = self._torch
+        n, b = g.shape
+        if u is None:
+            u = torch.empty_like(g)
+        self._check(self.lib.dash_precondition_vector(self.h, self._dense(Linv, "Linv", (n, b, b)),
+                                                      self._dense(g, "g", (n, b)), self._dense(u, "u", (n, b)), n, b))
+        return u
 
     def block_norms(self, A, eps: float = 0.0, scaling="frobenius", out=None):
         torch = self._torch

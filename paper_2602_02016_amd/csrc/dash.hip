@@ -81,6 +81,12 @@ bool overlap(const void* a, const void* b, size_t bytes) {
     return x < y + bytes && y < x + bytes;
 }
 
+bool overlap2(const void* a, size_t abytes, const void* b, size_t bbytes) {
+    const char* x = (const char*)a;
+    const char* y = (const char*)b;
+    return x < y + bbytes && y < x + abytes;
+}
+
 // per-block scratch of the scaling step: slab partials, s, 1/s, s^(-1/p), and the pool
 // vectors / products / quotients of the multi-Power-Iteration
 size_t scale_scratch_bytes(int B) {
@@ -136,7 +142,8 @@ dash_status run_gemm(dash_ctx* c, const GemmLaunch& g) {
     c->mm_block_products += (double)g.nprob * (double)g.nblocks;
     c->var_launches[variant] += 1;
     c->var_block_products[variant] += (double)g.nprob * (double)g.nblocks;
-    const double fl = (double)g.nprob * (double)g.nblocks * 2.0 * g.B * (double)g.B * g.B * gemm_tile_fraction(g);
+    const double fl = (double)g.nprob * (double)g.nblocks * 2.0 * (g.M ? g.M : g.B) * (double)(g.N ? g.N : g.B) *
+                      (g.K ? g.K : g.B) * gemm_tile_fraction(g);
     c->mm_flops += fl;
     c->var_flops[variant] += fl;
     return DASH_OK;
@@ -710,6 +717,119 @@ dash_status dash_accumulate_factors(dash_ctx* c, const float* G, float* L, float
     // G G^T and G^T G are symmetric bit for bit (same products, same summation order for (i,j) and (j,i))
     DASH_TRY(gemm1(c, problem(G, G, L, L, nullptr, alpha, beta, 0.f, 0, 1), N, B, nullptr, 0, true));
     DASH_TRY(gemm1(c, problem(G, G, R, R, nullptr, alpha, beta, 0.f, 1, 0), N, B, nullptr, 0, true));
+    return DASH_OK;
+}
+
+// ---- ragged gradient blocks (Section 4.1: G_rest of shape (N, Bm, Bn), L_rest (N, Bm, Bm), R_rest (N, Bn, Bn)) ----
+dash_status dash_accumulate_factors_rect(dash_ctx* c, const float* G, float* L, float* R, int64_t N, int Bm, int Bn,
+                                         float beta, float alpha) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(Bm) || !valid_B(Bn))
+        return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and Bm, Bn multiples of 64 (N=%lld Bm=%d Bn=%d)", (long long)N, Bm, Bn);
+    if (N == 0) return DASH_OK;
+    if (!G || !L || !R) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    const size_t gb = (size_t)N * Bm * Bn * 4, lb = (size_t)N * Bm * Bm * 4, rb = (size_t)N * Bn * Bn * 4;
+    if (overlap2(L, lb, G, gb) || overlap2(R, rb, G, gb) || overlap2(L, lb, R, rb))
+        return fail(c, DASH_ERR_INVALID_ARG, "G, L, R must not overlap");
+    HIP_TRY(c, hipSetDevice(c->device));
+    GemmLaunch g;
+    memset(&g, 0, sizeof(g));
+    g.nprob = 1; g.B = Bm; g.nblocks = N; g.half = HALF_NONE;
+    g.sym = c->symmetric ? 1 : 0;       // G G^T and G^T G are symmetric to the last bit
+    // L = beta L + alpha G G^T : (Bm x Bn)(Bn x Bm)
+    g.prob[0] = g.prob[1] = problem(G, G, L, L, nullptr, alpha, beta, 0.f, 0, 1);
+    g.M = Bm; g.N = Bm; g.K = Bn;
+    DASH_TRY(run_gemm(c, g));
+    // R = beta R + alpha G^T G : (Bn x Bm)(Bm x Bn)
+    g.prob[0] = g.prob[1] = problem(G, G, R, R, nullptr, alpha, beta, 0.f, 1, 0);
+    g.M = Bn; g.N = Bn; g.K = Bm;
+    DASH_TRY(run_gemm(c, g));
+    return DASH_OK;
+}
+
+dash_status dash_precondition_rect(dash_ctx* c, const float* Linv, const float* G, const float* Rinv, float* U, int64_t N,
+                                   int Bm, int Bn) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(Bm) || !valid_B(Bn))
+        return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and Bm, Bn multiples of 64 (N=%lld Bm=%d Bn=%d)", (long long)N, Bm, Bn);
+    if (N == 0) return DASH_OK;
+    if (!Linv || !G || !Rinv || !U) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    const size_t gsz = (size_t)Bm * Bn;
+    if (overlap2(U, (size_t)N * gsz * 4, G, (size_t)N * gsz * 4) || overlap2(U, (size_t)N * gsz * 4, Linv, (size_t)N * Bm * Bm * 4) ||
+        overlap2(U, (size_t)N * gsz * 4, Rinv, (size_t)N * Bn * Bn * 4))
+        return fail(c, DASH_ERR_INVALID_ARG, "U overlaps an input");
+    HIP_TRY(c, hipSetDevice(c->device));
+    const size_t per = gsz * sizeof(float);
+    if (!c->ws || c->ws_bytes < per) return fail(c, DASH_ERR_WORKSPACE, "workspace holds %zu bytes, one block needs %zu", c->ws_bytes, per);
+    int64_t chunk = (int64_t)(c->ws_bytes / per);
+    if (chunk > N) chunk = N;
+    float* T = (float*)c->ws;
+    for (int64_t b0 = 0; b0 < N; b0 += chunk) {
+        const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
+        GemmLaunch g;
+        memset(&g, 0, sizeof(g));
+        g.nprob = 1; g.B = Bm; g.nblocks = nb; g.half = HALF_NONE;
+        // T = Linv G : (Bm x Bm)(Bm x Bn)
+        g.prob[0] = g.prob[1] = problem(Linv + (size_t)b0 * Bm * Bm, G + (size_t)b0 * gsz, nullptr, T, nullptr, 1.f, 0.f, 0.f);
+        g.M = Bm; g.N = Bn; g.K = Bm;
+        DASH_TRY(run_gemm(c, g));
+        // U = T Rinv : (Bm x Bn)(Bn x Bn)
+        g.prob[0] = g.prob[1] = problem(T, Rinv + (size_t)b0 * Bn * Bn, nullptr, U + (size_t)b0 * gsz, nullptr, 1.f, 0.f, 0.f);
+        g.M = Bm; g.N = Bn; g.K = Bn;
+        DASH_TRY(run_gemm(c, g));
+    }
+    return DASH_OK;
+}
+
+// ---- block() and its inverse (Section 4.1) ----
+static dash_status block_layer_impl(dash_ctx* c, float* W, int64_t m, int64_t n, int B, float* full, float* row_rest,
+                                    float* col_rest, float* corner, bool scatter) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (m < 0 || n < 0 || B <= 0) return fail(c, DASH_ERR_INVALID_ARG, "need m, n >= 0 and B > 0 (m=%lld n=%lld B=%d)", (long long)m, (long long)n, B);
+    if (m == 0 || n == 0) return DASH_OK;
+    const int64_t Nm = m / B, Nn = n / B;
+    const int rm = (int)(m % B), rn = (int)(n % B);
+    if (!W || (Nm * Nn > 0 && !full) || (rm && Nn && !row_rest) || (rn && Nm && !col_rest) || (rm && rn && !corner))
+        return fail(c, DASH_ERR_INVALID_ARG, "null pointer for a non-empty group");
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, launch_block_copy(W, full, n, 0, 0, B, B, B, Nm, Nn, scatter, c->stream));
+    if (rm) HIP_TRY(c, launch_block_copy(W, row_rest, n, Nm * B, 0, B, rm, B, 1, Nn, scatter, c->stream));
+    if (rn) HIP_TRY(c, launch_block_copy(W, col_rest, n, 0, Nn * B, B, B, rn, Nm, 1, scatter, c->stream));
+    if (rm && rn) HIP_TRY(c, launch_block_copy(W, corner, n, Nm * B, Nn * B, B, rm, rn, 1, 1, scatter, c->stream));
+    return DASH_OK;
+}
+
+dash_status dash_block_layer(dash_ctx* c, const float* W, int64_t m, int64_t n, int B, float* full, float* row_rest,
+                             float* col_rest, float* corner) {
+    return block_layer_impl(c, const_cast<float*>(W), m, n, B, full, row_rest, col_rest, corner, false);
+}
+
+dash_status dash_unblock_layer(dash_ctx* c, float* W, int64_t m, int64_t n, int B, const float* full,
+                               const float* row_rest, const float* col_rest, const float* corner) {
+    return block_layer_impl(c, W, m, n, B, const_cast<float*>(full), const_cast<float*>(row_rest),
+                            const_cast<float*>(col_rest), const_cast<float*>(corner), true);
+}
+
+// ---- 1-D parameters (Section 4.1, normalisation layers): gradient blocks are vectors, only L exists ----
+dash_status dash_accumulate_vector(dash_ctx* c, const float* g, float* L, int64_t N, int B, float beta, float alpha) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64");
+    if (N == 0) return DASH_OK;
+    if (!g || !L) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, launch_outer_accumulate(g, L, N, B, beta, alpha, c->stream));
+    return DASH_OK;
+}
+
+dash_status dash_precondition_vector(dash_ctx* c, const float* Linv, const float* g, float* u, int64_t N, int B) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64");
+    if (N == 0) return DASH_OK;
+    if (!Linv || !g || !u) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    if (overlap(u, g, (size_t)N * B * 4) || overlap2(u, (size_t)N * B * 4, Linv, (size_t)N * B * B * 4))
+        return fail(c, DASH_ERR_INVALID_ARG, "u overlaps an input");
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, launch_matvec(Linv, g, u, N, B, c->stream));
     return DASH_OK;
 }
 

@@ -208,6 +208,70 @@ __global__ __launch_bounds__(NT) void graft_apply_kernel(const float* __restrict
     }
 }
 
+// ---- 1-D parameters (normalisation layers, paper Section 4.1): the gradient block is a vector ----
+// L_b <- beta L_b + alpha g_b g_b^T ; grid = (B*B/4/NT, nblocks)
+__global__ __launch_bounds__(NT) void outer_accumulate_kernel(const float* __restrict__ g, float* __restrict__ L, int B,
+                                                             float beta, float alpha) {
+    const int64_t b = blockIdx.y;
+    const int f = blockIdx.x * NT + threadIdx.x;
+    const int qpr = B / 4;
+    if (f >= B * qpr) return;
+    const int r = f / qpr, c = 4 * (f % qpr);
+    const float* __restrict__ gb = g + (size_t)b * B;
+    const float gi = alpha * gb[r];
+    const v4f gj = *reinterpret_cast<const v4f*>(gb + c);
+    float* __restrict__ p = L + (size_t)b * B * B + (size_t)r * B + c;
+    v4f l = *reinterpret_cast<const v4f*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) l[i] = beta * l[i] + gi * gj[i];
+    *reinterpret_cast<v4f*>(p) = l;
+}
+
+// u_b = X_b g_b ; grid = (B/16, nblocks); each of the 4 wavefronts of a workgroup owns 4 rows,
+// lanes stride along the row with 16-byte loads, wavefront shuffle reduction
+__global__ __launch_bounds__(NT) void matvec_kernel(const float* __restrict__ X, const float* __restrict__ g,
+                                                   float* __restrict__ u, int B) {
+    const int64_t b = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float* __restrict__ gb = g + (size_t)b * B;
+    for (int rr = 0; rr < 4; ++rr) {
+        const int r = blockIdx.x * 16 + wave * 4 + rr;
+        const float* __restrict__ xr = X + (size_t)b * B * B + (size_t)r * B;
+        float acc = 0.f;
+        for (int k = 4 * lane; k < B; k += 256) {
+            const v4f x = *reinterpret_cast<const v4f*>(xr + k);
+            const v4f v = *reinterpret_cast<const v4f*>(gb + k);
+            acc += x[0] * v[0] + x[1] * v[1] + x[2] * v[2] + x[3] * v[3];
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) u[(size_t)b * B + r] = acc;
+    }
+}
+
+// ---- block() / its inverse (paper Section 4.1): sub-matrices of a row-major layer <-> a stack ----
+// stack[(im*nn + in)][r][c] <-> W[(r0 + im*B + r) * ld + c0 + in*B + c], r < bm, c < bn.
+// VEC = 4: 16-byte accesses (needs ld, c0, B, bn multiples of 4 and aligned bases); VEC = 1: any shape.
+// grid = (ceil(bm*bn/VEC / NT), nm*nn)
+template <int VEC, bool SCATTER>
+__global__ __launch_bounds__(NT) void block_copy_kernel(float* __restrict__ W, float* __restrict__ stack, int64_t ld,
+                                                       int64_t r0, int64_t c0, int B, int bm, int bn, int nn) {
+    const int64_t blk = blockIdx.y;
+    const int64_t im = blk / nn, in = blk % nn;
+    const int per_row = bn / VEC;
+    const int64_t f = (int64_t)blockIdx.x * NT + threadIdx.x;
+    if (f >= (int64_t)bm * per_row) return;
+    const int r = (int)(f / per_row), c = (int)(f % per_row) * VEC;
+    float* w = W + (r0 + im * B + r) * ld + c0 + in * B + c;
+    float* s = stack + blk * bm * bn + (int64_t)r * bn + c;
+    if (VEC == 4) {
+        if (SCATTER) *reinterpret_cast<v4f*>(w) = *reinterpret_cast<const v4f*>(s);
+        else *reinterpret_cast<v4f*>(s) = *reinterpret_cast<const v4f*>(w);
+    } else {
+        if (SCATTER) *w = *s;
+        else *s = *w;
+    }
+}
+
 // ---- launchers ------------------------------------------------------------------------
 
 
@@ -243,6 +307,52 @@ hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps
                            h2 ? static_cast<unsigned short*>(h2) + o : nullptr, nonfinite ? nonfinite + b0 : nullptr,
                            half, l1 ? static_cast<unsigned short*>(l1) + o : nullptr,
                            l2 ? static_cast<unsigned short*>(l2) + o : nullptr);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_outer_accumulate(const float* g, float* L, int64_t nblocks, int B, float beta, float alpha,
+                                   hipStream_t stream) {
+    const unsigned gx = (unsigned)(((size_t)B * B / 4 + NT - 1) / NT);
+    for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
+        const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
+        hipLaunchKernelGGL(outer_accumulate_kernel, dim3(gx, (unsigned)nb), dim3(NT), 0, stream, g + (size_t)b0 * B,
+                           L + (size_t)b0 * B * B, B, beta, alpha);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_matvec(const float* X, const float* g, float* u, int64_t nblocks, int B, hipStream_t stream) {
+    for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
+        const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
+        hipLaunchKernelGGL(matvec_kernel, dim3(B / 16, (unsigned)nb), dim3(NT), 0, stream, X + (size_t)b0 * B * B,
+                           g + (size_t)b0 * B, u + (size_t)b0 * B, B);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_block_copy(float* W, float* stack, int64_t ld, int64_t r0, int64_t c0, int B, int bm, int bn,
+                             int64_t nm, int64_t nn, bool scatter, hipStream_t stream) {
+    if (nm <= 0 || nn <= 0 || bm <= 0 || bn <= 0) return hipSuccess;
+    if (nn > 0x7fffffff) return hipErrorInvalidValue;
+    const bool vec = ld % 4 == 0 && c0 % 4 == 0 && B % 4 == 0 && bn % 4 == 0 && (uintptr_t)W % 16 == 0 &&
+                     (uintptr_t)stack % 16 == 0;
+    const int V = vec ? 4 : 1;
+    const unsigned gx = (unsigned)(((int64_t)bm * (bn / V) + NT - 1) / NT);
+    const int64_t total = nm * nn;
+    // grid.y is limited to 65535: whole rows of blocks per launch (all of them in the usual case)
+    const int64_t rows_per = nn > 65535 ? 0 : 65535 / nn;
+    if (rows_per == 0) return hipErrorInvalidValue;
+    (void)total;
+    for (int64_t m0 = 0; m0 < nm; m0 += rows_per) {
+        const int64_t mr = nm - m0 < rows_per ? nm - m0 : rows_per;
+        dim3 grid(gx, (unsigned)(mr * nn)), block(NT);
+        float* st = stack + m0 * nn * bm * bn;
+        const int64_t rr = r0 + m0 * B;
+        if (vec && scatter) hipLaunchKernelGGL((block_copy_kernel<4, true>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, (int)nn);
+        else if (vec) hipLaunchKernelGGL((block_copy_kernel<4, false>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, (int)nn);
+        else if (scatter) hipLaunchKernelGGL((block_copy_kernel<1, true>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, (int)nn);
+        else hipLaunchKernelGGL((block_copy_kernel<1, false>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, (int)nn);
     }
     return hipGetLastError();
 }

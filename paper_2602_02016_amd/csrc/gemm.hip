@@ -132,9 +132,11 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     const int64_t per = W / NUM_XCD, rem = W % NUM_XCD;
     const int64_t lid = xcd * per + (xcd < rem ? xcd : rem) + local;
 
-    const int B = g.B;
-    const int tiles = B / TILE;
-    const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles;
+    // op(A) is Md x Kd, op(B) is Kd x Nd, C is Md x Nd (all equal to g.B unless a rectangular launch
+    // sets g.M, g.N, g.K: ragged gradient blocks, paper Section 4.1 "rest" blocks)
+    const int Md = g.M ? g.M : g.B, Nd = g.N ? g.N : g.B, Kd = g.K ? g.K : g.B;
+    const int tiles = Md / TILE, tiles_n = Nd / TILE;
+    const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles_n;
     const int64_t blk = lid / ((int64_t)g.nprob * T);
     const int r1 = (int)(lid % ((int64_t)g.nprob * T));
     const int pi = r1 / T;
@@ -146,16 +148,17 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
         while (left >= len) { left -= len; --len; ++ti; }
         tj = ti + left;
     } else {
-        ti = tile / tiles;
-        tj = tile % tiles;
+        ti = tile / tiles_n;
+        tj = tile % tiles_n;
     }
     const int row0 = ti * TILE;
     const int col0 = tj * TILE;
 
     const GemmProblem& P = g.prob[pi];
-    const size_t boff = (size_t)blk * B * B;
-    const float* __restrict__ Ab = static_cast<const float*>(P.A) + boff;
-    const float* __restrict__ Bb = static_cast<const float*>(P.B) + boff;
+    const size_t boff = (size_t)blk * Md * Nd;          // C, D, C2
+    const float* __restrict__ Ab = static_cast<const float*>(P.A) + (size_t)blk * Md * Kd;
+    const float* __restrict__ Bb = static_cast<const float*>(P.B) + (size_t)blk * Kd * Nd;
+    const int lda = TA ? Md : Kd, ldb = TB ? Kd : Nd;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
@@ -169,20 +172,20 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     v4f ra[NV], rb[NV];
-    load_slab<TILE, A_KC>(Ab, B, row0, 0, ra);
-    load_slab<TILE, B_KC>(Bb, B, col0, 0, rb);
+    load_slab<TILE, A_KC>(Ab, lda, row0, 0, ra);
+    load_slab<TILE, B_KC>(Bb, ldb, col0, 0, rb);
     store_slab<TILE, A_KC>(lds, ra);
     store_slab<TILE, B_KC>(lds + SLAB, rb);
     __syncthreads();
 
-    const int KT = B / BK;
+    const int KT = Kd / BK;
     for (int kt = 0; kt < KT; ++kt) {
         const float* sa = lds + (kt & 1) * 2 * SLAB;
         const float* sb = sa + SLAB;
         const bool more = kt + 1 < KT;
         if (more) {
-            load_slab<TILE, A_KC>(Ab, B, row0, (kt + 1) * BK, ra);
-            load_slab<TILE, B_KC>(Bb, B, col0, (kt + 1) * BK, rb);
+            load_slab<TILE, A_KC>(Ab, lda, row0, (kt + 1) * BK, ra);
+            load_slab<TILE, B_KC>(Bb, ldb, col0, (kt + 1) * BK, rb);
         }
 #pragma unroll
         for (int c = 0; c < BK / 8; ++c) {
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const int row = rbase + m;
-                    const size_t off = (size_t)row * B + col;
+                    const size_t off = (size_t)row * Nd + col;
                     float v = alpha * acc[i][j][4 * q + m];
                     if (Db) v += beta * Db[off];
                     if (row == col) v += gamma;
@@ -247,8 +250,8 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
                     }
                 }
                 if (mirror) {
-                    *reinterpret_cast<v4f*>(Cb + (size_t)col * B + rbase) = out;
-                    if (C2b) *reinterpret_cast<v4f*>(C2b + (size_t)col * B + rbase) = out2;
+                    *reinterpret_cast<v4f*>(Cb + (size_t)col * Nd + rbase) = out;
+                    if (C2b) *reinterpret_cast<v4f*>(C2b + (size_t)col * Nd + rbase) = out2;
                 }
             }
         }
@@ -257,8 +260,8 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
 
 template <int TILE>
 static hipError_t launch_tile(const GemmLaunch& g, hipStream_t stream) {
-    const int tiles = g.B / TILE;
-    const int64_t W = g.nblocks * g.nprob * (g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles);
+    const int tiles = (g.M ? g.M : g.B) / TILE, tiles_n = (g.N ? g.N : g.B) / TILE;
+    const int64_t W = g.nblocks * g.nprob * (g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles_n);
     if (W <= 0) return hipSuccess;
     if (W > 0x7fffffffLL) return hipErrorInvalidValue;
     // both products of a launch must use the same transpose flags (one kernel instance)
@@ -273,6 +276,10 @@ static hipError_t launch_tile(const GemmLaunch& g, hipStream_t stream) {
 
 hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
     if (g.nprob < 1 || g.nprob > 2 || g.B <= 0 || g.B % 64) return hipErrorInvalidValue;
+    if (g.M % 64 || g.N % 64 || g.K % 64 || g.M < 0 || g.N < 0 || g.K < 0) return hipErrorInvalidValue;
+    const bool rect = g.M || g.N || g.K;
+    if (rect && g.half != HALF_NONE) return hipErrorInvalidValue;              // rectangular: fp32 only
+    if (g.sym && (g.M ? g.M : g.B) != (g.N ? g.N : g.B)) return hipErrorInvalidValue;   // mirroring needs a square output
     if (g.nprob == 2 && (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
         return hipErrorInvalidValue;
     if (g.half != HALF_NONE) return launch_gemm_half(g, stream);
@@ -281,14 +288,17 @@ hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
 
 // 128-wide tiles when they still give the chip enough workgroups, else 64-wide
 int gemm_tile_edge(const GemmLaunch& g) {
-    const bool big = (g.B % 128 == 0) && (g.nblocks * g.nprob * (int64_t)(g.B / 128) * (g.B / 128) >= 256);
+    const int Md = g.M ? g.M : g.B, Nd = g.N ? g.N : g.B, Kd = g.K ? g.K : g.B;
+    (void)Kd;                                     // the K loop only needs K % 16 == 0
+    const bool big = Md % 128 == 0 && Nd % 128 == 0 &&
+                     g.nblocks * g.nprob * (int64_t)(Md / 128) * (Nd / 128) >= 256;
     return big ? 128 : 64;
 }
 
 // fraction of the B x B output tiles a launch computes (1, or (t+1)/(2t) in symmetric mode)
 double gemm_tile_fraction(const GemmLaunch& g) {
     if (!g.sym) return 1.0;
-    const int t = g.B / gemm_tile_edge(g);
+    const int t = (g.M ? g.M : g.B) / gemm_tile_edge(g);
     return (double)(t + 1) / (2.0 * t);
 }
 

@@ -42,6 +42,8 @@ struct GemmLaunch {
     GemmProblem prob[2];
     int nprob;
     int B;                 // block edge
+    int M, N, K;           // 0 = B.  Non-zero: op(A) is M x K, op(B) is K x N, C is M x N per block
+                           // (contiguous stacks; fp32 launches only; symmetric mode needs M == N)
     int64_t nblocks;       // blocks in this launch
     int32_t* nonfinite;    // per-block flag for prob[0]'s output, or null
     int half;              // HALF_NONE: fp32 MFMA operands; HALF_BF16 / HALF_FP16: 16-bit operands
@@ -79,6 +81,17 @@ size_t power_iteration_bytes_per_block(int B);
 hipError_t launch_power_iteration(const float* A, int64_t nblocks, int B, float eps, const float* V0, int pool,
                                   int sweeps, int p, float* V, float* W, float* q, float* s, float* inv_s,
                                   float* unscale, hipStream_t stream);
+
+// 1-D parameters: L_b <- beta L_b + alpha g_b g_b^T (g: [n][B]);  u_b = X_b g_b
+hipError_t launch_outer_accumulate(const float* g, float* L, int64_t nblocks, int B, float beta, float alpha,
+                                   hipStream_t stream);
+hipError_t launch_matvec(const float* X, const float* g, float* u, int64_t nblocks, int B, hipStream_t stream);
+
+// block() of a row-major layer W (leading dimension ld): the nm x nn grid of bm x bn sub-matrices with
+// origin (r0, c0) and pitch B in both directions <-> stack [nm*nn][bm][bn] (row-major block order).
+// scatter = false: W -> stack; true: stack -> W.
+hipError_t launch_block_copy(float* W, float* stack, int64_t ld, int64_t r0, int64_t c0, int B, int bm, int bn,
+                             int64_t nm, int64_t nn, bool scatter, hipStream_t stream);
 
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
 

@@ -1,0 +1,100 @@
+"""Pins of oracle/blocking.py: the worked example of paper Section 4.1 (shapes and counts), round
+trips, the blocked step against the un-blocked definition, and the 1-D case against closed forms."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import blocking, shampoo
+from oracle.evd import inverse_root_evd
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_blocking_example.txt")
+
+
+def _golden():
+    out = {}
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        k, v = [t.strip() for t in line.split("=")]
+        out[k] = tuple(int(t) for t in v.split(",")) if "," in v else int(v)
+    return out
+
+
+def test_paper_worked_example_shapes():
+    g = _golden()
+    sh = blocking.stack_shapes(g["V"], g["E"], g["B"])
+    assert sh["G_full"] == g["G_full"] and sh["G_row_rest"] == g["G_rest"]
+    assert sh["L_row_rest"] == g["L_rest"] and sh["R_row_rest"] == g["R_rest"]
+    assert sh["S_full"] == g["S_full"] and sh["S_rest"] == [g["S_rest"]]
+    assert "G_col_rest" not in sh and "G_corner" not in sh
+    # the classification head is the transposed layer: L_rest and R_rest swap roles
+    sh_t = blocking.stack_shapes(g["E"], g["V"], g["B"])
+    assert sh_t["R_col_rest"] == g["L_rest"] and sh_t["L_col_rest"] == g["R_rest"] and sh_t["S_full"] == g["S_full"]
+    # the library's host-side plan gives the same group shapes
+    from paper_2602_02016_amd.binding import layer_plan
+    plan = layer_plan(g["V"], g["E"], g["B"])
+    assert plan["full"] == g["G_full"] and plan["row_rest"] == g["G_rest"] and plan["col_rest"][0] == 0 and plan["corner"][0] == 0
+
+
+def test_small_scale_example_array_shapes():
+    # the same layer scaled down 64x: (500, 32), B = 16 -> 31 x 2 full blocks and 2 rest blocks of 4 rows
+    W = np.arange(500 * 32, dtype=np.float64).reshape(500, 32)
+    gr = blocking.block_layer(W, 16)
+    assert gr["full"].shape == (62, 16, 16) and gr["row_rest"].shape == (2, 4, 16)
+    assert gr["col_rest"].shape[0] == 0 and gr["corner"].shape[0] == 0
+    # block (i, j) sits at index i*Nn + j: element (0,0) of block (3,1) is W[48, 16]
+    assert gr["full"][3 * 2 + 1][0, 0] == W[48, 16] and gr["row_rest"][1][3, 15] == W[499, 31]
+
+
+@pytest.mark.parametrize("m,n,B", [(7, 5, 2), (8, 8, 4), (3, 9, 4), (10, 3, 4), (5, 5, 8)])
+def test_round_trip_and_every_element_once(m, n, B):
+    W = np.arange(m * n, dtype=np.float64).reshape(m, n) + 1
+    gr = blocking.block_layer(W, B)
+    assert sum(v.size for v in gr.values()) == m * n
+    allv = np.sort(np.concatenate([v.ravel() for v in gr.values()]))
+    assert np.array_equal(allv, np.sort(W.ravel()))
+    assert np.array_equal(blocking.unblock_layer(gr, m, n, B), W)
+
+
+def test_blocked_step_equals_per_group_stack_step():
+    """layer_step (slices of the layer) against the stacked route: block -> accumulate/precondition per
+    group with oracle.shampoo -> unblock."""
+    rng = np.random.default_rng(5)
+    m, n, B = 11, 10, 4
+    Wg = rng.standard_normal((m, n))
+    U_ref, fac = blocking.layer_step(Wg, None, B, beta=0.9, eps=1e-3, p=4)
+    gr = blocking.block_layer(Wg, B)
+    out = {}
+    for k, G in gr.items():
+        if G.shape[0] == 0:
+            out[k] = G
+            continue
+        L0 = np.zeros((G.shape[0], G.shape[1], G.shape[1])); R0 = np.zeros((G.shape[0], G.shape[2], G.shape[2]))
+        L, R = shampoo.accumulate_factors(G, L0, R0, 0.9)
+        out[k] = shampoo.precondition(inverse_root_evd(L, 4, 1e-3), G, inverse_root_evd(R, 4, 1e-3))
+    U = blocking.unblock_layer(out, m, n, B)
+    assert np.allclose(U, U_ref, rtol=1e-10, atol=1e-12)
+    # one block covering the whole layer (B >= m, n) is full-matrix Shampoo
+    U_one, _ = blocking.layer_step(Wg, None, 16, beta=0.9, eps=1e-3, p=4)
+    L = 0.1 * Wg @ Wg.T; R = 0.1 * Wg.T @ Wg
+    assert np.allclose(U_one, inverse_root_evd(L, 4, 1e-3) @ Wg @ inverse_root_evd(R, 4, 1e-3), rtol=1e-10, atol=1e-12)
+
+
+def test_vector_step_closed_form():
+    """From L = 0, one accumulation gives the rank-one L = alpha g g^T, whose damped inverse square
+    root acts on g as (alpha |g|^2 + eps)^(-1/2): u = g / sqrt(alpha |g|^2 + eps)."""
+    rng = np.random.default_rng(9)
+    N, E, B = 3, 8, 4
+    grads = rng.standard_normal((N, E))
+    L0 = np.zeros((N * E // B, B, B))
+    U, L1 = blocking.norm_layers_step(grads, L0, B, beta=0.75, eps=1e-2)
+    g = grads.reshape(-1, B)
+    expect = g / np.sqrt(0.25 * (g * g).sum(axis=1, keepdims=True) + 1e-2)
+    assert np.allclose(U, expect.reshape(N, E), rtol=1e-10)
+    assert np.allclose(L1, 0.25 * g[:, :, None] * g[:, None, :])
+    # a vector is a B x 1 matrix: the matrix functions give the same L and the same u
+    Lm, Rm = shampoo.accumulate_factors(g[:, :, None], L0, np.zeros((g.shape[0], 1, 1)), 0.75)
+    assert np.allclose(Lm, L1) and np.allclose(Rm[:, 0, 0], 0.25 * (g * g).sum(axis=1))
+    assert np.allclose(blocking.precondition_vector(L1, g)[:, :, None], np.matmul(L1, g[:, :, None]))
