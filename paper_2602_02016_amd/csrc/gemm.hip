@@ -298,7 +298,7 @@ int gemm_tile_edge(const GemmLaunch& g) {
 // fraction of the B x B output tiles a launch computes (1, or (t+1)/(2t) in symmetric mode)
 double gemm_tile_fraction(const GemmLaunch& g) {
     if (!g.sym) return 1.0;
-    const int t = (g.M ? g.M : g.B) / gemm_tile_edge(g);
+    const int t = (g.M ? g.M : g.B) / (g.half != HALF_NONE ? gemm_half_tile_edge(g) : gemm_tile_edge(g));
     return (double)(t + 1) / (2.0 * t);
 }
 

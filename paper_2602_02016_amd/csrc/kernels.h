@@ -52,7 +52,8 @@ struct GemmLaunch {
 };
 
 hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream);
-int gemm_tile_edge(const GemmLaunch& g);          // tile edge launch_gemm picks (64 or 128)
+int gemm_tile_edge(const GemmLaunch& g);          // tile edge launch_gemm picks for fp32 (64 or 128)
+int gemm_half_tile_edge(const GemmLaunch& g);     // tile edge of a 16-bit launch (64 or 128)
 double gemm_tile_fraction(const GemmLaunch& g);   // share of output tiles actually computed
 hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream);   // gemm_half.hip
 
