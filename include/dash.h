@@ -274,6 +274,56 @@ typedef struct {
  * U = X_L G X_R -> (if graft) grafted update.  args: host pointer. */
 dash_status dash_step(dash_ctx* ctx, const dash_step_args* args);
 
+/* ---- all layers of a GPU in shared stacks (Section 4.1, the variant the paper calls DashGpu) ---- */
+
+/* The blocks of every layer are bucketed by shape and every factor of one size, whatever layer or side
+ * it belongs to, sits in one stack: a step is one block() per layer, one accumulate and one precondition
+ * per bucket, and ONE inverse-root call per factor size (for the paper's embedding example:
+ * stack(L_full, R_full, R_rest) of 126 blocks of 1024 and L_rest of 2 blocks of 256).  Between refreshes
+ * (the paper's recomputation frequency f > 1) the stored roots are reused.
+ * A layer is m x n row-major; n = 0 marks a 1-D parameter (normalisation layer) of m entries, which is cut
+ * into vectors of B entries with a left factor only and root p_vec (the paper uses 2).  m mod B, n mod B
+ * must be multiples of 64 (DASH_ERR_UNSUPPORTED otherwise). */
+typedef struct { int64_t m, n; } dash_layer_shape;
+typedef struct dash_model dash_model;
+typedef struct {
+    int32_t n_layers, n_buckets, n_stacks, B;
+    int64_t n_gradient_blocks, n_factor_blocks;
+    int64_t arena_bytes;        /* device memory the model needs: factors, roots, staging of G and U */
+} dash_model_info;
+
+/* Host-side planning only; the model keeps ctx (which must outlive it).  p, p_vec in {2, 4}. */
+dash_status dash_model_create(dash_ctx* ctx, const dash_layer_shape* layers, int n_layers, int B,
+                              int p, int p_vec, dash_model** out);
+dash_status dash_model_destroy(dash_model* model);
+const char* dash_model_last_error(const dash_model* model);
+dash_status dash_model_get_info(const dash_model* model, dash_model_info* info);
+/* bucket i: block shape (bn = 0: vectors of bm entries) and number of blocks; any output may be null */
+dash_status dash_model_get_bucket(const dash_model* model, int i, int32_t* bm, int32_t* bn, int64_t* count);
+/* factor stack i: block edge, root, number of blocks, and (once the arena is set, else null) the device
+ * addresses of its factors S [count][size][size] and roots X; any output may be null */
+dash_status dash_model_get_stack(const dash_model* model, int i, int32_t* size, int32_t* p, int64_t* count,
+                                 float** S, float** X);
+/* workspace the context needs for dash_model_step with this method / precision (a smaller one makes the
+ * inverse root and the rectangular precondition run in chunks) */
+size_t dash_model_workspace_bytes(const dash_model* model, dash_method method, dash_precision precision);
+/* Caller-owned device memory of at least arena_bytes, 256-byte aligned; the caller zeroes it once
+ * (factors start at zero) and keeps it for the life of the model: it is the optimizer state. */
+dash_status dash_model_set_arena(dash_model* model, void* dev_ptr, size_t bytes);
+
+typedef struct {
+    const float* const* grads;  /* host array [n_layers] of device pointers, layer l: [m][n] (or [m]) */
+    float* const* updates;      /* host array [n_layers] of device pointers, same shapes: U per layer */
+    float beta, alpha, eps;
+    int32_t method, iters, scaling, precision;
+    int32_t refresh;            /* 0: skip the inverse roots and precondition with the stored ones */
+    const double* cheb_coeffs;  /* as in dash_inverse_root */
+    double cheb_a, cheb_b;
+    int32_t* nonfinite_out;     /* dev [n_factor_blocks] in stack order, or NULL */
+} dash_model_step_args;
+
+dash_status dash_model_step(dash_model* model, const dash_model_step_args* args);
+
 #ifdef __cplusplus
 }
 #endif

@@ -106,6 +106,55 @@ def layer_step(W_grad, factors: dict | None, B: int, beta: float, eps: float, p:
     return U, new
 
 
+def layer_step_cached(W_grad, factors, roots, B: int, beta: float, eps: float, p: int = 4, alpha: float | None = None,
+                      refresh: bool = True, inverse_root=None):
+    """layer_step with the paper's recomputation frequency (Section 4.1, f > 1): the factors are updated
+    at every step, the inverse roots only when `refresh` is true; otherwise the roots of the last refresh
+    (`roots`: (r0, c0) -> (X_L, X_R)) precondition the new gradient.  Returns (U, factors, roots)."""
+    if alpha is None:
+        alpha = 1.0 - beta
+    if inverse_root is None:
+        inverse_root = inverse_root_evd
+    G = np.asarray(W_grad, dtype=np.float64)
+    m, n = G.shape
+    U = np.zeros_like(G)
+    new_f, new_r = {}, {}
+    for r0 in range(0, m, B):
+        for c0 in range(0, n, B):
+            Gb = G[r0:min(r0 + B, m), c0:min(c0 + B, n)]
+            L, R = (factors or {}).get((r0, c0), (np.zeros((Gb.shape[0],) * 2), np.zeros((Gb.shape[1],) * 2)))
+            L = beta * L + alpha * Gb @ Gb.T
+            R = beta * R + alpha * Gb.T @ Gb
+            new_f[(r0, c0)] = (L, R)
+            new_r[(r0, c0)] = (inverse_root(L, p, eps), inverse_root(R, p, eps)) if refresh else roots[(r0, c0)]
+            XL, XR = new_r[(r0, c0)]
+            U[r0:r0 + Gb.shape[0], c0:c0 + Gb.shape[1]] = XL @ Gb @ XR
+    return U, new_f, new_r
+
+
+def vector_param_step_cached(grad, factors, roots, B: int, beta: float, eps: float, p: int = 2,
+                             alpha: float | None = None, refresh: bool = True, inverse_root=None):
+    """One 1-D parameter of E entries: pieces of B entries (and one of E mod B), each with a left factor
+    only: L <- beta L + alpha g g^T, u = (L + eps I)^(-1/p) g (roots as in layer_step_cached).
+    factors, roots: lists per piece (None = zeros / nothing cached).  Returns (u, factors, roots)."""
+    if alpha is None:
+        alpha = 1.0 - beta
+    if inverse_root is None:
+        inverse_root = inverse_root_evd
+    g = np.asarray(grad, dtype=np.float64)
+    E = g.shape[0]
+    u = np.zeros_like(g)
+    new_f, new_r = [], []
+    for j, a in enumerate(range(0, E, B)):
+        gj = g[a:min(a + B, E)]
+        L = factors[j] if factors else np.zeros((gj.shape[0],) * 2)
+        L = beta * L + alpha * np.outer(gj, gj)
+        new_f.append(L)
+        new_r.append(inverse_root(L, p, eps) if refresh else roots[j])
+        u[a:a + gj.shape[0]] = new_r[j] @ gj
+    return u, new_f, new_r
+
+
 # ---- normalisation layers (Section 4.1): vectors as B x 1 blocks, left factor only, p = 2 ----
 def accumulate_vector(g, L, beta: float, alpha: float | None = None):
     """L_i <- beta L_i + alpha g_i g_i^T for g of shape (N, B)."""

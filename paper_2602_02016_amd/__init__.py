@@ -6,4 +6,4 @@ pointers of torch tensors.  Importing this package does not load the library; th
 first use of `binding.Dash` does, and fails loudly if it has not been built.
 """
 from . import binding  # noqa: F401
-from .binding import Dash, DashError, chebyshev_fit, load_library  # noqa: F401
+from .binding import Dash, DashError, DashModel, chebyshev_fit, load_library, model_plan  # noqa: F401

@@ -54,6 +54,24 @@ class _StepArgs(C.Structure):
     ]
 
 
+class _LayerShape(C.Structure):
+    _fields_ = [("m", C.c_int64), ("n", C.c_int64)]
+
+
+class _ModelInfo(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_buckets", C.c_int32), ("n_stacks", C.c_int32), ("B", C.c_int32),
+                ("n_gradient_blocks", C.c_int64), ("n_factor_blocks", C.c_int64), ("arena_bytes", C.c_int64)]
+
+
+class _ModelStepArgs(C.Structure):
+    _fields_ = [("grads", C.POINTER(C.c_void_p)), ("updates", C.POINTER(C.c_void_p)),
+                ("beta", C.c_float), ("alpha", C.c_float), ("eps", C.c_float),
+                ("method", C.c_int32), ("iters", C.c_int32), ("scaling", C.c_int32), ("precision", C.c_int32),
+                ("refresh", C.c_int32),
+                ("cheb_coeffs", C.POINTER(C.c_double)), ("cheb_a", C.c_double), ("cheb_b", C.c_double),
+                ("nonfinite_out", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -88,6 +106,18 @@ def load_library(path: str = LIB_PATH):
     lib.dash_precondition_vector.argtypes = [vp, vp, vp, vp, i64, i32]
     lib.dash_block_layer.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.dash_unblock_layer.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.dash_model_create.argtypes = [vp, C.POINTER(_LayerShape), i32, i32, i32, i32, C.POINTER(vp)]
+    lib.dash_model_destroy.argtypes = [vp]
+    lib.dash_model_last_error.argtypes = [vp]
+    lib.dash_model_last_error.restype = C.c_char_p
+    lib.dash_model_get_info.argtypes = [vp, C.POINTER(_ModelInfo)]
+    lib.dash_model_get_bucket.argtypes = [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(i64)]
+    lib.dash_model_get_stack.argtypes = [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(i64),
+                                         C.POINTER(vp), C.POINTER(vp)]
+    lib.dash_model_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.dash_model_workspace_bytes.restype = C.c_size_t
+    lib.dash_model_set_arena.argtypes = [vp, vp, C.c_size_t]
+    lib.dash_model_step.argtypes = [vp, C.POINTER(_ModelStepArgs)]
     lib.dash_block_norms.argtypes = [vp, vp, i64, i32, f32, i32, vp]
     lib.dash_inverse_root.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, f32, i32, i32,
                                       C.POINTER(f64), f64, f64, vp, vp]
@@ -97,7 +127,9 @@ def load_library(path: str = LIB_PATH):
     lib.dash_step.argtypes = [vp, C.POINTER(_StepArgs)]
     for name in ("dash_create", "dash_destroy", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
                  "dash_set_symmetric", "dash_set_power_iteration", "dash_accumulate_factors_rect",
-                 "dash_block_layer", "dash_unblock_layer",
+                 "dash_block_layer", "dash_unblock_layer", "dash_model_create", "dash_model_destroy",
+                 "dash_model_get_info", "dash_model_get_bucket", "dash_model_get_stack", "dash_model_set_arena",
+                 "dash_model_step",
                  "dash_precondition_rect", "dash_accumulate_vector", "dash_precondition_vector",
                  "dash_get_stats", "dash_gemm_batched", "dash_accumulate_factors", "dash_block_norms",
                  "dash_inverse_root", "dash_chebyshev_fit", "dash_precondition", "dash_graft_update", "dash_step"):
@@ -405,3 +437,113 @@ class Dash:
             self.ensure_workspace(2 * n, b, method, p, precision, workspace_max_bytes)
         self._check(self.lib.dash_step(self.h, C.byref(a)))
         return U
+
+
+def model_plan(layers, B: int, p: int = 4, p_vec: int = 2, ctx_handle=None):
+    """Host-side plan of dash_model_create for a list of layer shapes ((m, n), or (m,) / (m, 0) for a
+    1-D parameter): dict(info=..., buckets=[(bm, bn, count)], stacks=[(size, p, count)]).  Needs no GPU
+    when ctx_handle is None (planning never touches the context)."""
+    lib = load_library()
+    arr = (_LayerShape * len(layers))(*[_LayerShape(int(s[0]), int(s[1]) if len(s) > 1 else 0) for s in layers])
+    h = C.c_void_p()
+    # planning only stores the context pointer; a dummy non-null value is enough without a GPU
+    st = lib.dash_model_create(ctx_handle if ctx_handle is not None else C.c_void_p(1), arr, len(layers), B, p, p_vec,
+                               C.byref(h))
+    if st != OK:
+        raise DashError(st, "dash_model_create: " + lib.dash_status_string(st).decode())
+    try:
+        return _describe_model(lib, h)
+    finally:
+        lib.dash_model_destroy(h)
+
+
+def _describe_model(lib, h):
+    info = _ModelInfo()
+    lib.dash_model_get_info(h, C.byref(info))
+    buckets, stacks = [], []
+    for i in range(info.n_buckets):
+        bm, bn, cnt = C.c_int32(), C.c_int32(), C.c_int64()
+        lib.dash_model_get_bucket(h, i, C.byref(bm), C.byref(bn), C.byref(cnt))
+        buckets.append((bm.value, bn.value, cnt.value))
+    for i in range(info.n_stacks):
+        size, p, cnt = C.c_int32(), C.c_int32(), C.c_int64()
+        lib.dash_model_get_stack(h, i, C.byref(size), C.byref(p), C.byref(cnt), None, None)
+        stacks.append((size.value, p.value, cnt.value))
+    return dict(info={k: getattr(info, k) for k, _ in _ModelInfo._fields_}, buckets=buckets, stacks=stacks)
+
+
+class DashModel:
+    """All layers of a model in shared stacks (dash_model_* of dash.h).  The arena (optimizer state) is a
+    torch tensor owned by this object, zero-initialised."""
+
+    def __init__(self, dash: Dash, layers, B: int, p: int = 4, p_vec: int = 2):
+        import torch
+        self.dash, self.lib = dash, dash.lib
+        self.shapes = [(int(s[0]), int(s[1]) if len(s) > 1 else 0) for s in layers]
+        arr = (_LayerShape * len(self.shapes))(*[_LayerShape(m, n) for m, n in self.shapes])
+        h = C.c_void_p()
+        st = self.lib.dash_model_create(dash.h, arr, len(self.shapes), B, p, p_vec, C.byref(h))
+        if st != OK:
+            raise DashError(st, "dash_model_create: " + self.lib.dash_status_string(st).decode())
+        self.h = h
+        self.plan = _describe_model(self.lib, h)
+        self.arena = torch.zeros(max(self.plan["info"]["arena_bytes"], 256), dtype=torch.uint8, device=dash.device)
+        self._check(self.lib.dash_model_set_arena(h, C.c_void_p(self.arena.data_ptr()), self.arena.numel()))
+
+    def _check(self, st: int):
+        if st != OK:
+            raise DashError(st, self.lib.dash_model_last_error(self.h).decode() or self.lib.dash_status_string(st).decode())
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.dash_model_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def stack(self, i: int):
+        """(S, X) of factor stack i as torch views [count, size, size] into the arena."""
+        import torch
+        size, p, cnt = self.plan["stacks"][i]
+        S, X = C.c_void_p(), C.c_void_p()
+        self._check(self.lib.dash_model_get_stack(self.h, i, None, None, None, C.byref(S), C.byref(X)))
+        base = self.arena.data_ptr()
+        n = cnt * size * size
+        f = self.arena.view(torch.float32)
+        return (f[(S.value - base) // 4:(S.value - base) // 4 + n].view(cnt, size, size),
+                f[(X.value - base) // 4:(X.value - base) // 4 + n].view(cnt, size, size))
+
+    def step(self, grads, updates, beta: float, eps: float, alpha: Optional[float] = None, method="newton_db",
+             iters: int = 10, scaling="frobenius", precision="fp32", refresh: bool = True,
+             cheb_coeffs: Optional[Sequence[float]] = None, cheb_a: float = 0.0, cheb_b: float = 1.0,
+             nonfinite_out=None, workspace_max_bytes: Optional[int] = None):
+        import torch
+        if len(grads) != len(self.shapes) or len(updates) != len(self.shapes):
+            raise DashError(ERR_INVALID_ARG, "one gradient and one update tensor per layer")
+        for t, (m, n) in zip(list(grads) + list(updates), self.shapes * 2):
+            self.dash._dense(t, "layer tensor", (m, n) if n else (m,))
+        a = _ModelStepArgs()
+        gp = (C.c_void_p * len(grads))(*[t.data_ptr() for t in grads])
+        up = (C.c_void_p * len(updates))(*[t.data_ptr() for t in updates])
+        a.grads, a.updates = gp, up
+        a.beta, a.alpha, a.eps = beta, (1.0 - beta) if alpha is None else alpha, eps
+        a.method, a.iters = _enum(_METHODS, method), iters
+        a.scaling, a.precision, a.refresh = _enum(_SCALINGS, scaling), _enum(_PRECISIONS, precision), int(refresh)
+        keep = None
+        if cheb_coeffs is not None:
+            keep = (C.c_double * len(cheb_coeffs))(*[float(v) for v in cheb_coeffs])
+            a.cheb_coeffs = C.cast(keep, C.POINTER(C.c_double))
+        a.cheb_a, a.cheb_b = cheb_a, cheb_b
+        a.nonfinite_out = self.dash._vec(nonfinite_out, "nonfinite_out", self.plan["info"]["n_factor_blocks"],
+                                         torch.int32).value
+        need = int(self.lib.dash_model_workspace_bytes(self.h, a.method, a.precision))
+        if workspace_max_bytes is not None:
+            need = min(need, int(workspace_max_bytes))
+        if self.dash._ws is None or self.dash._ws.numel() < need:
+            self.dash.set_workspace_bytes(need)
+        self._check(self.lib.dash_model_step(self.h, C.byref(a)))
+        return updates

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdash.so")
-SOURCES = ["dash.hip", "gemm.hip", "gemm_half.hip", "elementwise.hip", "power_iteration.hip"]
+SOURCES = ["dash.hip", "gemm.hip", "gemm_half.hip", "elementwise.hip", "power_iteration.hip", "model.hip"]
 
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",

@@ -56,6 +56,29 @@ def test_step_args_layout_matches_header():
     assert fields == [f[0] for f in _StepArgs._fields_]
 
 
+def _struct_fields(text, typedef_name):
+    end = text.index("} " + typedef_name + ";")
+    body = text[text.rindex("typedef struct {", 0, end):end]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.replace("typedef struct {", "").strip()
+        if not decl:
+            continue
+        names = decl.split(",")
+        fields.append(names[0].split()[-1].lstrip("*"))
+        fields += [n.strip().lstrip("*") for n in names[1:]]
+    return fields
+
+
+def test_model_structs_match_header():
+    from paper_2602_02016_amd.binding import _LayerShape, _ModelInfo, _ModelStepArgs
+    text = open(HEADER).read()
+    assert _struct_fields(text, "dash_layer_shape") == [f[0] for f in _LayerShape._fields_]
+    assert _struct_fields(text, "dash_model_info") == [f[0] for f in _ModelInfo._fields_]
+    assert _struct_fields(text, "dash_model_step_args") == [f[0] for f in _ModelStepArgs._fields_]
+
+
 @pytest.mark.parametrize("p,d,a,b,n", [(2, 8, 0.01, 1.0, 1000), (4, 16, 1e-3, 1.001, 10000), (4, 60, 1e-6, 1.000001, 10000)])
 def test_host_chebyshev_fit_matches_oracle(lib, p, d, a, b, n):
     from paper_2602_02016_amd import chebyshev_fit

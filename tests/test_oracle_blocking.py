@@ -98,3 +98,42 @@ def test_vector_step_closed_form():
     Lm, Rm = shampoo.accumulate_factors(g[:, :, None], L0, np.zeros((g.shape[0], 1, 1)), 0.75)
     assert np.allclose(Lm, L1) and np.allclose(Rm[:, 0, 0], 0.25 * (g * g).sum(axis=1))
     assert np.allclose(blocking.precondition_vector(L1, g)[:, :, None], np.matmul(L1, g[:, :, None]))
+
+
+def test_cached_roots_schedule():
+    """refresh = True reproduces layer_step; refresh = False keeps the old roots but still moves the factors."""
+    rng = np.random.default_rng(21)
+    m, n, B = 6, 7, 4
+    G1, G2 = rng.standard_normal((m, n)), rng.standard_normal((m, n))
+    U1, f1 = blocking.layer_step(G1, None, B, 0.9, 1e-3)
+    U1c, f1c, r1c = blocking.layer_step_cached(G1, None, None, B, 0.9, 1e-3)
+    assert np.array_equal(U1, U1c) and all(np.array_equal(f1[k][0], f1c[k][0]) for k in f1)
+    U2s, f2s, r2s = blocking.layer_step_cached(G2, f1c, r1c, B, 0.9, 1e-3, refresh=False)
+    _, f2 = blocking.layer_step(G2, f1, B, 0.9, 1e-3)
+    assert all(np.array_equal(f2[k][1], f2s[k][1]) for k in f2)            # factors moved
+    assert all(r2s[k][0] is r1c[k][0] for k in r1c)                        # roots did not
+    XL, XR = r1c[(4, 4)]
+    assert np.allclose(U2s[4:, 4:], XL @ G2[4:, 4:] @ XR)
+    # a 1-D parameter is the E x 1 layer with the right factor (a positive scalar) dropped
+    g = rng.standard_normal(10)
+    u, fv, rv = blocking.vector_param_step_cached(g, None, None, 4, 0.9, 1e-3, p=2)
+    un, Ln = blocking.norm_layers_step(g[None, :8], np.zeros((2, 4, 4)), 4, 0.9, 1e-3)
+    assert np.allclose(u[:8], un[0]) and np.allclose(fv[1], Ln[1]) and fv[2].shape == (2, 2)
+
+
+def test_model_plan_matches_paper_example_and_counts():
+    """The library's host-side plan (no GPU needed): the paper's embedding example gives S_full of 126
+    blocks of 1024 and S_rest of 2 blocks of 256; sharing stacks across layers only adds counts."""
+    from paper_2602_02016_amd import model_plan
+    g = _golden()
+    plan = model_plan([(g["V"], g["E"])], g["B"])
+    assert plan["buckets"] == [(1024, 1024, 62), (256, 1024, 2)]
+    assert plan["stacks"] == [(g["S_full"][1], 4, g["S_full"][0]), (g["S_rest"][1], 4, g["S_rest"][0])]
+    # embedding + classification head (transposed) + two square layers + two normalisation layers
+    plan = model_plan([(32000, 2048), (2048, 32000), (2048, 2048), (2048, 8192), (2048,), (2048,)], 1024)
+    sh = [blocking.stack_shapes(m, n, 1024) for m, n in [(32000, 2048), (2048, 32000), (2048, 2048), (2048, 8192)]]
+    assert dict((s, c) for s, p, c in plan["stacks"] if p == 4) == {1024: sum(x["S_full"][0] for x in sh), 256: 4}
+    assert [(s, p, c) for s, p, c in plan["stacks"] if p == 2] == [(1024, 2, 4)]
+    assert plan["info"]["n_gradient_blocks"] == sum(x["G_full"][0] for x in sh) + 2 + 2 + 4
+    with pytest.raises(Exception):
+        model_plan([(1000, 2048)], 1024)            # 1000 mod 1024 is not a multiple of 64
