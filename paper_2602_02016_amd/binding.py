@@ -86,6 +86,7 @@ def load_library(path: str = LIB_PATH):
     vp, i32, i64, f32, f64 = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_double
     lib.dash_create.argtypes = [C.POINTER(vp), i32, vp]
     lib.dash_destroy.argtypes = [vp]
+    lib.dash_set_stream.argtypes = [vp, vp]
     lib.dash_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
     lib.dash_workspace_bytes.restype = C.c_size_t
     lib.dash_set_workspace.argtypes = [vp, vp, C.c_size_t]
@@ -125,7 +126,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_precondition.argtypes = [vp, vp, vp, vp, vp, i64, i32]
     lib.dash_graft_update.argtypes = [vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, vp]
     lib.dash_step.argtypes = [vp, C.POINTER(_StepArgs)]
-    for name in ("dash_create", "dash_destroy", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
+    for name in ("dash_create", "dash_destroy", "dash_set_stream", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
                  "dash_set_symmetric", "dash_set_power_iteration", "dash_accumulate_factors_rect",
                  "dash_block_layer", "dash_unblock_layer", "dash_model_create", "dash_model_destroy",
                  "dash_model_get_info", "dash_model_get_bucket", "dash_model_get_stack", "dash_model_set_arena",
@@ -184,6 +185,11 @@ class Dash:
         if getattr(self, "h", None):
             self.lib.dash_destroy(self.h)
             self.h = None
+
+    def set_stream(self, stream):
+        """Later calls enqueue on this torch stream (kept alive by this object)."""
+        self.stream = stream
+        self._check(self.lib.dash_set_stream(self.h, C.c_void_p(stream.cuda_stream)))
 
     def __del__(self):
         try:

@@ -589,6 +589,12 @@ dash_status dash_create(dash_ctx** out, int device, void* hip_stream) {
     return DASH_OK;
 }
 
+dash_status dash_set_stream(dash_ctx* c, void* hip_stream) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    c->stream = (hipStream_t)hip_stream;
+    return DASH_OK;
+}
+
 dash_status dash_destroy(dash_ctx* c) {
     if (!c) return DASH_ERR_INVALID_ARG;
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
