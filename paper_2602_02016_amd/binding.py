@@ -82,6 +82,12 @@ def load_library(path: str = LIB_PATH):
         return _lib
     if not os.path.exists(path):
         raise DashError(ERR_HIP, f"{path} not found: build it first (python -m paper_2602_02016_amd.build)")
+    # torch ships its own HIP runtime; if libdash.so were loaded first it would pull in the system one and
+    # the process would end up with two (dash_create then fails with a HIP error).  Load torch's first.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     vp, i32, i64, f32, f64 = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_double
     lib.dash_create.argtypes = [C.POINTER(vp), i32, vp]

@@ -112,7 +112,7 @@ __device__ __forceinline__ v4f read_frag(const float* __restrict__ s, int r0, in
 
 // TILE x TILE output tile per workgroup; each of the 4 waves owns (TILE/2) x (TILE/2),
 // i.e. MT x MT MFMA tiles of 32 x 32 with MT = TILE/64.
-template <int TILE, bool TA, bool TB>
+template <int TILE, bool TA, bool TB, bool RECT = false>
 #ifndef DASH_MIN_WG
 #define DASH_MIN_WG 2
 #endif
@@ -134,7 +134,8 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
 
     // op(A) is Md x Kd, op(B) is Kd x Nd, C is Md x Nd (all equal to g.B unless a rectangular launch
     // sets g.M, g.N, g.K: ragged gradient blocks, paper Section 4.1 "rest" blocks)
-    const int Md = g.M ? g.M : g.B, Nd = g.N ? g.N : g.B, Kd = g.K ? g.K : g.B;
+    // (a separate instantiation: the square kernel keeps one dimension in registers)
+    const int Md = RECT && g.M ? g.M : g.B, Nd = RECT && g.N ? g.N : Md, Kd = RECT && g.K ? g.K : Md;
     const int tiles = Md / TILE, tiles_n = Nd / TILE;
     const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles_n;
     const int64_t blk = lid / ((int64_t)g.nprob * T);
@@ -267,6 +268,13 @@ static hipError_t launch_tile(const GemmLaunch& g, hipStream_t stream) {
     // both products of a launch must use the same transpose flags (one kernel instance)
     const int ta = g.prob[0].transA, tb = g.prob[0].transB;
     dim3 grid((unsigned)W), block(NTHREADS);
+    if (g.M || g.N || g.K) {
+        if (!ta && !tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, false, true>), grid, block, 0, stream, g);
+        else if (!ta && tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, true, true>), grid, block, 0, stream, g);
+        else if (ta && !tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, true, false, true>), grid, block, 0, stream, g);
+        else hipLaunchKernelGGL((gemm_f32_kernel<TILE, true, true, true>), grid, block, 0, stream, g);
+        return hipGetLastError();
+    }
     if (!ta && !tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, false>), grid, block, 0, stream, g);
     else if (!ta && tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, true>), grid, block, 0, stream, g);
     else if (ta && !tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, true, false>), grid, block, 0, stream, g);
