@@ -29,7 +29,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 # HBM bytes the matmul kernel moves per block product on this workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size
 # (profiles/gemm_f32_cfg2_hbm_traffic.txt); the algorithmic figure is 12*B^2 = 12.58e6.
-MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 16.07e6
+MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 15.98e6
 
 
 def log(*a):
@@ -165,7 +165,7 @@ def main():
     # above the diagonal only), never the full-product count
     achieved_tflops = st["variant_flops"][0] / (mm_ms * 1e-3) / 1e12 if mm_ms > 0 else 0.0
     tile_fraction = st["variant_flops"][0] / (flop_per_product * st["variant_block_products"][0])
-    roofline = dict(bound="mfma", kernel="dash::gemm_f32_kernel<128, false, false>",
+    roofline = dict(bound="mfma", kernel="dash::gemm_f32_kernel<128, false, false, false>",
                     achieved=achieved_tflops, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
                     frac=achieved_tflops / PEAK_FP32_MFMA_TFLOPS,
                     computed_tile_fraction=tile_fraction,
