@@ -29,7 +29,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 # HBM bytes the matmul kernel moves per block product on this workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size
 # (profiles/gemm_f32_cfg2_hbm_traffic.txt); the algorithmic figure is 12*B^2 = 12.58e6.
-MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 15.98e6
+MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 15.42e6
 
 
 def log(*a):
@@ -61,6 +61,61 @@ def cpu_baseline(sample_blocks: int, B: int, beta: float, eps: float, p: int, re
                        f"blocks, precondition) on {sample_blocks} of the 16 gradient blocks, B={B}")
 
 
+def sweep(dash):
+    """Throughput of the inverse root alone on the shapes of the other workload configurations
+    (cfg1: 16 x 128; cfg4: 256 x 256, 64 x 512, 4 x 2048; cfg5: 1024 x 1024), every method and
+    precision.  Timing does not depend on the values, so the stacks are well-conditioned random SPD
+    blocks; accuracy on the configurations' own spectra is the business of tests/test_gpu_configs.py.
+    Returns a list of records; `mfma_frac` prices the executed flops against the peak of the operand type."""
+    import torch
+    from paper_2602_02016_amd import chebyshev_fit
+    rows = []
+    shapes = [("cfg1", 16, 128), ("cfg4", 256, 256), ("cfg4", 64, 512), ("cfg4", 4, 2048), ("cfg5", 1024, 1024)]
+    for cfg, N, B in shapes:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(N + B)
+        A = torch.empty(N, B, B, device="cuda")
+        chunk = max(1, min(N, (1 << 28) // (B * B)))
+        for i in range(0, N, chunk):                       # A = G G^T / B + 0.1 I, built in chunks
+            Gm = torch.randn(min(chunk, N - i), B, B, device="cuda", generator=gen)
+            A[i:i + chunk] = Gm @ Gm.transpose(1, 2) / B
+        A += 0.1 * torch.eye(B, device="cuda")
+        X = torch.empty_like(A)
+        cases = []
+        for pp in (2, 4):
+            for k in (5, 10, 20):
+                cases.append(("newton_db", pp, k, "fp32"))
+            for d in (8, 16, 32):
+                cases.append(("chebyshev", pp, d, "fp32"))
+            cases.append(("coupled_newton", pp, 10, "fp32"))
+        if cfg == "cfg5":
+            cases += [("newton_db", 4, 10, "bf16"), ("newton_db", 4, 10, "fp16"), ("newton_db", 4, 10, "bf16x3"),
+                      ("coupled_newton", 4, 10, "fp16"), ("chebyshev", 4, 16, "fp16")]
+        for method, pp, it, prec in cases:
+            kw = dict(method=method, p=pp, iters=it, eps=1e-6, precision=prec)
+            if method == "chebyshev":
+                kw.update(cheb_coeffs=chebyshev_fit(pp, it, 0.05, 1.0), cheb_a=0.05, cheb_b=1.0)
+            dash.inverse_root(A, X, **kw)                  # warm-up (also sizes the workspace)
+            torch.cuda.synchronize()
+            reps = 3 if N * B * B >= (1 << 28) else 10
+            dash.reset_stats()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                dash.inverse_root(A, X, **kw)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / reps
+            fl = dash.get_stats()["matmul_flops"] / reps
+            peak = PEAK_FP32_MFMA_TFLOPS if prec == "fp32" else 2500.0
+            rows.append(dict(cfg=cfg, N=N, B=B, method=method, p=pp, iters=it, precision=prec, ms=ms,
+                             blocks_per_s=N / (ms * 1e-3), executed_tflops=fl / (ms * 1e-3) / 1e12,
+                             mfma_frac=fl / (ms * 1e-3) / 1e12 / peak))
+            log(f"{cfg} N={N:5d} B={B:5d} {method:14s} p={pp} it={it:2d} {prec:6s}: {ms:9.3f} ms "
+                f"{rows[-1]['blocks_per_s']:10.0f} blocks/s {rows[-1]['executed_tflops']:7.1f} TFLOP/s "
+                f"({100 * rows[-1]['mfma_frac']:.1f}%)")
+        del A, X
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +131,9 @@ def main():
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc: one device copy of known size, then three launches of the "
                          "matmul kernel on the workload's 32-block stack; prints nothing else")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline step: inverse-root throughput on the shapes of the other "
+                         "configurations, all methods and precisions (table on stderr, one JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over blocks; see DESIGN.md); "
@@ -92,6 +150,11 @@ def main():
     dev = torch.device("cuda", 0)
     dash = Dash(0)
     dash.set_symmetric(not args.full_products)
+
+    if args.sweep:
+        print(json.dumps({"sweep": sweep(dash), "unit": "blocks/s", "n_gpus": 1, "data": "synthetic",
+                          "symmetric_products": not args.full_products}))
+        return
 
     if args.pmc_probe:
         gen = torch.Generator(device=dev)

@@ -211,9 +211,13 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
         __syncthreads();
     }
 
-    // ---- epilogue: C = mult * (alpha*acc + beta*D + gamma*I) ----
-    // 32x32 accumulator layout: register r of lane l holds
-    //   row = 8*(r/4) + 4*(l/32) + r%4, col = l%32 of the MFMA tile.
+    // ---- epilogue: C = mult * (alpha*acc + beta*D + gamma*I), staged through LDS ----
+    // The MFMA leaves a lane with one column and scattered rows (register r of lane l holds row
+    // 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32 x 32 tile): storing from there is 4 bytes per lane.
+    // Instead every wavefront passes its accumulators, a strip of 32 rows x TILE/2 columns at a time,
+    // through a private region of the (now free) operand buffers and comes back with row-contiguous
+    // quads: D is read and C, C2 are written 16 bytes per lane.  Measured on 32 blocks of 1024: the
+    // direct epilogue cost 8 % of the launch without D and 15 % with it.
     const float mult = P.mult ? P.mult[blk] : 1.f;
     const float alpha = P.alpha * mult, beta = P.beta * mult, gamma = P.gamma * mult;
     const float* __restrict__ Db = P.D ? P.D + boff : nullptr;
@@ -221,41 +225,69 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     // optional second output C2 = a2 * C + g2 * I (Coupled-Newton: M' and C' = (1+1/p) I - M'/p at once)
     float* __restrict__ C2b = P.C2 ? P.C2 + boff : nullptr;
     const float a2 = P.a2, g2 = P.g2;
-    // symmetric mode: an off-diagonal tile (ti < tj) is also written transposed to (tj, ti).
-    // A lane holds four consecutive rows of one column, i.e. four consecutive elements of a
-    // row of the transposed tile: one 16-byte store each.
+    // symmetric mode: an off-diagonal tile (ti < tj) is also written transposed to (tj, ti)
     const bool mirror = g.sym && ti != tj;
+    constexpr int WT = TILE / 2;                  // columns of a wavefront's strip
+    constexpr int SP = WT + 4;                    // strip pitch in floats
+    constexpr int QPR = WT / 4;                   // quads per strip row
+    constexpr int RPI = 64 / QPR;                 // strip rows one pass of the wavefront covers
+    static_assert(4 * 32 * SP <= 2 * 2 * SLAB, "strips must fit the operand buffers");
+    float* strip = lds + wave * 32 * SP;
     bool bad = false;
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+    for (int i = 0; i < MT; ++i) {
+        // phase A: alpha * acc into the strip
 #pragma unroll
-        for (int j = 0; j < MT; ++j) {
-            const int col = col0 + wn + 32 * j + (lane & 31);
+        for (int j = 0; j < MT; ++j)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int rbase = row0 + wm + 32 * i + 8 * q + 4 * (lane >> 5);
-                v4f out, out2;
+            for (int r = 0; r < 16; ++r)
+                strip[(8 * (r / 4) + 4 * (lane >> 5) + (r % 4)) * SP + 32 * j + (lane & 31)] = alpha * acc[i][j][r];
+        __syncthreads();
+        // phase B: row-contiguous quads
+        const int rbase = row0 + wm + 32 * i, cbase = col0 + wn;
+#pragma unroll 2
+        for (int t = 0; t < 32 / RPI; ++t) {
+            const int rl = lane / QPR + RPI * t, c = (lane % QPR) * 4;
+            v4f v = *reinterpret_cast<const v4f*>(strip + rl * SP + c);
+            const int row = rbase + rl, col = cbase + c;
+            const size_t off = (size_t)row * Nd + col;
+            if (Db) {
+                const v4f d = *reinterpret_cast<const v4f*>(Db + off);
+#pragma unroll
+                for (int m = 0; m < 4; ++m) v[m] += beta * d[m];
+            }
+            v4f v2;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                if (row == col + m) v[m] += gamma;
+                bad |= !(fabsf(v[m]) <= 3.0e38f);
+                v2[m] = a2 * v[m] + (row == col + m ? g2 : 0.f);
+            }
+            *reinterpret_cast<v4f*>(Cb + off) = v;
+            if (C2b) *reinterpret_cast<v4f*>(C2b + off) = v2;
+            if (mirror) *reinterpret_cast<v4f*>(strip + rl * SP + c) = v;      // final values for phase C
+        }
+        __syncthreads();
+        // phase C (mirrored tiles only): back in the MFMA layout a lane holds four consecutive rows of
+        // one column = four consecutive elements of a row of the transposed tile: one 16-byte store
+        if (mirror) {
+#pragma unroll 2
+            for (int jq = 0; jq < MT * 4; ++jq) {
+                const int j = jq >> 2, q = jq & 3;
+                const int rl = 8 * q + 4 * (lane >> 5), cl = 32 * j + (lane & 31);
+                v4f v, v2;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
-                    const int row = rbase + m;
-                    const size_t off = (size_t)row * Nd + col;
-                    float v = alpha * acc[i][j][4 * q + m];
-                    if (Db) v += beta * Db[off];
-                    if (row == col) v += gamma;
-                    bad |= !(fabsf(v) <= 3.0e38f);
-                    Cb[off] = v;
-                    out[m] = v;
-                    if (C2b) {
-                        out2[m] = a2 * v + (row == col ? g2 : 0.f);
-                        C2b[off] = out2[m];
-                    }
+                    v[m] = strip[(rl + m) * SP + cl];
+                    v2[m] = a2 * v[m];                      // never on the diagonal
                 }
-                if (mirror) {
-                    *reinterpret_cast<v4f*>(Cb + (size_t)col * Nd + rbase) = out;
-                    if (C2b) *reinterpret_cast<v4f*>(C2b + (size_t)col * Nd + rbase) = out2;
-                }
+                const size_t moff = (size_t)(cbase + cl) * Nd + rbase + rl;
+                *reinterpret_cast<v4f*>(Cb + moff) = v;
+                if (C2b) *reinterpret_cast<v4f*>(C2b + moff) = v2;
             }
+            __syncthreads();
         }
+    }
     if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;
 }
 
