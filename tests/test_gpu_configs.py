@@ -124,7 +124,7 @@ def test_config3_full_stack(dash):
     dt = time.time() - t1
     flop = (2 * N * 2 * (3 * c["ndb_iters"] - 3) + 4 * N) * 2.0 * B ** 3
     print(f"cfg3: step over 3072 factor blocks {dt * 1e3:.0f} ms = {2 * N / dt:.0f} blocks/s, "
-          f"{flop / dt / 1e12:.1f} TFLOP/s executed", flush=True)
+          f"{flop / dt / 1e12:.1f} TFLOP/s full-product equivalent (symmetric mode computes fewer tiles)", flush=True)
     ref = oshampoo.step(Gs, L64, R64, beta=c["beta"], eps=c["eps"], p=c["p"])
     print(f"cfg3: oracle step on blocks {sample} done ({time.time() - t0:.1f} s)", flush=True)
     idx = torch.tensor(sample, device="cuda")
