@@ -79,13 +79,24 @@ namespace {
 constexpr int HBK = DASH_HBK;         // K slab (16-bit elements): 32 or 64
 constexpr int HKC_PITCH = HBK + 8;    // elements per row in the KC layout (8 of padding)
 constexpr int HKQ = HBK / 8;          // 16-byte vectors per row of a KC slab
-constexpr int HNT = 256;
+// workgroup shape per tile edge: WC x WC wavefronts, each computing a WT x WT part of the tile
+//   TILE  64: 2 x 2 wavefronts of 32 x 32   (256 threads)
+//   TILE 128: 2 x 2 wavefronts of 64 x 64   (256 threads, two workgroups per CU)
+//   TILE 256: 4 x 4 wavefronts of 64 x 64  (1024 threads, one workgroup per CU: the same four wavefronts
+//             per SIMD as two 128 tiles, but every operand panel fetched from L2 serves twice the flops)
+template <int TILE>
+struct HCfg {
+    static constexpr int WT = TILE == 64 ? 32 : 64;
+    static constexpr int WC = TILE / WT;
+    static constexpr int NT = 64 * WC * WC;
+    static constexpr int OCC = TILE == 256 ? 1 : 2;        // workgroups per CU the kernel is built for
+};
 constexpr int HNUM_XCD = 8;
 
 // 16-byte vectors a thread carries per operand slab
 template <int TILE>
 struct HRegs {
-    static constexpr int NV = TILE * HKQ / HNT;
+    static constexpr int NV = TILE * HKQ / HCfg<TILE>::NT;
 };
 
 template <int TILE>
@@ -100,10 +111,10 @@ struct HLds {
 // k-groups = 256 threads.
 template <int TILE>
 struct HK8 {
-    static constexpr int LINES = TILE / 32;        // 8, 4, 2 for TILE 256, 128, 64 (= NV)
+    static constexpr int LINES = HRegs<TILE>::NV;  // 2, 4, 2 for TILE 256, 128, 64
     static constexpr int GPL = TILE / 8;           // 8-row groups per k-line
     static constexpr int SUBS = 8 / LINES;         // line groups per group of 8 k
-    static_assert(GPL * SUBS * HKQ == HNT, "K8 decomposition must cover the workgroup");
+    static_assert(GPL * SUBS * HKQ == HCfg<TILE>::NT, "K8 decomposition must cover the workgroup");
 };
 
 // A slab is TILE*HBK 16-bit elements = TILE*HKQ 16-byte vectors; a thread carries TILE*HKQ/256 of them.
@@ -115,7 +126,7 @@ __device__ __forceinline__ void hload_slab(const u16* __restrict__ base, int ld,
     if (KC) {           // element (row, k) at base[row*ld + k]: HKQ vectors per row
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int f = t + HNT * u;
+            const int f = t + HCfg<TILE>::NT * u;
             const int row = f / HKQ, kq = f % HKQ;
             r[u] = *reinterpret_cast<const v4u*>(base + (size_t)(row0 + row) * ld + k0 + 8 * kq);
         }
@@ -139,7 +150,7 @@ __device__ __forceinline__ void hstore_slab(char* __restrict__ s, const v4u (&r)
     if (KC) {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int f = t + HNT * u;
+            const int f = t + HCfg<TILE>::NT * u;
             const int row = f / HKQ, kq = f % HKQ;
             *reinterpret_cast<v4u*>(s + (row * HKC_PITCH + 8 * kq) * 2) = r[u];
         }
@@ -180,8 +191,8 @@ __device__ __forceinline__ v4u hread_frag(const char* __restrict__ s, int r0, in
 }
 
 template <typename H, int TILE, bool TA, bool TB>
-__global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
-    constexpr int MT = TILE / 64;
+__global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_kernel(GemmLaunch g) {
+    constexpr int MT = HCfg<TILE>::WT / 32;
     constexpr bool A_KC = !TA;
     constexpr bool B_KC = TB;
     constexpr int NV = HRegs<TILE>::NV;
@@ -227,7 +238,7 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
     const u16* __restrict__ Blo = P.B2 ? static_cast<const u16*>(P.B2) + boff : Bhi;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
+    const int wm = (wave / HCfg<TILE>::WC) * HCfg<TILE>::WT, wn = (wave % HCfg<TILE>::WC) * HCfg<TILE>::WT;
 
     v16f acc[MT][MT];
 #pragma unroll
@@ -306,11 +317,11 @@ __global__ __launch_bounds__(HNT, 2) void gemm_half_kernel(GemmLaunch g) {
     const float a2 = P.a2, g2 = P.g2;
     // symmetric mode: an off-diagonal tile is also written transposed
     const bool mirror = g.sym && ti != tj;
-    constexpr int WT = TILE / 2;                  // columns of a wavefront's strip
+    constexpr int WT = HCfg<TILE>::WT;            // columns of a wavefront's strip
     constexpr int SP = WT + 4;                    // strip pitch in floats
     constexpr int QPR = WT / 4;                   // quads per strip row
     constexpr int RPI = 64 / QPR;                 // strip rows one pass of the wavefront covers
-    static_assert(4 * 32 * SP * 4 <= 4 * SLAB, "strips must fit the operand buffers");
+    static_assert((HCfg<TILE>::NT / 64) * 32 * SP * 4 <= 4 * SLAB, "strips must fit the operand buffers");
     float* strip = reinterpret_cast<float*>(lds) + wave * 32 * SP;
     bool bad = false;
     static_for<MT>([&](auto I) {
@@ -388,7 +399,7 @@ hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
     if (W <= 0) return hipSuccess;
     if (W > 0x7fffffffLL) return hipErrorInvalidValue;
     const int ta = g.prob[0].transA, tb = g.prob[0].transB;
-    dim3 grid((unsigned)W), block(HNT);
+    dim3 grid((unsigned)W), block(HCfg<TILE>::NT);
     if (!ta && !tb) hipLaunchKernelGGL((gemm_half_kernel<H, TILE, false, false>), grid, block, 0, stream, g);
     else if (!ta && tb) hipLaunchKernelGGL((gemm_half_kernel<H, TILE, false, true>), grid, block, 0, stream, g);
     else if (ta && !tb) hipLaunchKernelGGL((gemm_half_kernel<H, TILE, true, false>), grid, block, 0, stream, g);
@@ -398,14 +409,25 @@ hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
 
 }  // namespace
 
-// A 256 x 256 tile (wavefront tile 128 x 128, one workgroup per CU) was built and measured: 500-560 TFLOP/s
-// against 580-610 for the 128 tile with two workgroups per CU, so it is not instantiated.
-int gemm_half_tile_edge(const GemmLaunch& g) { return gemm_tile_edge(g); }
+// tile edge of a 16-bit launch: 256 when the block edge allows it and the launch still gives every CU a
+// workgroup, else as the fp32 kernel.  (A 256 tile of four wavefronts with 128 x 128 each, accumulators in
+// AGPRs, was also built: one wavefront per SIMD cannot hide its own latencies, 500-560 TFLOP/s.)
+int gemm_half_tile_edge(const GemmLaunch& g) {
+#ifndef DASH_NO_TILE256
+    const int64_t t = g.B / 256;
+    if (g.B % 256 == 0 && g.nblocks * g.nprob * (g.sym ? t * (t + 1) / 2 : t * t) >= 256) return 256;
+#endif
+    return gemm_tile_edge(g);
+}
 
 hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream) {
-    const bool big = gemm_half_tile_edge(g) == 128;
-    if (g.half == HALF_BF16) return big ? hlaunch_tile<Bf16, 128>(g, stream) : hlaunch_tile<Bf16, 64>(g, stream);
-    if (g.half == HALF_FP16) return big ? hlaunch_tile<Fp16, 128>(g, stream) : hlaunch_tile<Fp16, 64>(g, stream);
+    const int edge = gemm_half_tile_edge(g);
+    if (g.half == HALF_BF16)
+        return edge == 256 ? hlaunch_tile<Bf16, 256>(g, stream)
+                           : edge == 128 ? hlaunch_tile<Bf16, 128>(g, stream) : hlaunch_tile<Bf16, 64>(g, stream);
+    if (g.half == HALF_FP16)
+        return edge == 256 ? hlaunch_tile<Fp16, 256>(g, stream)
+                           : edge == 128 ? hlaunch_tile<Fp16, 128>(g, stream) : hlaunch_tile<Fp16, 64>(g, stream);
     return hipErrorInvalidValue;
 }
 
