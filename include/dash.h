@@ -245,6 +245,14 @@ dash_status dash_precondition(dash_ctx* ctx, const float* Linv, const float* G,
 dash_status dash_graft_update(dash_ctx* ctx, const float* G, const float* U, float* Acc,
                               float* theta, int64_t N, int B, float beta_g, float eps_g,
                               float lr, float* s_out);
+/* The same grafting on blocks of any shape, given as `elems` contiguous floats per block (a multiple of 4;
+ * of 32 from 4096 on, of 128 from 65536 on): Acc is updated, s_i computed, and U_scaled_i <- s_i U_i written
+ * (U_scaled may equal U, or be NULL).  Used for ragged blocks and vectors (Section 4.1). */
+dash_status dash_graft_scale(dash_ctx* ctx, const float* G, const float* U, float* Acc, int64_t N,
+                             int64_t elems, float beta_g, float eps_g, float* U_scaled, float* s_out);
+/* theta <- theta - lr * update over n floats (Algorithm 1, parameter update); n a multiple of 4,
+ * both pointers dev, 16-byte aligned. */
+dash_status dash_apply_update(dash_ctx* ctx, float* theta, const float* update, int64_t n, float lr);
 
 /* ---- one optimizer step (Algorithm 1 on a stack) ----------------------------------- */
 
@@ -293,7 +301,8 @@ typedef struct dash_model dash_model;
 typedef struct {
     int32_t n_layers, n_buckets, n_stacks, B;
     int64_t n_gradient_blocks, n_factor_blocks;
-    int64_t arena_bytes;        /* device memory the model needs: factors, roots, staging of G and U */
+    int64_t arena_bytes;        /* device memory the model needs: factors, roots, staging of G and U,
+                                   and the grafting accumulators */
 } dash_model_info;
 
 /* Host-side planning only; the model keeps ctx (which must outlive it).  p, p_vec in {2, 4}. */
@@ -324,6 +333,10 @@ typedef struct {
     const double* cheb_coeffs;  /* as in dash_inverse_root */
     double cheb_a, cheb_b;
     int32_t* nonfinite_out;     /* dev [n_factor_blocks] in stack order, or NULL */
+    int32_t graft;              /* 1: block-wise Adam grafting (Section 2.3): updates become s_b U_b */
+    float beta_g, eps_g;
+    float* const* thetas;       /* host array [n_layers] of device pointers or NULL: theta_l -= lr * update_l */
+    float lr;
 } dash_model_step_args;
 
 dash_status dash_model_step(dash_model* model, const dash_model_step_args* args);

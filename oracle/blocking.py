@@ -155,6 +155,29 @@ def vector_param_step_cached(grad, factors, roots, B: int, beta: float, eps: flo
     return u, new_f, new_r
 
 
+def graft_layer(G, U, Acc, B: int, beta_g: float, eps_g: float):
+    """Block-wise Adam grafting (Section 2.3) of one layer (2-D, or 1-D cut into pieces of B): the
+    second-moment accumulator is elementwise over the layer, Acc <- beta_g Acc + (1-beta_g) G*G,
+    P = G / (eps_g + sqrt(Acc)), and every block b of the grid gets s_b = ||P_b||_F / ||U_b||_F and
+    U_b <- s_b U_b.  Returns (U_grafted, Acc_new)."""
+    G = np.asarray(G, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    Acc = beta_g * np.asarray(Acc, dtype=np.float64) + (1.0 - beta_g) * G * G
+    P = G / (eps_g + np.sqrt(Acc))
+    out = np.zeros_like(U)
+    if G.ndim == 1:
+        for a in range(0, G.shape[0], B):
+            sl = slice(a, min(a + B, G.shape[0]))
+            out[sl] = U[sl] * (np.linalg.norm(P[sl]) / np.linalg.norm(U[sl]))
+        return out, Acc
+    m, n = G.shape
+    for r0 in range(0, m, B):
+        for c0 in range(0, n, B):
+            sl = (slice(r0, min(r0 + B, m)), slice(c0, min(c0 + B, n)))
+            out[sl] = U[sl] * (np.linalg.norm(P[sl]) / np.linalg.norm(U[sl]))
+    return out, Acc
+
+
 # ---- normalisation layers (Section 4.1): vectors as B x 1 blocks, left factor only, p = 2 ----
 def accumulate_vector(g, L, beta: float, alpha: float | None = None):
     """L_i <- beta L_i + alpha g_i g_i^T for g of shape (N, B)."""

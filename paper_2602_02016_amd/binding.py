@@ -69,7 +69,9 @@ class _ModelStepArgs(C.Structure):
                 ("method", C.c_int32), ("iters", C.c_int32), ("scaling", C.c_int32), ("precision", C.c_int32),
                 ("refresh", C.c_int32),
                 ("cheb_coeffs", C.POINTER(C.c_double)), ("cheb_a", C.c_double), ("cheb_b", C.c_double),
-                ("nonfinite_out", C.c_void_p)]
+                ("nonfinite_out", C.c_void_p),
+                ("graft", C.c_int32), ("beta_g", C.c_float), ("eps_g", C.c_float),
+                ("thetas", C.POINTER(C.c_void_p)), ("lr", C.c_float)]
 
 
 _lib = None
@@ -132,9 +134,11 @@ def load_library(path: str = LIB_PATH):
     lib.dash_precondition.argtypes = [vp, vp, vp, vp, vp, i64, i32]
     lib.dash_graft_update.argtypes = [vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, vp]
     lib.dash_step.argtypes = [vp, C.POINTER(_StepArgs)]
+    lib.dash_graft_scale.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, vp, vp]
+    lib.dash_apply_update.argtypes = [vp, vp, vp, i64, f32]
     for name in ("dash_create", "dash_destroy", "dash_set_stream", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
                  "dash_set_symmetric", "dash_set_power_iteration", "dash_accumulate_factors_rect",
-                 "dash_block_layer", "dash_unblock_layer", "dash_model_create", "dash_model_destroy",
+                 "dash_block_layer", "dash_unblock_layer", "dash_graft_scale", "dash_apply_update", "dash_model_create", "dash_model_destroy",
                  "dash_model_get_info", "dash_model_get_bucket", "dash_model_get_stack", "dash_model_set_arena",
                  "dash_model_step",
                  "dash_precondition_rect", "dash_accumulate_vector", "dash_precondition_vector",
@@ -417,6 +421,29 @@ class Dash:
             self._stack(theta, "theta", n, b) if theta is not None else C.c_void_p(None), n, b, beta_g, eps_g, lr,
             self._vec(s_out, "s_out", n, torch.float32)))
 
+    def graft_scale(self, G, U, Acc, U_scaled=None, beta_g: float = 0.999, eps_g: float = 1e-8, s_out=None):
+        """Grafting on a stack of blocks of any shape [N, ...]: Acc updated, U_scaled = s_b U_b (default: in place)."""
+        torch = self._torch
+        n = G.shape[0]
+        elems = G[0].numel() if n else 4
+        if U_scaled is None:
+            U_scaled = U
+        for t, name in ((G, "G"), (U, "U"), (Acc, "Acc"), (U_scaled, "U_scaled")):
+            self._dense(t, name, tuple(G.shape))
+        if n > 0 and (self._ws is None or self._ws.numel() < 512 * n):
+            self.set_workspace_bytes(512 * n)
+        self._check(self.lib.dash_graft_scale(self.h, C.c_void_p(G.data_ptr()), C.c_void_p(U.data_ptr()),
+                                              C.c_void_p(Acc.data_ptr()), n, elems, beta_g, eps_g,
+                                              C.c_void_p(U_scaled.data_ptr()), self._vec(s_out, "s_out", n, torch.float32)))
+        return U_scaled
+
+    def apply_update(self, theta, update, lr: float):
+        self._dense(update, "update", tuple(theta.shape))
+        self._dense(theta, "theta", tuple(theta.shape))
+        self._check(self.lib.dash_apply_update(self.h, C.c_void_p(theta.data_ptr()), C.c_void_p(update.data_ptr()),
+                                               theta.numel(), lr))
+        return theta
+
     def step(self, G, S, X, U, beta: float, eps: float, alpha: Optional[float] = None, method="newton_db", p: int = 4,
              iters: int = 10, scaling="frobenius", precision="fp32", refresh: bool = True,
              cheb_coeffs: Optional[Sequence[float]] = None, cheb_a: float = 0.0, cheb_b: float = 1.0,
@@ -532,7 +559,8 @@ class DashModel:
     def step(self, grads, updates, beta: float, eps: float, alpha: Optional[float] = None, method="newton_db",
              iters: int = 10, scaling="frobenius", precision="fp32", refresh: bool = True,
              cheb_coeffs: Optional[Sequence[float]] = None, cheb_a: float = 0.0, cheb_b: float = 1.0,
-             nonfinite_out=None, workspace_max_bytes: Optional[int] = None):
+             nonfinite_out=None, workspace_max_bytes: Optional[int] = None, graft: bool = False,
+             beta_g: float = 0.999, eps_g: float = 1e-8, thetas=None, lr: float = 0.0):
         import torch
         if len(grads) != len(self.shapes) or len(updates) != len(self.shapes):
             raise DashError(ERR_INVALID_ARG, "one gradient and one update tensor per layer")
@@ -552,6 +580,15 @@ class DashModel:
         a.cheb_a, a.cheb_b = cheb_a, cheb_b
         a.nonfinite_out = self.dash._vec(nonfinite_out, "nonfinite_out", self.plan["info"]["n_factor_blocks"],
                                          torch.int32).value
+        a.graft, a.beta_g, a.eps_g, a.lr = int(graft), beta_g, eps_g, lr
+        tp = None
+        if thetas is not None:
+            if len(thetas) != len(self.shapes):
+                raise DashError(ERR_INVALID_ARG, "one parameter tensor per layer")
+            for t, (m, n) in zip(thetas, self.shapes):
+                self.dash._dense(t, "theta", (m, n) if n else (m,))
+            tp = (C.c_void_p * len(thetas))(*[t.data_ptr() for t in thetas])
+            a.thetas = tp
         need = int(self.lib.dash_model_workspace_bytes(self.h, a.method, a.precision))
         if workspace_max_bytes is not None:
             need = min(need, int(workspace_max_bytes))

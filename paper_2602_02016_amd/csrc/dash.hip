@@ -1017,9 +1017,44 @@ dash_status dash_graft_update(dash_ctx* c, const float* G, const float* U, float
     for (int64_t b0 = 0; b0 < N; b0 += chunk) {
         const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
         const size_t o = (size_t)b0 * mat;
-        HIP_TRY(c, launch_graft_partials(G + o, U + o, Acc + o, nb, B, beta_g, eps_g, partial, c->stream));
-        HIP_TRY(c, launch_graft_apply(U + o, theta ? theta + o : nullptr, partial, nb, B, lr, s_out ? s_out + b0 : nullptr, c->stream));
+        HIP_TRY(c, launch_graft_partials(G + o, U + o, Acc + o, nb, (int64_t)mat, beta_g, eps_g, partial, c->stream));
+        HIP_TRY(c, launch_graft_apply(U + o, theta ? theta + o : nullptr, partial, nb, (int64_t)mat, lr,
+                                      s_out ? s_out + b0 : nullptr, nullptr, c->stream));
     }
+    return DASH_OK;
+}
+
+dash_status dash_graft_scale(dash_ctx* c, const float* G, const float* U, float* Acc, int64_t N, int64_t elems,
+                             float beta_g, float eps_g, float* U_scaled, float* s_out) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || elems <= 0 || elems % 4 || elems % (4 * graft_slabs(elems)))
+        return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and the block size a multiple of 4 (of 32 from 4096, of 128 from 65536 on)");
+    if (N == 0) return DASH_OK;
+    if (!G || !U || !Acc) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    HIP_TRY(c, hipSetDevice(c->device));
+    const size_t per = SCALARS_PER_BLOCK;
+    if (!c->ws || c->ws_bytes < per) return fail(c, DASH_ERR_WORKSPACE, "workspace needed (%zu bytes per block)", per);
+    int64_t chunk = (int64_t)(c->ws_bytes / per);
+    if (chunk > N) chunk = N;
+    float* partial = (float*)c->ws;
+    for (int64_t b0 = 0; b0 < N; b0 += chunk) {
+        const int64_t nb = N - b0 < chunk ? N - b0 : chunk;
+        const size_t o = (size_t)b0 * elems;
+        HIP_TRY(c, launch_graft_partials(G + o, U + o, Acc + o, nb, elems, beta_g, eps_g, partial, c->stream));
+        HIP_TRY(c, launch_graft_apply(U + o, nullptr, partial, nb, elems, 0.f, s_out ? s_out + b0 : nullptr,
+                                      U_scaled ? U_scaled + o : nullptr, c->stream));
+    }
+    return DASH_OK;
+}
+
+dash_status dash_apply_update(dash_ctx* c, float* theta, const float* update, int64_t n, float lr) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (n < 0 || n % 4) return fail(c, DASH_ERR_INVALID_ARG, "element count must be a non-negative multiple of 4");
+    if (n == 0) return DASH_OK;
+    if (!theta || !update) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    if (((uintptr_t)theta | (uintptr_t)update) % 16) return fail(c, DASH_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, launch_axpy(theta, update, n, lr, c->stream));
     return DASH_OK;
 }
 

@@ -151,13 +151,13 @@ __global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
 
 // grid = (P, nblocks)
 __global__ __launch_bounds__(NT) void graft_partials_kernel(const float* __restrict__ G, const float* __restrict__ U,
-                                                           float* __restrict__ Acc, int B, int P, float beta_g,
+                                                           float* __restrict__ Acc, int64_t elems, int P, float beta_g,
                                                            float eps_g, float* __restrict__ partial) {
     __shared__ float sh[NT / 64];
     const int q = blockIdx.x;
     const int64_t b = blockIdx.y;
-    const size_t per = (size_t)B * B / P;             // contiguous floats per slab
-    const size_t base = (size_t)b * B * B + (size_t)q * per;
+    const size_t per = (size_t)elems / P;             // contiguous floats per slab
+    const size_t base = (size_t)b * elems + (size_t)q * per;
     float sp = 0.f, su = 0.f;
     for (size_t f = threadIdx.x; f < per / 4; f += NT) {
         const size_t off = base + 4 * f;
@@ -182,9 +182,10 @@ __global__ __launch_bounds__(NT) void graft_partials_kernel(const float* __restr
 }
 
 // grid = (P, nblocks)
-__global__ __launch_bounds__(NT) void graft_apply_kernel(const float* __restrict__ U, float* __restrict__ theta,
-                                                        const float* __restrict__ partial, int B, int P, float lr,
-                                                        float* __restrict__ s_out) {
+// theta -= lr * s_b * U (theta may be null); scaled = s_b * U (scaled may be null, may equal U)
+__global__ __launch_bounds__(NT) void graft_apply_kernel(const float* U, float* __restrict__ theta,
+                                                        const float* __restrict__ partial, int64_t elems, int P, float lr,
+                                                        float* __restrict__ s_out, float* scaled) {
     const int q = blockIdx.x;
     const int64_t b = blockIdx.y;
     float tp = 0.f, tu = 0.f;
@@ -194,17 +195,36 @@ __global__ __launch_bounds__(NT) void graft_apply_kernel(const float* __restrict
     }
     const float s = sqrtf(tp) / sqrtf(tu);
     if (s_out && q == 0 && threadIdx.x == 0) s_out[b] = s;
-    if (!theta) return;
+    if (!theta && !scaled) return;
     const float k = lr * s;
-    const size_t per = (size_t)B * B / P;
-    const size_t base = (size_t)b * B * B + (size_t)q * per;
+    const size_t per = (size_t)elems / P;
+    const size_t base = (size_t)b * elems + (size_t)q * per;
     for (size_t f = threadIdx.x; f < per / 4; f += NT) {
         const size_t off = base + 4 * f;
         const v4f u = *reinterpret_cast<const v4f*>(U + off);
-        v4f t = *reinterpret_cast<v4f*>(theta + off);
+        if (theta) {
+            v4f t = *reinterpret_cast<v4f*>(theta + off);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] -= k * u[i];
-        *reinterpret_cast<v4f*>(theta + off) = t;
+            for (int i = 0; i < 4; ++i) t[i] -= k * u[i];
+            *reinterpret_cast<v4f*>(theta + off) = t;
+        }
+        if (scaled) {
+            v4f w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w[i] = s * u[i];
+            *reinterpret_cast<v4f*>(scaled + off) = w;
+        }
+    }
+}
+
+// y -= a * x over n floats (n a multiple of 4, 16-byte aligned)
+__global__ __launch_bounds__(NT) void axpy_kernel(float* __restrict__ y, const float* __restrict__ x, int64_t n4, float a) {
+    for (int64_t f = blockIdx.x * (int64_t)NT + threadIdx.x; f < n4; f += (int64_t)gridDim.x * NT) {
+        const v4f u = reinterpret_cast<const v4f*>(x)[f];
+        v4f t = reinterpret_cast<v4f*>(y)[f];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] -= a * u[i];
+        reinterpret_cast<v4f*>(y)[f] = t;
     }
 }
 
@@ -363,28 +383,42 @@ hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_graft_partials(const float* G, const float* U, float* Acc, int64_t nblocks, int B,
+// slabs a block of `elems` floats is cut into for the grafting reductions (each a multiple of 4 floats)
+int graft_slabs(int64_t elems) { return elems >= 65536 ? 32 : elems >= 4096 ? 8 : 1; }
+
+hipError_t launch_graft_partials(const float* G, const float* U, float* Acc, int64_t nblocks, int64_t elems,
                                  float beta_g, float eps_g, float* partial, hipStream_t stream) {
-    const int P = norm_slabs(B);
+    const int P = graft_slabs(elems);
+    if (elems % (4 * P)) return hipErrorInvalidValue;
     for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
         const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
-        const size_t o = (size_t)b0 * B * B;
+        const size_t o = (size_t)b0 * elems;
         hipLaunchKernelGGL(graft_partials_kernel, dim3(P, (unsigned)nb), dim3(NT), 0, stream, G + o, U + o,
-                           Acc + o, B, P, beta_g, eps_g, partial + b0 * P * 2);
+                           Acc + o, elems, P, beta_g, eps_g, partial + b0 * P * 2);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_graft_apply(const float* U, float* theta, const float* partial, int64_t nblocks, int B,
-                              float lr, float* s_out, hipStream_t stream) {
-    const int P = norm_slabs(B);
+hipError_t launch_graft_apply(const float* U, float* theta, const float* partial, int64_t nblocks, int64_t elems,
+                              float lr, float* s_out, float* scaled, hipStream_t stream) {
+    const int P = graft_slabs(elems);
+    if (elems % (4 * P)) return hipErrorInvalidValue;
     for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
         const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
-        const size_t o = (size_t)b0 * B * B;
+        const size_t o = (size_t)b0 * elems;
         hipLaunchKernelGGL(graft_apply_kernel, dim3(P, (unsigned)nb), dim3(NT), 0, stream, U + o,
-                           theta ? theta + o : nullptr, partial + b0 * P * 2, B, P, lr,
-                           s_out ? s_out + b0 : nullptr);
+                           theta ? theta + o : nullptr, partial + b0 * P * 2, elems, P, lr,
+                           s_out ? s_out + b0 : nullptr, scaled ? scaled + o : nullptr);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_axpy(float* y, const float* x, int64_t n, float a, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    if (n % 4) return hipErrorInvalidValue;
+    const int64_t n4 = n / 4;
+    const int64_t want = (n4 + NT - 1) / NT;
+    hipLaunchKernelGGL(axpy_kernel, dim3((unsigned)(want < 8192 ? want : 8192)), dim3(NT), 0, stream, y, x, n4, a);
     return hipGetLastError();
 }
 

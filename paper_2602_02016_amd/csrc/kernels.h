@@ -96,12 +96,17 @@ hipError_t launch_block_copy(float* W, float* stack, int64_t ld, int64_t r0, int
 
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
 
-// grafting: Acc <- beta_g Acc + (1-beta_g) G.G ; partial sums of P^2 and U^2 per slab
-hipError_t launch_graft_partials(const float* G, const float* U, float* Acc, int64_t nblocks, int B,
-                                 float beta_g, float eps_g, float* partial /* [n][P][2] */,
+// grafting on blocks of `elems` contiguous floats (elems a multiple of 4 x graft_slabs(elems)):
+// Acc <- beta_g Acc + (1-beta_g) G.G ; partial sums of P^2 and U^2 per slab
+int graft_slabs(int64_t elems);
+hipError_t launch_graft_partials(const float* G, const float* U, float* Acc, int64_t nblocks, int64_t elems,
+                                 float beta_g, float eps_g, float* partial /* [n][slabs][2] */,
                                  hipStream_t stream);
-// s_b = sqrt(sum P^2 / sum U^2); theta -= lr * s_b * U (theta may be null); s_out may be null
+// s_b = sqrt(sum P^2 / sum U^2); theta -= lr * s_b * U (theta may be null); scaled = s_b * U (may be null,
+// may equal U); s_out may be null
 hipError_t launch_graft_apply(const float* U, float* theta, const float* partial, int64_t nblocks,
-                              int B, float lr, float* s_out, hipStream_t stream);
+                              int64_t elems, float lr, float* s_out, float* scaled, hipStream_t stream);
+// y -= a * x over n floats (n a multiple of 4)
+hipError_t launch_axpy(float* y, const float* x, int64_t n, float a, hipStream_t stream);
 
 }  // namespace dash

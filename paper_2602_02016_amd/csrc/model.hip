@@ -24,6 +24,7 @@ struct Bucket {                 // all gradient blocks of one shape
     int stackL, stackR;         // factor stacks holding its L and R segments (stackR = -1 for vectors)
     int64_t offL, offR;         // first block of the segment inside the stack
     size_t g_off, u_off;        // staging areas in the arena
+    size_t acc_off;             // second-moment accumulator of the grafting (same shape as the staging)
 };
 
 struct Stack {                  // all factors of one size that take the same root
@@ -98,7 +99,7 @@ dash_status dash_model_create(dash_ctx* ctx, const dash_layer_shape* layers, int
         auto it = bucket_of.find(key);
         if (it == bucket_of.end()) {
             it = bucket_of.emplace(key, (int)m->buckets.size()).first;
-            m->buckets.push_back(Bucket{bm, bn, 0, -1, -1, 0, 0, 0, 0});
+            m->buckets.push_back(Bucket{bm, bn, 0, -1, -1, 0, 0, 0, 0, 0});
         }
         Bucket& b = m->buckets[it->second];
         Part pt{it->second, b.count};
@@ -162,6 +163,7 @@ dash_status dash_model_create(dash_ctx* ctx, const dash_layer_shape* layers, int
         const size_t bytes = align_up((size_t)b.count * b.bm * (b.bn ? b.bn : 1) * sizeof(float));
         b.g_off = off; off += bytes;
         b.u_off = off; off += bytes;
+        b.acc_off = off; off += bytes;
     }
     m->arena_bytes = off;
     *out = m;
@@ -297,6 +299,15 @@ dash_status dash_model_step(dash_model* m, const dash_model_step_args* a) {
         }
         if (lib(m, st) != DASH_OK) return st;
     }
+    // 4b. block-wise Adam grafting (Section 2.3): U_b <- s_b U_b with s_b = ||P_b||_F / ||U_b||_F
+    if (a->graft) {
+        for (const Bucket& b : m->buckets) {
+            const int64_t elems = (int64_t)b.bm * (b.bn ? b.bn : 1);
+            dash_status st = lib(m, dash_graft_scale(c, at(m, b.g_off), at(m, b.u_off), at(m, b.acc_off), b.count, elems,
+                                                     a->beta_g, a->eps_g, at(m, b.u_off), nullptr));
+            if (st != DASH_OK) return st;
+        }
+    }
     // 5. back to the layers' own layout
     for (int l = 0; l < nl; ++l) {
         const Layer& L = m->layers[l];
@@ -304,6 +315,11 @@ dash_status dash_model_step(dash_model* m, const dash_model_step_args* a) {
         dash_status st = lib(m, dash_unblock_layer(c, a->updates[l], mm, nn, B, group(L, 0, true), group(L, 1, true),
                                                    group(L, 2, true), group(L, 3, true)));
         if (st != DASH_OK) return st;
+        // Algorithm 1, parameter update
+        if (a->thetas && a->thetas[l]) {
+            st = lib(m, dash_apply_update(c, a->thetas[l], a->updates[l], L.m * (L.n ? L.n : 1), a->lr));
+            if (st != DASH_OK) return st;
+        }
     }
     return DASH_OK;
 }

@@ -76,6 +76,38 @@ def test_model_step_matches_per_layer_oracle(dash, ws_cap):
     model.close()
 
 
+def test_model_step_with_grafting_and_parameter_update(dash):
+    """Grafted updates s_b U_b per block of every bucket shape and theta <- theta - lr * update (Section 2.3,
+    Algorithm 1) against the oracle working on slices of each layer."""
+    import torch
+    from paper_2602_02016_amd import DashModel
+    model = DashModel(dash, LAYERS, B, p=4, p_vec=2)
+    beta, eps, k, beta_g, eps_g, lr = 0.9, 1e-5, 30, float(np.float32(0.999)), 1e-8, 0.01
+    state = [None] * len(LAYERS)
+    accs = [np.zeros(s) for s in LAYERS]
+    rng = np.random.default_rng(99)
+    theta_np = [rng.standard_normal(s).astype(np.float32) for s in LAYERS]
+    thetas = [torch.from_numpy(t).cuda() for t in theta_np]
+    theta_ref = [t.astype(np.float64) for t in theta_np]
+    for step in range(3):
+        g_np = _grads(step)
+        grads = [torch.from_numpy(g).cuda() for g in g_np]
+        ups = [torch.zeros_like(g) for g in grads]
+        model.step(grads, ups, beta=beta, eps=eps, method="newton_db", iters=k, graft=True, beta_g=beta_g, eps_g=eps_g,
+                   thetas=thetas, lr=lr)
+        ref, state = _oracle_step(g_np, state, beta, eps, True)
+        for i, (g, u) in enumerate(zip(g_np, ref)):
+            ug, accs[i] = oblocking.graft_layer(g, u, accs[i], B, beta_g, eps_g)
+            theta_ref[i] = theta_ref[i] - float(np.float32(lr)) * ug
+            got = ups[i].cpu().numpy()
+            e = np.linalg.norm(got - ug) / np.linalg.norm(ug)
+            assert e < 2e-4, (step, i, e)
+            et = np.abs(thetas[i].cpu().numpy() - theta_ref[i]).max()
+            assert et < 1e-5, (step, i, et)
+    print("grafted model step ok", flush=True)
+    model.close()
+
+
 def test_model_errors(dash):
     import torch
     from paper_2602_02016_amd import DashModel, DashError

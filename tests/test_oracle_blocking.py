@@ -137,3 +137,23 @@ def test_model_plan_matches_paper_example_and_counts():
     assert plan["info"]["n_gradient_blocks"] == sum(x["G_full"][0] for x in sh) + 2 + 2 + 4
     with pytest.raises(Exception):
         model_plan([(1000, 2048)], 1024)            # 1000 mod 1024 is not a multiple of 64
+
+
+def test_graft_layer_against_stack_grafting_and_norm_property():
+    """graft_layer (slices of the layer) equals oracle.shampoo.adam_graft on the blocked stacks, and the
+    grafted block has exactly the Frobenius norm of the Adam direction of that block."""
+    rng = np.random.default_rng(33)
+    m, n, B = 8, 12, 4
+    G, U, Acc = rng.standard_normal((m, n)), rng.standard_normal((m, n)), rng.random((m, n))
+    Ug, Acc1 = blocking.graft_layer(G, U, Acc, B, 0.9, 1e-8)
+    gs, us, accs = (blocking.block_layer(x, B)["full"] for x in (G, U, Acc))
+    acc_ref, s_ref = shampoo.adam_graft(gs, us, accs, 0.9, 1e-8)
+    assert np.allclose(blocking.block_layer(Acc1, B)["full"], acc_ref)
+    assert np.allclose(blocking.block_layer(Ug, B)["full"], s_ref[:, None, None] * us)
+    P = G / (1e-8 + np.sqrt(Acc1))
+    assert np.isclose(np.linalg.norm(Ug[4:8, 8:12]), np.linalg.norm(P[4:8, 8:12]))
+    # 1-D: pieces of B entries and a shorter last one
+    g, u, a = rng.standard_normal(10), rng.standard_normal(10), rng.random(10)
+    ug, a1 = blocking.graft_layer(g, u, a, 4, 0.9, 1e-8)
+    p1 = g / (1e-8 + np.sqrt(a1))
+    assert np.isclose(np.linalg.norm(ug[8:]), np.linalg.norm(p1[8:])) and np.allclose(ug[:4] / u[:4], ug[0] / u[0])
