@@ -61,17 +61,29 @@ __global__ __launch_bounds__(PNT) void pi_sweep_kernel(const float* __restrict__
     v16f acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    for (int k0 = 0; k0 < B; k0 += 32) {
-        v4f a[4];
-        float v[16];
+    // Two register sets: the loads of the next 32-wide k chunk are in flight while the 16 MFMAs of the
+    // current one run (a wavefront is alone on its SIMD when the stack is short, so nothing else hides
+    // the latency of its loads).  B is a multiple of 64: the number of chunks is even.
+    v4f a0[4], a1[4];
+    float v0[16], v1[16];
+    auto load = [&](int k0, v4f (&a)[4], float (&v)[16]) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) a[u] = *reinterpret_cast<const v4f*>(arow + k0 + 4 * u);
 #pragma unroll
         for (int s = 0; s < 16; ++s) v[s] = vcol[(size_t)(k0 + s) * POOL];
-        // MFMA step s contracts k = k0 + 16*h + s on both operands
+    };
+    // MFMA step s contracts k = k0 + 16*h + s on both operands
+    auto mul = [&](const v4f (&a)[4], const float (&v)[16]) {
 #pragma unroll
         for (int s = 0; s < 16; ++s)
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s >> 2][s & 3], v[s], acc, 0, 0, 0);
+    };
+    load(0, a0, v0);
+    for (int k0 = 0; k0 < B; k0 += 64) {
+        load(k0 + 32, a1, v1);
+        mul(a0, v0);
+        if (k0 + 64 < B) load(k0 + 64, a0, v0);
+        mul(a1, v1);
     }
     float* __restrict__ Wb = W + (size_t)b * B * POOL;
 #pragma unroll
