@@ -116,6 +116,57 @@ def sweep(dash):
     return rows
 
 
+def hbm_kernels(dash):
+    """Achieved HBM bandwidth of the memory-bound kernels of the path on a long stack (256 blocks of
+    1024 x 1024 fp32 = 1 GiB, plus a ragged 4096 x 4000 layer for block()).  bytes = algorithmic bytes of
+    the call (every operand read once, every result written once); peak 8 TB/s."""
+    import torch
+    N, B = 256, 1024
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    A = torch.randn(N, B, B, device="cuda", generator=gen)
+    A = (A + A.transpose(1, 2)) * 0.01 + torch.eye(B, device="cuda")
+    G = torch.randn(N, B, B, device="cuda", generator=gen) * 0.01
+    U = torch.randn(N, B, B, device="cuda", generator=gen)
+    Acc = torch.zeros(N, B, B, device="cuda")
+    X = torch.empty_like(A)
+    g = torch.randn(N, B, device="cuda", generator=gen)
+    u = torch.empty_like(g)
+    Wl = torch.randn(4096, 4000, device="cuda", generator=gen)
+    V0 = torch.randn(B, 16, device="cuda", generator=gen)
+    dash.set_power_iteration(V0, 4)
+    blk = B * B * 4
+    groups = {}
+
+    def block():
+        groups.update(dash.block_layer(Wl, 1024))
+
+    cases = [
+        ("block_norms frobenius (norm_partials + finalize)", lambda: dash.block_norms(A, scaling="frobenius"), N * blk),
+        ("block_norms power iteration, 4 sweeps of pool 16", lambda: dash.block_norms(A, scaling="pi"), 4 * N * blk),
+        ("graft_update (read G, U, Acc; write Acc)", lambda: dash.graft_update(G, U, Acc), 4 * N * blk),
+        ("graft_scale in place (read G, U, Acc; then U again; write Acc, U)", lambda: dash.graft_scale(G, U, Acc), 6 * N * blk),
+        ("accumulate_vector (read + write L)", lambda: dash.accumulate_vector(g, A, 0.95), 2 * N * blk),
+        ("precondition_vector (read L)", lambda: dash.precondition_vector(A, g, u), N * blk),
+        ("block_layer 4096 x 4000, B = 1024 (read + write)", block, 2 * Wl.numel() * 4),
+        ("apply_update (read theta, update; write theta)", lambda: dash.apply_update(U, G, 0.1), 3 * N * blk),
+    ]
+    rows = []
+    for name, fn, nbytes in cases:
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        reps = 10
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / reps
+        rows.append(dict(kernel=name, us=us, algorithmic_bytes=nbytes, tb_per_s=nbytes / us / 1e6, frac_of_hbm_peak=nbytes / us / 1e6 / 8.0))
+        log(f"{name:75s} {us:9.1f} us  {rows[-1]['tb_per_s']:5.2f} TB/s ({100 * rows[-1]['frac_of_hbm_peak']:.0f}% of 8 TB/s)")
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +185,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline step: inverse-root throughput on the shapes of the other "
                          "configurations, all methods and precisions (table on stderr, one JSON line)")
+    ap.add_argument("--hbm-kernels", action="store_true",
+                    help="instead of the headline step: achieved bandwidth of the memory-bound kernels on a "
+                         "1 GiB stack (table on stderr, one JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over blocks; see DESIGN.md); "
@@ -150,6 +204,10 @@ def main():
     dev = torch.device("cuda", 0)
     dash = Dash(0)
     dash.set_symmetric(not args.full_products)
+
+    if args.hbm_kernels:
+        print(json.dumps({"hbm_kernels": hbm_kernels(dash), "peak_tb_per_s": 8.0, "n_gpus": 1, "data": "synthetic"}))
+        return
 
     if args.sweep:
         print(json.dumps({"sweep": sweep(dash), "unit": "blocks/s", "n_gpus": 1, "data": "synthetic",
