@@ -121,3 +121,25 @@ def test_step_with_power_iteration_scaling(dash):
     ref = oshampoo.step(G, L64, R64, beta=beta, eps=eps, p=4)
     assert rel_frobenius_error(X.cpu().numpy(), np.concatenate([ref["X_L"], ref["X_R"]])).max() < 1e-4
     assert rel_frobenius_error(U.cpu().numpy(), ref["U"]).max() < 1e-4
+
+
+def test_power_iteration_scaling_saves_iterations_on_wishart_factors(dash):
+    """The paper's Section 3.4 argument on the benchmark's kind of factor (EMA of G G^T, eigenvalues near
+    ||L||_F / sqrt(B)): scaled by 2 lambda_PI, Newton-DB with five updates per call is converged to the fp32
+    floor, scaled by the Frobenius norm it is still far off and needs eight."""
+    import torch
+    N, B, eps = 4, 512, 1e-6
+    S = torch.zeros(2 * N, B, B, device="cuda")
+    for t in range(20):
+        G = torch.from_numpy(workloads.gradient_stack(N, B, 3000 + t)).cuda()
+        dash.accumulate_factors(G, S[:N], S[N:], 0.95)
+    X_evd = inverse_root_evd(S.cpu().numpy().astype(np.float64), 4, eps)
+    V0 = torch.from_numpy(workloads.start_vectors(B, 16, 77)).cuda()
+    dash.set_power_iteration(V0, 4)
+    err = {}
+    for scaling in ("frobenius", "pi"):
+        for k in (5, 8):
+            X = dash.inverse_root(S, p=4, iters=k, eps=eps, scaling=scaling).cpu().numpy()
+            err[scaling, k] = rel_frobenius_error(X, X_evd).max()
+    print({f"{a} k={k}": f"{e:.1e}" for (a, k), e in err.items()}, flush=True)
+    assert err["pi", 5] < 1e-4 and err["frobenius", 5] > 1e-2 and err["frobenius", 8] < 1e-4
