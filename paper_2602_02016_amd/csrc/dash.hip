@@ -222,7 +222,7 @@ struct ScaleScratch {
         unscale = (float*)cv.take((size_t)nb * sizeof(float));
         piV = (float*)cv.take((size_t)nb * B * 32 * sizeof(float));
         piW = (float*)cv.take((size_t)nb * B * 32 * sizeof(float));
-        piq = (float*)cv.take((size_t)nb * 32 * sizeof(float));
+        piq = (float*)cv.take((size_t)nb * power_iteration_q_floats(B) * sizeof(float));
         return partial && s && inv_s && unscale && piV && piW && piq;
     }
 };

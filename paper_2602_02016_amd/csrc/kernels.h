@@ -77,8 +77,10 @@ hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps
 
 // Multi-Power-Iteration scaling (power_iteration.hip): s_b = 2 * lambda_PI(A_b + eps I) from
 // `sweeps` passes over the block with a pool of `pool` (<= 32) start vectors V0 ([B][pool]
-// row-major, shared by all blocks).  V, W: scratch of n * B * 32 floats each (kept pool-major, [n][32][B]); q: scratch [n][32].
+// row-major, shared by all blocks).  V, W: scratch of n * B * 32 floats each (kept pool-major, [n][32][B]); q: scratch of
+// n * power_iteration_q_floats(B) floats.
 size_t power_iteration_bytes_per_block(int B);
+size_t power_iteration_q_floats(int B);
 hipError_t launch_power_iteration(const float* A, int64_t nblocks, int B, float eps, const float* V0, int pool,
                                   int sweeps, int p, float* V, float* W, float* q, float* s, float* inv_s,
                                   float* unscale, hipStream_t stream);

@@ -8,14 +8,18 @@
 // ([32][B] per block: a column of V is contiguous) so that every operand of the sweep is
 // read 16 bytes per lane.  Kernels:
 //   pi_init    V_b = start vectors with unit columns (pool padded with zero columns to 32)
-//   pi_sweep   W_b = A_b V_b + eps V_b with v_mfma_f32_32x32x2_f32.  A workgroup owns 64 rows
-//              of A; its four wavefronts split K (32-wide chunks, round robin), each streams its
-//              part of the 64 rows straight from global memory into the MFMA A operand (every
-//              element of A is used once, so LDS staging would buy nothing) and reuses each
-//              chunk of V for both 32-row tiles; the four partial results meet in LDS.  The loads
-//              of a wavefront's next chunk are in flight while the MFMAs of the current one run.
-//   pi_reduce  per block: q_j = v_j . w_j, V <- W with unit columns; after the last sweep
-//              s = 2 max_j q_j, 1/s and s^(-1/p)
+//   pi_sweep   W_b = A_b V_b + eps V_b with v_mfma_f32_32x32x2_f32, computed as W^T = V^T A (the
+//              blocks are symmetric).  A workgroup owns 128 columns of A; its four wavefronts split
+//              K (16-wide half-chunks, round robin), each streams its rows of the 128 columns
+//              straight from global memory into the MFMA column operand -- 512 contiguous bytes
+//              per half-wavefront and load, every element of A used once, no LDS staging -- and
+//              reuses its chunk of V for the four column groups; the four partial results meet
+//              in LDS.  The loads of a wavefront's next half-chunk are in flight while the MFMAs
+//              of the current one run.
+//              A sweep also leaves, per workgroup, the partial sums of |w_j|^2 and v_j . w_j of its
+//              columns; the next sweep scales its input columns to unit length from them on the
+//              way in, so no pass over the vectors lies between two sweeps.
+//   pi_finalize  per block, after the last sweep: q_j = v_j . w_j, s = 2 max_j q_j, 1/s and s^(-1/p)
 // Reductions are per block in a fixed order (no atomics): results do not depend on scheduling.
 #include "kernels.h"
 
@@ -28,14 +32,6 @@ namespace {
 
 constexpr int POOL = 32;     // columns of V (pool members beyond the requested count are zero)
 constexpr int PNT = 256;
-
-// sum over the 8 consecutive lanes that share a pool column
-__device__ __forceinline__ float sum8(float x) {
-    x += __shfl_xor(x, 1);
-    x += __shfl_xor(x, 2);
-    x += __shfl_xor(x, 4);
-    return x;
-}
 
 // grid = nblocks; V0: [B][m] row-major (shared by all blocks); V: [nblocks][32][B]
 __global__ __launch_bounds__(PNT) void pi_init_kernel(const float* __restrict__ V0, int m, int B,
@@ -61,112 +57,143 @@ __global__ __launch_bounds__(PNT) void pi_init_kernel(const float* __restrict__ 
     }
 }
 
-// grid = (B/64, nblocks); the four wavefronts of a workgroup split K
-__global__ __launch_bounds__(PNT) void pi_sweep_kernel(const float* __restrict__ A, const float* __restrict__ V,
-                                                      float* __restrict__ W, int B, float eps) {
-    __shared__ float part[4][2][16][64];          // [wavefront][row tile][accumulator register][lane]
+// per-block scalars: q[32], then per workgroup of the sweep (128 columns each) the partial sums
+// sum_n w[j][n]^2 and sum_n v[j][n] w[j][n] of its columns: [groups][2][32]
+__host__ __device__ inline int pi_groups(int B) { return (B + 127) / 128; }
+__host__ __device__ inline int pi_q_floats(int B) { return POOL + 2 * POOL * pi_groups(B); }
+
+// grid = (B/128, nblocks); the four wavefronts of a workgroup split K.
+// The blocks are symmetric, so W^T = V^T A: the pool is the MFMA's row operand and A its column operand,
+// whose lane <-> column mapping lets a half-wavefront read 512 contiguous bytes of one row of A per load:
+// lane (n', h) loads A[k][c0 + 4n' .. 4n'+3] for k = 16c + 8h + s (s = 0..7 within half-chunk c of 16 k) and
+// feeds element m of the quad to the MFMA of column group m (columns c0 + 4n' + m, n' = 0..31); lane (j, h)
+// supplies V[k][j] for the same k.  (For an input that is not exactly symmetric this is the power
+// iteration of A^T, which has the same spectrum.)
+// V holds the un-normalised product of the previous sweep; its columns are scaled to unit length on the
+// way in, with the norms the previous sweep left as per-workgroup partial sums in qprev -- so a sweep is
+// one launch, and it leaves its own partial sums (norms and Rayleigh quotients of its output) in qnext.
+__global__ __launch_bounds__(PNT, 2) void pi_sweep_kernel(const float* __restrict__ A, const float* __restrict__ V,
+                                                         float* __restrict__ W, int B, float eps,
+                                                         const float* __restrict__ qprev, float* __restrict__ qnext) {
+    __shared__ float part[4][4][16][64];          // [wavefront][column group][accumulator register][lane]
+    __shared__ float inv_norm[POOL];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int row0 = blockIdx.x * 64;
+    const int c0 = blockIdx.x * 128;
     const int64_t b = blockIdx.y;
     const int i = lane & 31, h = lane >> 5;
-    // lane (i, h) feeds row row0 + 32 t + i of A and pool column i of V, k = 32 c + 16 h + 0..15 of chunk c
-    const float* __restrict__ arow = A + (size_t)b * B * B + (size_t)(row0 + i) * B + 16 * h;
+    const int QF = pi_q_floats(B), NG = pi_groups(B);
+    if (threadIdx.x < POOL) {
+        const float* __restrict__ pp = qprev + b * QF + POOL;
+        float nn = 0.f;
+        for (int gidx = 0; gidx < NG; ++gidx) nn += pp[(size_t)gidx * 2 * POOL + threadIdx.x];
+        inv_norm[threadIdx.x] = nn > 0.f ? 1.f / sqrtf(nn) : 0.f;
+    }
+    __syncthreads();
+    const float my_inv = inv_norm[i];             // lane (j = i, h) feeds pool column i
+    const bool valid = c0 + 4 * i < B;            // B is a multiple of 64: the last workgroup may own only 64 columns
+    const float* __restrict__ acol = A + (size_t)b * B * B + (size_t)(8 * h) * B + c0 + 4 * i;
     const float* __restrict__ Vb = V + (size_t)b * B * POOL;
-    const float* __restrict__ vcol = Vb + (size_t)i * B + 16 * h;
-    v16f acc[2];
+    const float* __restrict__ vrow = Vb + (size_t)i * B + 8 * h;
+    v16f acc[4];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int m = 0; m < 4; ++m)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-    struct Chunk { v4f a[2][4]; v4f v[4]; };
-    auto load = [&](int c, Chunk& x) {
-        const int k0 = 32 * c;
+        for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
+    struct Half { v4f a[8]; v4f v[2]; };         // eight rows of A (a quad of columns each), eight k of V
+    auto load = [&](int c, Half& x) {
+        const int k0 = 16 * c;
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int s = 0; s < 8; ++s) {
+            if (valid) x.a[s] = *reinterpret_cast<const v4f*>(acol + (size_t)(k0 + s) * B);
+            else x.a[s] = v4f{0.f, 0.f, 0.f, 0.f};
+        }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) x.a[t][u] = *reinterpret_cast<const v4f*>(arow + (size_t)(32 * t) * B + k0 + 4 * u);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) x.v[u] = *reinterpret_cast<const v4f*>(vcol + k0 + 4 * u);
+        for (int u = 0; u < 2; ++u) x.v[u] = *reinterpret_cast<const v4f*>(vrow + k0 + 4 * u);
     };
-    // MFMA step s contracts k = 32 c + 16 h + s on both operands
-    auto mul = [&](const Chunk& x) {
+    // MFMA step s contracts k = 16 c + 8 h + s on both operands
+    auto mul = [&](const Half& x) {
 #pragma unroll
-        for (int s = 0; s < 16; ++s)
+        for (int s = 0; s < 8; ++s)
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(x.a[t][s >> 2][s & 3], x.v[s >> 2][s & 3], acc[t], 0, 0, 0);
+            for (int m = 0; m < 4; ++m)
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(x.v[s >> 2][s & 3] * my_inv, x.a[s][m], acc[m], 0, 0, 0);
     };
-    const int nchunks = B / 32;
-    Chunk c0, c1;
+    // half-chunks of 16 k, dealt round robin to the four wavefronts; the loads of a wavefront's next
+    // half-chunk are in flight while the MFMAs of the current one run
+    const int nhalf = B / 16;
+    Half x0, x1;
     int c = wave;
-    if (c < nchunks) load(c, c0);
-    while (c < nchunks) {
-        if (c + 4 < nchunks) load(c + 4, c1);
-        mul(c0);
+    if (c < nhalf) load(c, x0);
+    while (c < nhalf) {
+        if (c + 4 < nhalf) load(c + 4, x1);
+        mul(x0);
         c += 4;
-        if (c >= nchunks) break;
-        if (c + 4 < nchunks) load(c + 4, c0);
-        mul(c1);
+        if (c >= nhalf) break;
+        if (c + 4 < nhalf) load(c + 4, x0);
+        mul(x1);
         c += 4;
     }
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int m = 0; m < 4; ++m)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) part[wave][t][r][lane] = acc[t][r];
+        for (int r = 0; r < 16; ++r) part[wave][m][r][lane] = acc[m][r];
     __syncthreads();
-    // wavefront w finishes (tile, register group) pairs 2w and 2w+1: four consecutive rows of pool column i
+    // accumulator register r of lane (n', h) is pool row j = 8 (r/4) + 4 h + r%4, column c0 + 4 n' + m of
+    // group m: the four groups give a quad of consecutive columns.  Wavefront w finishes r = 4w .. 4w+3,
+    // i.e. every pool row is finished by exactly one half-wavefront, which also sums its partials.
     float* __restrict__ Wb = W + (size_t)b * B * POOL;
+    float* __restrict__ qn = qnext + b * QF + POOL + (size_t)blockIdx.x * 2 * POOL;
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int pq = 2 * wave + e, t = pq >> 2, q4 = pq & 3;
-        const int row = row0 + 32 * t + 8 * q4 + 4 * h;
-        const size_t off = (size_t)i * B + row;
-        v4f out = *reinterpret_cast<const v4f*>(Vb + off);
+    for (int e = 0; e < 4; ++e) {
+        const int r = 4 * wave + e;
+        const int j = 8 * (r >> 2) + 4 * h + (r & 3);
+        const size_t off = (size_t)j * B + c0 + 4 * i;
+        float nn = 0.f, vw = 0.f;
+        if (valid) {
+            v4f vhat = *reinterpret_cast<const v4f*>(Vb + off);
+            const float sj = inv_norm[j];
+            v4f out;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            float sum = 0.f;
+            for (int m = 0; m < 4; ++m) {
+                float sum = 0.f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) sum += part[w][t][4 * q4 + m][lane];
-            out[m] = sum + eps * out[m];
+                for (int w = 0; w < 4; ++w) sum += part[w][m][r][lane];
+                vhat[m] *= sj;
+                out[m] = sum + eps * vhat[m];
+                nn += out[m] * out[m];
+                vw += vhat[m] * out[m];
+            }
+            *reinterpret_cast<v4f*>(Wb + off) = out;
         }
-        *reinterpret_cast<v4f*>(Wb + off) = out;
+#pragma unroll
+        for (int d = 1; d < 32; d <<= 1) {
+            nn += __shfl_xor(nn, d);
+            vw += __shfl_xor(vw, d);
+        }
+        if (i == 0) {
+            qn[j] = nn;
+            qn[POOL + j] = vw;
+        }
     }
 }
 
-// grid = nblocks.  last != 0: also writes s = 2 max q, 1/s, s^(-1/p).  Eight threads per pool column.
-__global__ __launch_bounds__(PNT) void pi_reduce_kernel(float* __restrict__ V, const float* __restrict__ W, int B,
-                                                       float* __restrict__ q_out, int last, int p,
-                                                       float* __restrict__ s, float* __restrict__ inv_s,
-                                                       float* __restrict__ unscale) {
-    __shared__ float qj[POOL];
+// grid = nblocks: q_j = v_j . w_j of the last sweep (unit v), s = 2 max_j q_j, 1/s and s^(-1/p)
+__global__ __launch_bounds__(64) void pi_finalize_kernel(float* __restrict__ qbuf, int B, int p, float* __restrict__ s,
+                                                        float* __restrict__ inv_s, float* __restrict__ unscale) {
     const int64_t b = blockIdx.x;
-    const int j = threadIdx.x / 8, part = threadIdx.x % 8;
-    float* __restrict__ Vc = V + (size_t)b * B * POOL + (size_t)j * B;
-    const float* __restrict__ Wc = W + (size_t)b * B * POOL + (size_t)j * B;
-    float nn = 0.f, vw = 0.f;
-    for (int i = 4 * part; i < B; i += 32) {
-        const v4f w = *reinterpret_cast<const v4f*>(Wc + i);
-        const v4f v = *reinterpret_cast<const v4f*>(Vc + i);
+    const int QF = pi_q_floats(B), NG = pi_groups(B);
+    float* __restrict__ q = qbuf + b * QF;
+    const int j = threadIdx.x;
+    float vw = -3.0e38f;
+    if (j < POOL) {
+        vw = 0.f;
+        for (int gidx = 0; gidx < NG; ++gidx) vw += q[POOL + (size_t)gidx * 2 * POOL + POOL + j];
+        q[j] = vw;
+    }
+    float best = vw;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) { nn += w[m] * w[m]; vw += v[m] * w[m]; }
-    }
-    nn = sum8(nn);
-    vw = sum8(vw);
-    const float inv_norm = nn > 0.f ? 1.f / sqrtf(nn) : 0.f;
-    if (part == 0) {
-        qj[j] = vw;
-        q_out[b * POOL + j] = vw;
-    }
-    for (int i = 4 * part; i < B; i += 32) {
-        v4f w = *reinterpret_cast<const v4f*>(Wc + i);
-#pragma unroll
-        for (int m = 0; m < 4; ++m) w[m] *= inv_norm;
-        *reinterpret_cast<v4f*>(Vc + i) = w;
-    }
-    __syncthreads();
-    if (last && threadIdx.x == 0) {
-        float best = qj[0];
-        for (int c = 1; c < POOL; ++c) best = fmaxf(best, qj[c]);
+    for (int d = 1; d < 64; d <<= 1) best = fmaxf(best, __shfl_xor(best, d));
+    if (j == 0) {
         const float sv = 2.f * best;
         if (s) s[b] = sv;
         if (inv_s) inv_s[b] = 1.f / sv;
@@ -174,26 +201,47 @@ __global__ __launch_bounds__(PNT) void pi_reduce_kernel(float* __restrict__ V, c
     }
 }
 
+// grid = nblocks: the start vectors are unit columns: norm partial 1 in group 0, 0 elsewhere
+__global__ void pi_unit_norms_kernel(float* __restrict__ qbuf, int B) {
+    const int QF = pi_q_floats(B), NG = pi_groups(B);
+    float* __restrict__ q = qbuf + (size_t)blockIdx.x * QF + POOL;
+    for (int t = threadIdx.x; t < 2 * POOL * NG; t += blockDim.x) q[t] = t < POOL ? 1.f : 0.f;
+}
+
 }  // namespace
 
-size_t power_iteration_bytes_per_block(int B) { return 2 * (size_t)B * POOL * sizeof(float) + POOL * sizeof(float); }
+size_t power_iteration_q_floats(int B) { return 2 * (size_t)pi_q_floats(B); }       // two buffers, ping-pong
+
+size_t power_iteration_bytes_per_block(int B) {
+    return 2 * (size_t)B * POOL * sizeof(float) + power_iteration_q_floats(B) * sizeof(float);
+}
 
 hipError_t launch_power_iteration(const float* A, int64_t nblocks, int B, float eps, const float* V0, int pool,
                                   int sweeps, int p, float* V, float* W, float* q, float* s, float* inv_s,
                                   float* unscale, hipStream_t stream) {
     if (nblocks <= 0) return hipSuccess;
     if (pool < 1 || pool > POOL || sweeps < 1) return hipErrorInvalidValue;
+    const size_t QF = pi_q_floats(B);
+    float* q0 = q;                                   // [nblocks][QF]
+    float* q1 = q + (size_t)nblocks * QF;            // [nblocks][QF]
     for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
         const unsigned nb = (unsigned)(nblocks - b0 < 65535 ? nblocks - b0 : 65535);
         const size_t ov = (size_t)b0 * B * POOL;
-        hipLaunchKernelGGL(pi_init_kernel, dim3(nb), dim3(PNT), 0, stream, V0, pool, B, V + ov);
+        float* src = V + ov;
+        float* dst = W + ov;
+        float* qa = q0 + b0 * QF;
+        float* qb = q1 + b0 * QF;
+        hipLaunchKernelGGL(pi_init_kernel, dim3(nb), dim3(PNT), 0, stream, V0, pool, B, src);
+        hipLaunchKernelGGL(pi_unit_norms_kernel, dim3(nb), dim3(256), 0, stream, qa, B);
         for (int t = 1; t <= sweeps; ++t) {
-            hipLaunchKernelGGL(pi_sweep_kernel, dim3(B / 64, nb), dim3(PNT), 0, stream,
-                               A + (size_t)b0 * B * B, V + ov, W + ov, B, eps);
-            hipLaunchKernelGGL(pi_reduce_kernel, dim3(nb), dim3(PNT), 0, stream, V + ov, W + ov, B, q + b0 * POOL,
-                               t == sweeps ? 1 : 0, p, s ? s + b0 : nullptr, inv_s ? inv_s + b0 : nullptr,
-                               unscale ? unscale + b0 : nullptr);
+            hipLaunchKernelGGL(pi_sweep_kernel, dim3((B + 127) / 128, nb), dim3(PNT), 0, stream,
+                               A + (size_t)b0 * B * B, src, dst, B, eps, qa, qb);
+            float* tv = src; src = dst; dst = tv;
+            float* tq = qa; qa = qb; qb = tq;
         }
+        // qa now holds the partial sums of the last sweep
+        hipLaunchKernelGGL(pi_finalize_kernel, dim3(nb), dim3(64), 0, stream, qa, B, p, s ? s + b0 : nullptr,
+                           inv_s ? inv_s + b0 : nullptr, unscale ? unscale + b0 : nullptr);
     }
     return hipGetLastError();
 }
