@@ -125,8 +125,9 @@ dash_status dash_set_symmetric(dash_ctx* ctx, int on);
  * pool: number of start vectors, 1..32 (the paper uses 16 or 32).  sweeps >= 1: passes over
  * the block.  start_vectors: DEVICE pointer, row-major [rows][pool] fp32, rows >= the B of
  * later calls (their first B rows are used), shared by all blocks; drawn by the caller
- * (e.g. seeded N(0,1)); must stay valid while the setting is in use.  The block is read
- * through its rows as if symmetric.  Since R_A(v) <= lambda_max, s can be below lambda_max
+ * (e.g. seeded N(0,1)); must stay valid while the setting is in use.  The blocks are taken to be
+ * symmetric: the product is evaluated as (V^T A)^T, which for an input that is not exactly
+ * symmetric is the power iteration of A^T (same spectrum).  Since R_A(v) <= lambda_max, s can be below lambda_max
  * when the pool has not converged: Newton-DB still converges as long as lambda_max < 2 s
  * (its scalar map converges on (0, 3)), otherwise it diverges and the block is flagged. */
 dash_status dash_set_power_iteration(dash_ctx* ctx, int pool, int sweeps, const float* start_vectors, int rows);
