@@ -33,6 +33,8 @@
 extern "C" {
 #endif
 
+/* A context binds a device, a HIP stream, a workspace and statistics.  Calls on one context must not run
+ * concurrently (use one context per host thread); different contexts are independent. */
 typedef struct dash_ctx dash_ctx;
 
 typedef enum {
@@ -306,7 +308,8 @@ typedef struct {
                                    and the grafting accumulators */
 } dash_model_info;
 
-/* Host-side planning only; the model keeps ctx (which must outlive it).  p, p_vec in {2, 4}. */
+/* Host-side planning only; the model keeps ctx (which must outlive it).  ctx may be NULL for a model that
+ * is only described (dash_model_get_*), never stepped.  p, p_vec in {2, 4}. */
 dash_status dash_model_create(dash_ctx* ctx, const dash_layer_shape* layers, int n_layers, int B,
                               int p, int p_vec, dash_model** out);
 dash_status dash_model_destroy(dash_model* model);

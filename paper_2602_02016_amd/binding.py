@@ -485,9 +485,7 @@ def model_plan(layers, B: int, p: int = 4, p_vec: int = 2, ctx_handle=None):
     lib = load_library()
     arr = (_LayerShape * len(layers))(*[_LayerShape(int(s[0]), int(s[1]) if len(s) > 1 else 0) for s in layers])
     h = C.c_void_p()
-    # planning only stores the context pointer; a dummy non-null value is enough without a GPU
-    st = lib.dash_model_create(ctx_handle if ctx_handle is not None else C.c_void_p(1), arr, len(layers), B, p, p_vec,
-                               C.byref(h))
+    st = lib.dash_model_create(ctx_handle, arr, len(layers), B, p, p_vec, C.byref(h))     # NULL context: planning only
     if st != OK:
         raise DashError(st, "dash_model_create: " + lib.dash_status_string(st).decode())
     try:

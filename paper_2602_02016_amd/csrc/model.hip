@@ -71,7 +71,7 @@ dash_status mfail(dash_model* m, dash_status st, const char* fmt, ...) {
 
 // error of a library call: keep the context's message
 dash_status lib(dash_model* m, dash_status st) {
-    if (st != DASH_OK) snprintf(m->err, sizeof(m->err), "%s", dash_last_error(m->ctx));
+    if (st != DASH_OK && m->ctx) snprintf(m->err, sizeof(m->err), "%s", dash_last_error(m->ctx));
     return st;
 }
 
@@ -85,7 +85,7 @@ dash_status dash_model_create(dash_ctx* ctx, const dash_layer_shape* layers, int
                               dash_model** out) {
     if (!out) return DASH_ERR_INVALID_ARG;
     *out = nullptr;
-    if (!ctx || (!layers && n_layers > 0) || n_layers < 0 || B <= 0 || B % 64 || (p != 2 && p != 4) ||
+    if ((!layers && n_layers > 0) || n_layers < 0 || B <= 0 || B % 64 || (p != 2 && p != 4) ||
         (p_vec != 2 && p_vec != 4))
         return DASH_ERR_INVALID_ARG;
     dash_model* m = new (std::nothrow) dash_model();
@@ -234,6 +234,7 @@ dash_status dash_model_set_arena(dash_model* m, void* dev_ptr, size_t bytes) {
 
 dash_status dash_model_step(dash_model* m, const dash_model_step_args* a) {
     if (!m || !a) return DASH_ERR_INVALID_ARG;
+    if (!m->ctx) return mfail(m, DASH_ERR_INVALID_ARG, "the model was created without a context (planning only)");
     if (!m->arena) return mfail(m, DASH_ERR_WORKSPACE, "no arena set");
     const int nl = (int)m->layers.size();
     if (nl && (!a->grads || !a->updates)) return mfail(m, DASH_ERR_INVALID_ARG, "null pointer array");
