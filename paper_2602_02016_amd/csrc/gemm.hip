@@ -52,10 +52,12 @@ struct Lds {
 };
 
 // ---- global -> registers ------------------------------------------------------------
-// A slab holds TILE*BK floats = TILE*KQ float4; each thread carries TILE*KQ/256 of them.
+// A slab holds TILE*BK floats = TILE*KQ float4; each thread carries TILE*KQ/256 of them.  Their byte offsets
+// inside the block, without the part that moves with the slab, are fixed for the whole tile: computed once
+// (32 bits suffice: a block has at most 16384^2 * 4 bytes), so that every load is "uniform base of the slab +
+// per-thread offset" and the address arithmetic stays out of the K loop.
 template <int TILE, bool KC>
-__device__ __forceinline__ void load_slab(const float* __restrict__ base, int ld, int row0, int k0,
-                                          v4f (&r)[TILE * KQ / NTHREADS]) {
+__device__ __forceinline__ void slab_offsets(int ld, int row0, unsigned (&off)[TILE * KQ / NTHREADS]) {
     constexpr int NV = TILE * KQ / NTHREADS;
     const int t = threadIdx.x;
 #pragma unroll
@@ -63,13 +65,26 @@ __device__ __forceinline__ void load_slab(const float* __restrict__ base, int ld
         const int f = t + NTHREADS * u;
         if (KC) {   // element (row, k) at base[row*ld + k]
             const int row = f / KQ, kq = f % KQ;
-            r[u] = *reinterpret_cast<const v4f*>(base + (size_t)(row0 + row) * ld + k0 + 4 * kq);
+            off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 4u * kq) * 4u;
         } else {    // element (row, k) at base[k*ld + row]
             constexpr int QPR = TILE / 4;   // float4 per k-line
             const int k = f / QPR, rq = f % QPR;
-            r[u] = *reinterpret_cast<const v4f*>(base + (size_t)(k0 + k) * ld + row0 + 4 * rq);
+            off[u] = ((unsigned)k * (unsigned)ld + row0 + 4u * rq) * 4u;
         }
     }
+}
+
+// uniform byte offset of the slab starting at k0
+template <bool KC>
+__device__ __forceinline__ size_t slab_base(int ld, int k0) {
+    return KC ? (size_t)k0 * 4 : (size_t)k0 * ld * 4;
+}
+
+template <int TILE>
+__device__ __forceinline__ void load_slab(const char* __restrict__ slab, const unsigned (&off)[TILE * KQ / NTHREADS],
+                                          v4f (&r)[TILE * KQ / NTHREADS]) {
+#pragma unroll
+    for (int u = 0; u < TILE * KQ / NTHREADS; ++u) r[u] = *reinterpret_cast<const v4f*>(slab + off[u]);
 }
 
 // ---- registers -> LDS ----------------------------------------------------------------
@@ -173,8 +188,13 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     v4f ra[NV], rb[NV];
-    load_slab<TILE, A_KC>(Ab, lda, row0, 0, ra);
-    load_slab<TILE, B_KC>(Bb, ldb, col0, 0, rb);
+    unsigned offa[NV], offb[NV];
+    slab_offsets<TILE, A_KC>(lda, row0, offa);
+    slab_offsets<TILE, B_KC>(ldb, col0, offb);
+    const char* __restrict__ Ac = reinterpret_cast<const char*>(Ab);
+    const char* __restrict__ Bc = reinterpret_cast<const char*>(Bb);
+    load_slab<TILE>(Ac, offa, ra);
+    load_slab<TILE>(Bc, offb, rb);
     store_slab<TILE, A_KC>(lds, ra);
     store_slab<TILE, B_KC>(lds + SLAB, rb);
     __syncthreads();
@@ -185,8 +205,8 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
         const float* sb = sa + SLAB;
         const bool more = kt + 1 < KT;
         if (more) {
-            load_slab<TILE, A_KC>(Ab, lda, row0, (kt + 1) * BK, ra);
-            load_slab<TILE, B_KC>(Bb, ldb, col0, (kt + 1) * BK, rb);
+            load_slab<TILE>(Ac + slab_base<A_KC>(lda, (kt + 1) * BK), offa, ra);
+            load_slab<TILE>(Bc + slab_base<B_KC>(ldb, (kt + 1) * BK), offb, rb);
         }
 #pragma unroll
         for (int c = 0; c < BK / 8; ++c) {

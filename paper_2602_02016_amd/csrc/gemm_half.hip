@@ -117,10 +117,12 @@ struct HK8 {
     static_assert(GPL * SUBS * HKQ == HCfg<TILE>::NT, "K8 decomposition must cover the workgroup");
 };
 
-// A slab is TILE*HBK 16-bit elements = TILE*HKQ 16-byte vectors; a thread carries TILE*HKQ/256 of them.
+// A slab is TILE*HBK 16-bit elements = TILE*HKQ 16-byte vectors; a thread carries NV of them.  Their byte
+// offsets inside the block, without the part that moves with the slab, are fixed for the whole tile: they are
+// computed once (32 bits suffice: a block has at most 16384^2 * 2 bytes) and every load is "uniform base of
+// the slab + per-thread offset", which keeps the address arithmetic out of the K loop.
 template <int TILE, bool KC>
-__device__ __forceinline__ void hload_slab(const u16* __restrict__ base, int ld, int row0, int k0,
-                                           v4u (&r)[HRegs<TILE>::NV]) {
+__device__ __forceinline__ void hslab_offsets(int ld, int row0, unsigned (&off)[HRegs<TILE>::NV]) {
     constexpr int NV = HRegs<TILE>::NV;
     const int t = threadIdx.x;
     if (KC) {           // element (row, k) at base[row*ld + k]: HKQ vectors per row
@@ -128,15 +130,28 @@ __device__ __forceinline__ void hload_slab(const u16* __restrict__ base, int ld,
         for (int u = 0; u < NV; ++u) {
             const int f = t + HCfg<TILE>::NT * u;
             const int row = f / HKQ, kq = f % HKQ;
-            r[u] = *reinterpret_cast<const v4u*>(base + (size_t)(row0 + row) * ld + k0 + 8 * kq);
+            off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 8u * kq) * 2u;
         }
     } else {            // element (row, k) at base[k*ld + row]
         typedef HK8<TILE> U;
         const int rg = t % U::GPL, sub = (t / U::GPL) % U::SUBS, kg = t / (U::GPL * U::SUBS);
-        const u16* p = base + (size_t)(k0 + 8 * kg + U::LINES * sub) * ld + row0 + 8 * rg;
 #pragma unroll
-        for (int l = 0; l < U::LINES; ++l) r[l] = *reinterpret_cast<const v4u*>(p + (size_t)l * ld);
+        for (int l = 0; l < U::LINES; ++l)
+            off[l] = ((unsigned)(8 * kg + U::LINES * sub + l) * (unsigned)ld + row0 + 8u * rg) * 2u;
     }
+}
+
+// uniform byte offset of slab k0 inside the block
+template <bool KC>
+__device__ __forceinline__ size_t hslab_base(int ld, int k0) {
+    return KC ? (size_t)k0 * 2 : (size_t)k0 * ld * 2;
+}
+
+template <int TILE>
+__device__ __forceinline__ void hload_slab(const char* __restrict__ slab, const unsigned (&off)[HRegs<TILE>::NV],
+                                           v4u (&r)[HRegs<TILE>::NV]) {
+#pragma unroll
+    for (int u = 0; u < HRegs<TILE>::NV; ++u) r[u] = *reinterpret_cast<const v4u*>(slab + off[u]);
 }
 
 // K8 layout in LDS: [k/8][row'][8 k], 16 bytes per (k-group, row), row' = row ^ ((row / 8) % 8): the
@@ -251,13 +266,16 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     const int KS = B / HBK;             // slabs per segment
     const int KT = nseg * KS;           // slabs in all
     v4u ra[NV], rb[NV];
+    unsigned offa[NV], offb[NV];
+    hslab_offsets<TILE, A_KC>(B, row0, offa);
+    hslab_offsets<TILE, B_KC>(B, col0, offb);
     // slab kk belongs to segment kk / KS; the small terms are summed first
     auto load = [&](int kk) {
         const int seg = nseg == 1 ? 2 : kk / KS, k0 = (kk % KS) * HBK;
-        const u16* __restrict__ Ab = seg == 0 ? Alo : Ahi;
-        const u16* __restrict__ Bb = seg == 1 ? Blo : Bhi;
-        hload_slab<TILE, A_KC>(Ab, B, row0, k0, ra);
-        hload_slab<TILE, B_KC>(Bb, B, col0, k0, rb);
+        const char* __restrict__ Ab = reinterpret_cast<const char*>(seg == 0 ? Alo : Ahi) + hslab_base<A_KC>(B, k0);
+        const char* __restrict__ Bb = reinterpret_cast<const char*>(seg == 1 ? Blo : Bhi) + hslab_base<B_KC>(B, k0);
+        hload_slab<TILE>(Ab, offa, ra);
+        hload_slab<TILE>(Bb, offb, rb);
     };
     // multiply slab kt out of its LDS buffer
     auto compute = [&](int kt) {
