@@ -269,13 +269,25 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     unsigned offa[NV], offb[NV];
     hslab_offsets<TILE, A_KC>(B, row0, offa);
     hslab_offsets<TILE, B_KC>(B, col0, offb);
-    // slab kk belongs to segment kk / KS; the small terms are summed first
-    auto load = [&](int kk) {
-        const int seg = nseg == 1 ? 2 : kk / KS, k0 = (kk % KS) * HBK;
-        const char* __restrict__ Ab = reinterpret_cast<const char*>(seg == 0 ? Alo : Ahi) + hslab_base<A_KC>(B, k0);
-        const char* __restrict__ Bb = reinterpret_cast<const char*>(seg == 1 ? Blo : Bhi) + hslab_base<B_KC>(B, k0);
-        hload_slab<TILE>(Ab, offa, ra);
-        hload_slab<TILE>(Bb, offb, rb);
+    // The slabs are requested in order, segment after segment (the small terms are summed first:
+    // A_lo B_hi, A_hi B_lo, A_hi B_hi; a plain product is the last segment alone).  The uniform base
+    // addresses of the next slab are carried along and stepped, so the K loop holds no address set-up.
+    const size_t stepa = hslab_base<A_KC>(B, HBK), stepb = hslab_base<B_KC>(B, HBK);
+    int seg_next = nseg == 1 ? 2 : 0, ks_next = 0;
+    const char* pa = reinterpret_cast<const char*>(seg_next == 0 ? Alo : Ahi);
+    const char* pb = reinterpret_cast<const char*>(Bhi);
+    auto load_next = [&]() {
+        hload_slab<TILE>(pa, offa, ra);
+        hload_slab<TILE>(pb, offb, rb);
+        if (++ks_next < KS) {
+            pa += stepa;
+            pb += stepb;
+        } else {
+            ks_next = 0;
+            ++seg_next;
+            pa = reinterpret_cast<const char*>(Ahi);
+            pb = reinterpret_cast<const char*>(seg_next == 1 ? Blo : Bhi);
+        }
     };
     // multiply slab kt out of its LDS buffer
     auto compute = [&](int kt) {
@@ -303,13 +315,13 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
                     acc[i][j] = H::mfma(fa[cur][i], fb[cur][j], acc[i][j]);
         }
     };
-    load(0);
+    load_next();
     hstore_slab<TILE, A_KC>(lds, ra);
     hstore_slab<TILE, B_KC>(lds + SLAB, rb);
     __syncthreads();
     for (int kt = 0; kt < KT; ++kt) {
         const bool more = kt + 1 < KT;
-        if (more) load(kt + 1);          // next slab into registers while this one is multiplied
+        if (more) load_next();           // next slab into registers while this one is multiplied
         compute(kt);
         if (more) {
             char* da = lds + ((kt + 1) & 1) * 2 * SLAB;
