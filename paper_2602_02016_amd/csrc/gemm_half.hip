@@ -290,8 +290,8 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
         }
     };
     // multiply slab kt out of its LDS buffer
-    auto compute = [&](int kt) {
-        const char* sa = lds + (kt & 1) * 2 * SLAB;
+    auto compute = [&](auto BUF) {
+        const char* sa = lds + decltype(BUF)::value * 2 * SLAB;
         const char* sb = sa + SLAB;
         // operand fragments of step st+1 are requested from LDS before the MFMAs of step st issue
         v4u fa[2][MT], fb[2][MT];
@@ -319,16 +319,22 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     hstore_slab<TILE, A_KC>(lds, ra);
     hstore_slab<TILE, B_KC>(lds + SLAB, rb);
     __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
+    // one iteration per slab; the loop is unrolled by two so that the LDS buffer of a slab is a compile-time
+    // constant and every LDS address is "per-thread base + immediate"
+    auto iteration = [&](int kt, auto BUF) {
         const bool more = kt + 1 < KT;
         if (more) load_next();           // next slab into registers while this one is multiplied
-        compute(kt);
+        compute(BUF);
         if (more) {
-            char* da = lds + ((kt + 1) & 1) * 2 * SLAB;
+            char* da = lds + (1 - decltype(BUF)::value) * 2 * SLAB;
             hstore_slab<TILE, A_KC>(da, ra);
             hstore_slab<TILE, B_KC>(da + SLAB, rb);
         }
         __syncthreads();
+    };
+    for (int kt = 0; kt < KT; kt += 2) {
+        iteration(kt, std::integral_constant<int, 0>{});
+        if (kt + 1 < KT) iteration(kt + 1, std::integral_constant<int, 1>{});
     }
 
     // ---- epilogue, staged through LDS (free after the last barrier of the main loop) ----
