@@ -10,10 +10,11 @@
 //     v   = mult_b * (alpha * acc + beta * D_b + gamma * I)     (fp32)
 //     C_b = v (fp32, optional),  Ch_b = half(v) (optional),  C2h_b = half(a2 v + g2 I) (optional)
 //
-// Same decomposition as the fp32 kernel: 256 threads, 2 x 2 wavefronts, TILE x TILE per
-// workgroup, K slabs of 64 double-buffered in LDS, next slab prefetched into registers,
-// XCD-aware 1-D grid.  An MFMA operand wants per lane eight consecutive k of one row:
-//   KC  [row][k]  k contiguous in global memory: rows of 32 bf16 (pitch 40), one 16-byte
+// Same decomposition as the fp32 kernel: TILE x TILE per workgroup (2 x 2 wavefronts, or 4 x 4
+// for the 256 tile), K slabs of 64 double-buffered in LDS, next slab prefetched into registers,
+// LDS-staged epilogue, XCD-aware 1-D grid.  An MFMA operand wants per lane eight consecutive k
+// of one row:
+//   KC  [row][k]  k contiguous in global memory: rows of 64 elements (pitch 72), one 16-byte
 //       LDS read per MFMA operand;
 //   K8  [k/8][row][8]  row contiguous in global memory: a thread loads the same eight rows of
 //       2, 4 or 8 consecutive k-lines, transposes them in registers and stores, per row, its
