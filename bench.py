@@ -174,7 +174,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-blocks", type=int, default=16)
-    ap.add_argument("--cpu-repeats", type=int, default=3)
+    ap.add_argument("--cpu-repeats", type=int, default=4)
     ap.add_argument("--root-only-reps", type=int, default=-1,
                     help="extra timed calls of the inverse root alone (default steps/2; 0 = none)")
     ap.add_argument("--full-products", action="store_true",
