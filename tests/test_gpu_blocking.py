@@ -173,3 +173,29 @@ def test_ragged_layer_step_end_to_end(dash):
     e = rel_frobenius_error(U.cpu().numpy()[None], U_ref[None]).max()
     print(f"ragged layer step: U vs per-slice EVD step {e:.2e}", flush=True)
     assert e < 1e-4
+
+
+def test_invalid_arguments_of_the_new_entry_points(dash):
+    import ctypes as C
+    import torch
+    from paper_2602_02016_amd import DashError
+    z = lambda *sh: torch.zeros(*sh, device="cuda")
+    with pytest.raises(DashError):
+        dash.accumulate_vector(z(2, 100), z(2, 100, 100), 0.9)                  # B not a multiple of 64
+    with pytest.raises(DashError):
+        dash.precondition_vector(z(2, 64, 64), z(2, 128))                       # shapes do not match
+    with pytest.raises(DashError):
+        dash.graft_scale(z(2, 3, 2), z(2, 3, 2), z(2, 3, 2))                    # 6 elements per block: not a multiple of 4
+    with pytest.raises(DashError):
+        dash.apply_update(z(6), z(6), 0.1)                                      # 6 floats: not a multiple of 4
+    with pytest.raises(DashError):
+        dash.precondition_rect(z(1, 64, 64), z(1, 64, 128), z(1, 64, 64))       # Rinv must be 128 x 128
+    # null pointers reach the library and come back as status 1, not as a fault
+    vp = C.c_void_p
+    assert dash.lib.dash_accumulate_factors_rect(dash.h, vp(None), vp(None), vp(None), 1, 64, 128, 0.9, 0.1) == 1
+    assert dash.lib.dash_block_layer(dash.h, vp(None), 64, 64, 64, vp(None), vp(None), vp(None), vp(None)) == 1
+    assert dash.lib.dash_apply_update(dash.h, vp(None), vp(None), 64, 0.1) == 1
+    assert dash.lib.dash_graft_scale(dash.h, vp(None), vp(None), vp(None), 1, 64, 0.9, 1e-8, vp(None), vp(None)) == 1
+    # and an un-aligned parameter pointer is refused
+    t = z(65)
+    assert dash.lib.dash_apply_update(dash.h, vp(t.data_ptr() + 4), vp(t.data_ptr() + 4), 64, 0.1) == 1
