@@ -217,9 +217,25 @@ __global__ __launch_bounds__(NT) void graft_apply_kernel(const float* U, float* 
     }
 }
 
-// y -= a * x over n floats (n a multiple of 4, 16-byte aligned)
+// y -= a * x over n floats (n a multiple of 4, 16-byte aligned); four independent quads per thread and pass
 __global__ __launch_bounds__(NT) void axpy_kernel(float* __restrict__ y, const float* __restrict__ x, int64_t n4, float a) {
-    for (int64_t f = blockIdx.x * (int64_t)NT + threadIdx.x; f < n4; f += (int64_t)gridDim.x * NT) {
+    const int64_t stride = (int64_t)gridDim.x * NT;
+    int64_t f = blockIdx.x * (int64_t)NT + threadIdx.x;
+    for (; f + 3 * stride < n4; f += 4 * stride) {
+        v4f u[4], t[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u[q] = reinterpret_cast<const v4f*>(x)[f + q * stride];
+            t[q] = reinterpret_cast<v4f*>(y)[f + q * stride];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[q][i] -= a * u[q][i];
+            reinterpret_cast<v4f*>(y)[f + q * stride] = t[q];
+        }
+    }
+    for (; f < n4; f += stride) {
         const v4f u = reinterpret_cast<const v4f*>(x)[f];
         v4f t = reinterpret_cast<v4f*>(y)[f];
 #pragma unroll
