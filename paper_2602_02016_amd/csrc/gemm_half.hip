@@ -11,17 +11,20 @@
 //     C_b = v (fp32, optional),  Ch_b = half(v) (optional),  C2h_b = half(a2 v + g2 I) (optional)
 //
 // Same decomposition as the fp32 kernel: TILE x TILE per workgroup (2 x 2 wavefronts, or 4 x 4
-// for the 256 tile), K slabs of 64 double-buffered in LDS, next slab prefetched into registers,
-// LDS-staged epilogue, XCD-aware 1-D grid.  An MFMA operand wants per lane eight consecutive k
-// of one row:
-//   KC  [row][k]  k contiguous in global memory: rows of 64 elements (pitch 72), one 16-byte
-//       LDS read per MFMA operand;
-//   K8  [k/8][row][8]  row contiguous in global memory: a thread loads the same eight rows of
-//       2, 4 or 8 consecutive k-lines, transposes them in registers and stores, per row, its
-//       consecutive k (4, 8 or 16 bytes) into a swizzled 16-byte cell; an MFMA operand is
-//       again one 16-byte LDS read.
+// for the 256 tile), K slabs of 64 double-buffered in LDS, LDS-staged epilogue, XCD-aware 1-D grid.
+// Operand slabs go from global memory straight into LDS (global_load_lds_dwordx4: a wavefront-wide
+// load fills 1 KB of LDS in lane order, the source address of every lane is free), one slab ahead
+// of the MFMAs, so no registers and no LDS store instructions are spent on staging.  An MFMA
+// operand wants per lane eight consecutive k of one row:
+//   KC  [row][k]  k contiguous in global memory: LDS holds rows of 64 k (128 bytes, cells of 16
+//       bytes swizzled inside the row), one 16-byte LDS read per MFMA operand;
+//   KR  [k][row]  row contiguous in global memory: LDS holds the k-lines as they are in memory
+//       (cells swizzled inside the line) and the operand is assembled by two transposing reads
+//       (ds_read_b64_tr_b16: sixteen lanes read a 4 x 16 patch of 16-bit values and each gets
+//       one column of it).
 #include "kernels.h"
 
+#include <type_traits>
 #include <utility>
 
 namespace dash {
@@ -74,12 +77,8 @@ struct Fp16 {
 
 namespace {
 
-#ifndef DASH_HBK
-#define DASH_HBK 64
-#endif
-constexpr int HBK = DASH_HBK;         // K slab (16-bit elements): 32 or 64
-constexpr int HKC_PITCH = HBK + 8;    // elements per row in the KC layout (8 of padding)
-constexpr int HKQ = HBK / 8;          // 16-byte vectors per row of a KC slab
+constexpr int HBK = 64;               // K slab (16-bit elements)
+constexpr int HKQ = HBK / 8;          // 16-byte cells per row of a KC slab
 // workgroup shape per tile edge: WC x WC wavefronts, each computing a WT x WT part of the tile
 //   TILE  64: 2 x 2 wavefronts of 32 x 32   (256 threads)
 //   TILE 128: 2 x 2 wavefronts of 64 x 64   (256 threads, two workgroups per CU)
@@ -94,51 +93,44 @@ struct HCfg {
 };
 constexpr int HNUM_XCD = 8;
 
-// 16-byte vectors a thread carries per operand slab
+// An operand slab is TILE x 64 elements = TILE/8 chunks of 1 KB; one chunk is one wavefront-wide direct load.
 template <int TILE>
-struct HRegs {
-    static constexpr int NV = TILE * HKQ / HCfg<TILE>::NT;
+struct HDma {
+    static constexpr int NW = HCfg<TILE>::NT / 64;      // wavefronts of the workgroup
+    static constexpr int CHUNKS = TILE / 8;
+    static constexpr int NV = CHUNKS / NW;              // loads per wavefront, operand and slab: 2, 4, 2
+    static constexpr int CPR = TILE / 8;                // 16-byte cells per k-line of a KR slab
+    static constexpr int LPC = 64 / CPR;                // k-lines of a KR slab per chunk
+    static constexpr int SLAB = TILE * HBK * 2;         // bytes of one operand slab
 };
 
+// Swizzles (a direct load cannot pad rows, but every lane picks its own source cell):
+//   KC  cell q of row r sits at cell q ^ ((r / 2) % 8) of the row: sixteen consecutive rows at one q - what
+//       sixteen lanes of an operand read touch - fall into sixteen different 16-byte bank groups;
+//   KR  cell c of k-line k sits at cell c ^ kr_swizzle(k) of the line: the four k-lines x four cells that
+//       thirty-two lanes of a transposing read touch fall into sixteen different bank groups.
+__device__ __forceinline__ int kc_swizzle(int row) { return (row >> 1) & 7; }
 template <int TILE>
-struct HLds {
-    static constexpr int KC_BYTES = TILE * HKC_PITCH * 2;
-    static constexpr int K8_BYTES = HKQ * TILE * 16;
-    static constexpr int BYTES = KC_BYTES > K8_BYTES ? KC_BYTES : K8_BYTES;
-};
+__device__ __forceinline__ int kr_swizzle(int k) { return HDma<TILE>::CPR >= 16 ? 4 * (k & 3) : 4 * ((k >> 1) & 1); }
 
-// The K8 path (operand stored row-contiguous in global memory, i.e. k is the slow index): a thread owns
-// LINES consecutive k-lines x 8 consecutive rows.  TILE/8 row groups x 8/LINES line groups x HBK/8
-// k-groups = 256 threads.
-template <int TILE>
-struct HK8 {
-    static constexpr int LINES = HRegs<TILE>::NV;  // 2, 4, 2 for TILE 256, 128, 64
-    static constexpr int GPL = TILE / 8;           // 8-row groups per k-line
-    static constexpr int SUBS = 8 / LINES;         // line groups per group of 8 k
-    static_assert(GPL * SUBS * HKQ == HCfg<TILE>::NT, "K8 decomposition must cover the workgroup");
-};
-
-// A slab is TILE*HBK 16-bit elements = TILE*HKQ 16-byte vectors; a thread carries NV of them.  Their byte
-// offsets inside the block, without the part that moves with the slab, are fixed for the whole tile: they are
-// computed once (32 bits suffice: a block has at most 16384^2 * 2 bytes) and every load is "uniform base of
-// the slab + per-thread offset", which keeps the address arithmetic out of the K loop.
+// Byte offsets, inside the block and without the part that moves with the slab, of the cells one lane
+// fetches: fixed for the whole tile, computed once (32 bits suffice: a block has at most 16384^2 * 2 bytes),
+// so that every load is "uniform base of the slab + per-lane offset".
 template <int TILE, bool KC>
-__device__ __forceinline__ void hslab_offsets(int ld, int row0, unsigned (&off)[HRegs<TILE>::NV]) {
-    constexpr int NV = HRegs<TILE>::NV;
-    const int t = threadIdx.x;
-    if (KC) {           // element (row, k) at base[row*ld + k]: HKQ vectors per row
+__device__ __forceinline__ void hdma_offsets(int ld, int row0, int wave, int lane, unsigned (&off)[HDma<TILE>::NV]) {
+    typedef HDma<TILE> D;
 #pragma unroll
-        for (int u = 0; u < NV; ++u) {
-            const int f = t + HCfg<TILE>::NT * u;
-            const int row = f / HKQ, kq = f % HKQ;
-            off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 8u * kq) * 2u;
+    for (int u = 0; u < D::NV; ++u) {
+        const int ch = wave + D::NW * u;
+        if (KC) {           // element (row, k) at base[row*ld + k]: a chunk is eight rows
+            const int row = 8 * ch + (lane >> 3);
+            const int q = (lane & 7) ^ kc_swizzle(row);
+            off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 8u * q) * 2u;
+        } else {            // element (row, k) at base[k*ld + row]: a chunk is LPC k-lines
+            const int k = D::LPC * ch + lane / D::CPR;
+            const int c = (lane % D::CPR) ^ kr_swizzle<TILE>(k);
+            off[u] = ((unsigned)k * (unsigned)ld + row0 + 8u * c) * 2u;
         }
-    } else {            // element (row, k) at base[k*ld + row]
-        typedef HK8<TILE> U;
-        const int rg = t % U::GPL, sub = (t / U::GPL) % U::SUBS, kg = t / (U::GPL * U::SUBS);
-#pragma unroll
-        for (int l = 0; l < U::LINES; ++l)
-            off[l] = ((unsigned)(8 * kg + U::LINES * sub + l) * (unsigned)ld + row0 + 8u * rg) * 2u;
     }
 }
 
@@ -148,73 +140,66 @@ __device__ __forceinline__ size_t hslab_base(int ld, int k0) {
     return KC ? (size_t)k0 * 2 : (size_t)k0 * ld * 2;
 }
 
+// request one operand slab: global memory -> LDS, no registers in between.  `wave` must be uniform.
 template <int TILE>
-__device__ __forceinline__ void hload_slab(const char* __restrict__ slab, const unsigned (&off)[HRegs<TILE>::NV],
-                                           v4u (&r)[HRegs<TILE>::NV]) {
+__device__ __forceinline__ void hdma_load(const char* __restrict__ slab, const unsigned (&off)[HDma<TILE>::NV],
+                                          char* __restrict__ dst, int wave) {
+    typedef HDma<TILE> D;
 #pragma unroll
-    for (int u = 0; u < HRegs<TILE>::NV; ++u) r[u] = *reinterpret_cast<const v4u*>(slab + off[u]);
+    for (int u = 0; u < D::NV; ++u)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(slab + off[u]),
+                                         (__attribute__((address_space(3))) void*)(dst + (wave + D::NW * u) * 1024),
+                                         16, 0, 0);
 }
 
-// K8 layout in LDS: [k/8][row'][8 k], 16 bytes per (k-group, row), row' = row ^ ((row / 8) % 8): the
-// swizzle spreads the eight rows one thread writes at stride 128 bytes over all banks, and keeps 32
-// consecutive rows inside the same 512 bytes, so an MFMA operand (eight consecutive k of one row) is
-// one conflict-free 16-byte read per lane, exactly as in the KC layout.
-template <int TILE, bool KC>
-__device__ __forceinline__ void hstore_slab(char* __restrict__ s, const v4u (&r)[HRegs<TILE>::NV]) {
-    constexpr int NV = HRegs<TILE>::NV;
-    const int t = threadIdx.x;
-    if (KC) {
+// Per-lane LDS byte offsets of the operand fragments of a wavefront's MT sub-tiles of 32 rows, the first at
+// r0.  Lane L holds row L%32 of the sub-tile and k = 16 st + 8 (L/32) + 0..7 of MFMA step st.  KC: one offset
+// per step (the swizzle depends on the step), the sub-tile adds an immediate; KR: one offset per sub-tile (the
+// swizzle depends on it), the step adds an immediate.
+template <int TILE, bool KC, int MT>
+struct HFrag {
+    int base[KC ? 4 : MT];
+    __device__ __forceinline__ void init(int r0, int lane) {
+        if (KC) {
+            const int row = r0 + (lane & 31);
 #pragma unroll
-        for (int u = 0; u < NV; ++u) {
-            const int f = t + HCfg<TILE>::NT * u;
-            const int row = f / HKQ, kq = f % HKQ;
-            *reinterpret_cast<v4u*>(s + (row * HKC_PITCH + 8 * kq) * 2) = r[u];
-        }
-    } else {
-        typedef HK8<TILE> U;
-        const int rg = t % U::GPL, sub = (t / U::GPL) % U::SUBS, kg = t / (U::GPL * U::SUBS);
-        char* d = s + (kg * TILE + 8 * rg) * 16 + sub * U::LINES * 2;
+            for (int st = 0; st < 4; ++st) base[st] = row * 128 + (((2 * st + (lane >> 5)) ^ kc_swizzle(row)) << 4);
+        } else {
+            // sixteen lanes j = L%16 read the patch k-lines kk .. kk+3 x rows rs .. rs+15: lane j supplies the
+            // address of line kk + j/4, rows rs + 4 (j%4) .. +3, and receives row rs + j of all four lines
+            const int j = lane & 15;
+            const int kk = 8 * (lane >> 5) + (j >> 2);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {       // row 8*rg + i: its LINES consecutive k, two per dword
-            unsigned int w[U::LINES / 2];
-#pragma unroll
-            for (int kp = 0; kp < U::LINES / 2; ++kp) {
-                const unsigned int a = r[2 * kp][i / 2], b = r[2 * kp + 1][i / 2];
-                w[kp] = (i & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-            }
-            char* q = d + ((i ^ (rg & 7)) * 16);
-            if (U::LINES == 8) {
-                v4u v; v[0] = w[0]; v[1] = w[1 % (U::LINES / 2)]; v[2] = w[2 % (U::LINES / 2)]; v[3] = w[3 % (U::LINES / 2)];
-                *reinterpret_cast<v4u*>(q) = v;
-            } else if (U::LINES == 4) {
-                typedef unsigned int v2u __attribute__((ext_vector_type(2)));
-                v2u v; v[0] = w[0]; v[1] = w[1 % (U::LINES / 2)];
-                *reinterpret_cast<v2u*>(q) = v;
-            } else {
-                *reinterpret_cast<unsigned int*>(q) = w[0];
+            for (int i = 0; i < MT; ++i) {
+                const int rs = r0 + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
+                base[i] = (kk * HDma<TILE>::CPR + ((rs >> 3) ^ kr_swizzle<TILE>(kk))) * 16 + 8 * (j & 1);
             }
         }
     }
-}
-
-// operand of MFMA step `st` (16 k each) for the 32-row sub-tile at r0:
-// element (r0 + lane%32, 16*st + 8*(lane/32) + 0..7)
-template <int TILE, bool KC>
-__device__ __forceinline__ v4u hread_frag(const char* __restrict__ s, int r0, int st, int lane) {
-    const int rr = r0 + (lane & 31);
-    if (KC) return *reinterpret_cast<const v4u*>(s + (rr * HKC_PITCH + 16 * st + 8 * (lane >> 5)) * 2);
-    return *reinterpret_cast<const v4u*>(s + ((2 * st + (lane >> 5)) * TILE + (rr ^ ((rr >> 3) & 7))) * 16);
-}
+    __device__ __forceinline__ v4u read(const char* __restrict__ s, int i, int st) const {
+        if (KC) return *reinterpret_cast<const v4u*>(s + base[st] + i * (32 * 128));
+        typedef short v4h __attribute__((ext_vector_type(4)));
+        typedef v4h __attribute__((address_space(3))) * lptr;
+        const char* p = s + base[i] + st * (16 * HDma<TILE>::CPR * 16);
+        union { v4h h[2]; v4u u; } x;
+        x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
+        x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 4 * HDma<TILE>::CPR * 16));
+        return x.u;
+    }
+};
 
 template <typename H, int TILE, bool TA, bool TB>
 __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_kernel(GemmLaunch g) {
     constexpr int MT = HCfg<TILE>::WT / 32;
     constexpr bool A_KC = !TA;
     constexpr bool B_KC = TB;
-    constexpr int NV = HRegs<TILE>::NV;
-    constexpr int SLAB = HLds<TILE>::BYTES;
+    constexpr int NV = HDma<TILE>::NV;
+    constexpr int SLAB = HDma<TILE>::SLAB;
 
-    __shared__ __attribute__((aligned(16))) char lds[2 * 2 * SLAB];
+    // one object per stage: the compiler then knows that fragment reads of one stage cannot touch the other,
+    // into which the next slab is in flight, and does not wait for those loads before the reads
+    __shared__ __attribute__((aligned(1024))) char stage0[2 * SLAB];
+    __shared__ __attribute__((aligned(1024))) char stage1[2 * SLAB];
 
     const int64_t W = gridDim.x;
     const int64_t bid = blockIdx.x;
@@ -253,7 +238,7 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     const u16* __restrict__ Alo = P.A2 ? static_cast<const u16*>(P.A2) + boff : Ahi;
     const u16* __restrict__ Blo = P.B2 ? static_cast<const u16*>(P.B2) + boff : Bhi;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = (wave / HCfg<TILE>::WC) * HCfg<TILE>::WT, wn = (wave % HCfg<TILE>::WC) * HCfg<TILE>::WT;
 
     v16f acc[MT][MT];
@@ -266,10 +251,13 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
 
     const int KS = B / HBK;             // slabs per segment
     const int KT = nseg * KS;           // slabs in all
-    v4u ra[NV], rb[NV];
     unsigned offa[NV], offb[NV];
-    hslab_offsets<TILE, A_KC>(B, row0, offa);
-    hslab_offsets<TILE, B_KC>(B, col0, offb);
+    hdma_offsets<TILE, A_KC>(B, row0, wave, lane, offa);
+    hdma_offsets<TILE, B_KC>(B, col0, wave, lane, offb);
+    HFrag<TILE, A_KC, MT> fra;
+    HFrag<TILE, B_KC, MT> frb;
+    fra.init(wm, lane);
+    frb.init(wn, lane);
     // The slabs are requested in order, segment after segment (the small terms are summed first:
     // A_lo B_hi, A_hi B_lo, A_hi B_hi; a plain product is the last segment alone).  The uniform base
     // addresses of the next slab are carried along and stepped, so the K loop holds no address set-up.
@@ -277,9 +265,9 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     int seg_next = nseg == 1 ? 2 : 0, ks_next = 0;
     const char* pa = reinterpret_cast<const char*>(seg_next == 0 ? Alo : Ahi);
     const char* pb = reinterpret_cast<const char*>(Bhi);
-    auto load_next = [&]() {
-        hload_slab<TILE>(pa, offa, ra);
-        hload_slab<TILE>(pb, offb, rb);
+    auto load_next = [&](char* dst) {
+        hdma_load<TILE>(pa, offa, dst, wave);
+        hdma_load<TILE>(pb, offb, dst + SLAB, wave);
         if (++ks_next < KS) {
             pa += stepa;
             pb += stepb;
@@ -290,24 +278,23 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
             pb = reinterpret_cast<const char*>(seg_next == 1 ? Blo : Bhi);
         }
     };
-    // multiply slab kt out of its LDS buffer
-    auto compute = [&](auto BUF) {
-        const char* sa = lds + decltype(BUF)::value * 2 * SLAB;
+    // multiply a slab out of its stage
+    auto compute = [&](const char* sa) {
         const char* sb = sa + SLAB;
         // operand fragments of step st+1 are requested from LDS before the MFMAs of step st issue
         v4u fa[2][MT], fb[2][MT];
 #pragma unroll
-        for (int i = 0; i < MT; ++i) fa[0][i] = hread_frag<TILE, A_KC>(sa, wm + 32 * i, 0, lane);
+        for (int i = 0; i < MT; ++i) fa[0][i] = fra.read(sa, i, 0);
 #pragma unroll
-        for (int j = 0; j < MT; ++j) fb[0][j] = hread_frag<TILE, B_KC>(sb, wn + 32 * j, 0, lane);
+        for (int j = 0; j < MT; ++j) fb[0][j] = frb.read(sb, j, 0);
 #pragma unroll
         for (int st = 0; st < HBK / 16; ++st) {
             const int cur = st & 1, nxt = cur ^ 1;
             if (st + 1 < HBK / 16) {
 #pragma unroll
-                for (int i = 0; i < MT; ++i) fa[nxt][i] = hread_frag<TILE, A_KC>(sa, wm + 32 * i, st + 1, lane);
+                for (int i = 0; i < MT; ++i) fa[nxt][i] = fra.read(sa, i, st + 1);
 #pragma unroll
-                for (int j = 0; j < MT; ++j) fb[nxt][j] = hread_frag<TILE, B_KC>(sb, wn + 32 * j, st + 1, lane);
+                for (int j = 0; j < MT; ++j) fb[nxt][j] = frb.read(sb, j, st + 1);
             }
 #pragma unroll
             for (int i = 0; i < MT; ++i)
@@ -316,32 +303,25 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
                     acc[i][j] = H::mfma(fa[cur][i], fb[cur][j], acc[i][j]);
         }
     };
-    load_next();
-    hstore_slab<TILE, A_KC>(lds, ra);
-    hstore_slab<TILE, B_KC>(lds + SLAB, rb);
-    __syncthreads();
-    // one iteration per slab; the loop is unrolled by two so that the LDS buffer of a slab is a compile-time
-    // constant and every LDS address is "per-thread base + immediate"
-    auto iteration = [&](int kt, auto BUF) {
-        const bool more = kt + 1 < KT;
-        if (more) load_next();           // next slab into registers while this one is multiplied
-        compute(BUF);
-        if (more) {
-            char* da = lds + (1 - decltype(BUF)::value) * 2 * SLAB;
-            hstore_slab<TILE, A_KC>(da, ra);
-            hstore_slab<TILE, B_KC>(da + SLAB, rb);
-        }
-        __syncthreads();
-    };
+    load_next(stage0);
+    __syncthreads();                    // waits for the direct loads as well
+    // One iteration per slab, unrolled by two so that the stage of a slab is a compile-time constant.  The
+    // next slab is requested into the other stage, which every wavefront left before the last barrier.
     for (int kt = 0; kt < KT; kt += 2) {
-        iteration(kt, std::integral_constant<int, 0>{});
-        if (kt + 1 < KT) iteration(kt + 1, std::integral_constant<int, 1>{});
+        if (kt + 1 < KT) load_next(stage1);
+        compute(stage0);
+        __syncthreads();
+        if (kt + 1 < KT) {
+            if (kt + 2 < KT) load_next(stage0);
+            compute(stage1);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue, staged through LDS (free after the last barrier of the main loop) ----
     // The MFMA leaves a lane with one column and scattered rows; storing from there means 4-byte (or
     // 2-byte) stores and a fully unrolled epilogue whose code no longer fits the instruction cache.
-    // Instead every wavefront passes its accumulators, one strip of 32 rows x WT columns at a time,
+    // Instead every wavefront passes its accumulators, one strip of 16 rows x WT columns at a time,
     // through a private LDS region and comes back with row-contiguous quads: 16-byte loads of D,
     // 16-byte stores of fp32 outputs, 8-byte stores of 16-bit outputs, in a compact loop.
     const float mult = P.mult ? P.mult[blk] : 1.f;
@@ -355,75 +335,104 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     // symmetric mode: an off-diagonal tile is also written transposed
     const bool mirror = g.sym && ti != tj;
     constexpr int WT = HCfg<TILE>::WT;            // columns of a wavefront's strip
-    constexpr int SP = WT + 4;                    // strip pitch in floats
     constexpr int QPR = WT / 4;                   // quads per strip row
     constexpr int RPI = 64 / QPR;                 // strip rows one pass of the wavefront covers
-    static_assert((HCfg<TILE>::NT / 64) * 32 * SP * 4 <= 4 * SLAB, "strips must fit the operand buffers");
-    float* strip = reinterpret_cast<float*>(lds) + wave * 32 * SP;
+    static_assert((HCfg<TILE>::NT / 64) * 16 * WT * 4 <= 2 * SLAB, "strips must fit one stage");
+    // strip rows are not padded; rows whose bit 2 is set swap their column halves instead, which keeps the two
+    // rows (r, r + 4) that one MFMA register spreads over the lane halves in different banks
+    float* strip = reinterpret_cast<float*>(stage0) + wave * 16 * WT;
+    auto swz = [](int row) { return (WT / 2) * ((row >> 2) & 1); };
     bool bad = false;
-    static_for<MT>([&](auto I) {
-        constexpr int i = decltype(I)::value;
-        // phase A: alpha * acc into the strip, element (8q + 4(lane/32) + m, 32j + lane%32)
+    static_for<2 * MT>([&](auto IH) {
+        constexpr int i = decltype(IH)::value / 2, hs = decltype(IH)::value % 2;     // sub-tile, half of it
+        // phase A: alpha * acc into the strip, element (8 (q%2) + 4 (lane/32) + m, 32 j + lane%32), q = r/4, m = r%4
         static_for<MT>([&](auto J) {
             constexpr int j = decltype(J)::value;
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                strip[(8 * (r / 4) + 4 * (lane >> 5) + (r % 4)) * SP + 32 * j + (lane & 31)] = alpha * acc[i][j][r];
+            for (int r8 = 0; r8 < 8; ++r8) {
+                const int rl = 8 * (r8 / 4) + 4 * (lane >> 5) + (r8 % 4);
+                strip[rl * WT + ((32 * j + (lane & 31)) ^ swz(rl))] = alpha * acc[i][j][8 * hs + r8];
+            }
         });
-        __syncthreads();
-        // phase B: row-contiguous quads
-        const int rbase = row0 + wm + 32 * i, cbase = col0 + wn;
+        // The strip belongs to this wavefront alone, and the LDS executes the accesses of one wavefront in the
+        // order they were issued: no barrier between the phases, the compiler only has to keep that order.
+        __builtin_amdgcn_wave_barrier();
+        // phase B: row-contiguous quads.  Strips that the diagonal does not cross (the common case) skip all
+        // diagonal handling; outputs that were not asked for cost nothing.
+        const int rbase = row0 + wm + 32 * i + 16 * hs, cbase = col0 + wn;
+        auto quads = [&](auto DIAG) {
+            constexpr bool diag = decltype(DIAG)::value;
 #pragma unroll 1
-        for (int t = 0; t < 32 / RPI; ++t) {
-            const int rl = lane / QPR + RPI * t, c = (lane % QPR) * 4;
-            v4f v = *reinterpret_cast<const v4f*>(strip + rl * SP + c);
-            const int row = rbase + rl, col = cbase + c;
-            const size_t off = (size_t)row * B + col;
-            if (Db) {
-                const v4f d = *reinterpret_cast<const v4f*>(Db + off);
+            for (int t = 0; t < 16 / RPI; ++t) {
+                const int rl = lane / QPR + RPI * t, c = (lane % QPR) * 4;
+                float* sp = strip + rl * WT + (c ^ swz(rl));
+                v4f v = *reinterpret_cast<const v4f*>(sp);
+                const int row = rbase + rl, col = cbase + c;
+                const size_t off = (size_t)row * B + col;
+                if (Db) {
+                    const v4f d = *reinterpret_cast<const v4f*>(Db + off);
 #pragma unroll
-                for (int m = 0; m < 4; ++m) v[m] += beta * d[m];
-            }
-            v4s h, h2, lo;
+                    for (int m = 0; m < 4; ++m) v[m] += beta * d[m];
+                }
 #pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                if (row == col + m) v[m] += gamma;
-                bad |= !(fabsf(v[m]) <= 3.0e38f);
-                h[m] = H::from_float(v[m]);
-                lo[m] = H::from_float(v[m] - H::to_float(h[m]));
-                h2[m] = H::from_float(a2 * v[m] + (row == col + m ? g2 : 0.f));
+                for (int m = 0; m < 4; ++m) {
+                    if (diag && row == col + m) v[m] += gamma;
+                    bad |= !(fabsf(v[m]) <= 3.0e38f);
+                }
+                if (Cb) *reinterpret_cast<v4f*>(Cb + off) = v;
+                if (Hb || Lb) {
+                    v4s h, lo;
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        h[m] = H::from_float(v[m]);
+                        lo[m] = H::from_float(v[m] - H::to_float(h[m]));
+                    }
+                    if (Hb) *reinterpret_cast<v4s*>(Hb + off) = h;
+                    if (Lb) *reinterpret_cast<v4s*>(Lb + off) = lo;
+                }
+                if (H2b) {
+                    v4s h2;
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) h2[m] = H::from_float(a2 * v[m] + (diag && row == col + m ? g2 : 0.f));
+                    *reinterpret_cast<v4s*>(H2b + off) = h2;
+                }
+                if (mirror) *reinterpret_cast<v4f*>(sp) = v;       // final values for phase C
             }
-            if (Cb) *reinterpret_cast<v4f*>(Cb + off) = v;
-            if (Hb) *reinterpret_cast<v4s*>(Hb + off) = h;
-            if (Lb) *reinterpret_cast<v4s*>(Lb + off) = lo;
-            if (H2b) *reinterpret_cast<v4s*>(H2b + off) = h2;
-            if (mirror) *reinterpret_cast<v4f*>(strip + rl * SP + c) = v;     // final values for phase C
-        }
-        __syncthreads();
-        // phase C (mirrored tiles only): back in the MFMA layout a lane holds four consecutive rows of
-        // one column = four consecutive elements of a row of the transposed tile
+        };
+        if (rbase + 16 > cbase && rbase < cbase + WT) quads(std::true_type{});
+        else quads(std::false_type{});
+        __builtin_amdgcn_wave_barrier();
+        // phase C (mirrored tiles only, never on the diagonal): back in the MFMA layout a lane holds four
+        // consecutive rows of one column = four consecutive elements of a row of the transposed tile
         if (mirror) {
 #pragma unroll 1
-            for (int jq = 0; jq < MT * 4; ++jq) {
-                const int j = jq >> 2, q = jq & 3;
+            for (int jq = 0; jq < MT * 2; ++jq) {
+                const int j = jq >> 1, q = jq & 1;
                 const int rl = 8 * q + 4 * (lane >> 5), cl = 32 * j + (lane & 31);
                 const int row = rbase + rl, col = cbase + cl;
                 v4f v;
-                v4s h, h2, lo;
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    v[m] = strip[(rl + m) * SP + cl];
-                    h[m] = H::from_float(v[m]);
-                    lo[m] = H::from_float(v[m] - H::to_float(h[m]));
-                    h2[m] = H::from_float(a2 * v[m] + (row + m == col ? g2 : 0.f));
-                }
+                for (int m = 0; m < 4; ++m) v[m] = strip[(rl + m) * WT + (cl ^ swz(rl))];
                 const size_t moff = (size_t)col * B + row;
                 if (Cb) *reinterpret_cast<v4f*>(Cb + moff) = v;
-                if (Hb) *reinterpret_cast<v4s*>(Hb + moff) = h;
-                if (Lb) *reinterpret_cast<v4s*>(Lb + moff) = lo;
-                if (H2b) *reinterpret_cast<v4s*>(H2b + moff) = h2;
+                if (Hb || Lb) {
+                    v4s h, lo;
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        h[m] = H::from_float(v[m]);
+                        lo[m] = H::from_float(v[m] - H::to_float(h[m]));
+                    }
+                    if (Hb) *reinterpret_cast<v4s*>(Hb + moff) = h;
+                    if (Lb) *reinterpret_cast<v4s*>(Lb + moff) = lo;
+                }
+                if (H2b) {
+                    v4s h2;
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) h2[m] = H::from_float(a2 * v[m]);
+                    *reinterpret_cast<v4s*>(H2b + moff) = h2;
+                }
             }
-            __syncthreads();
+            __builtin_amdgcn_wave_barrier();
         }
     });
     if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;
