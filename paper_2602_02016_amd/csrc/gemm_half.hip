@@ -77,39 +77,50 @@ struct Fp16 {
 
 namespace {
 
-constexpr int HBK = 64;               // K slab (16-bit elements)
-constexpr int HKQ = HBK / 8;          // 16-byte cells per row of a KC slab
-// workgroup shape per tile edge: WC x WC wavefronts, each computing a WT x WT part of the tile
-//   TILE  64: 2 x 2 wavefronts of 32 x 32   (256 threads)
-//   TILE 128: 2 x 2 wavefronts of 64 x 64   (256 threads, two workgroups per CU)
+// workgroup shape per tile edge: WC x WC wavefronts, each computing a WT x WT part of the tile; K slabs of
+// HBK elements in a ring of NS LDS stages (NS - 1 slabs are in flight while one is multiplied)
+//   TILE  64: 2 x 2 wavefronts of 32 x 32   (256 threads), slabs of 64, 2 stages
+//   TILE 128: 2 x 2 wavefronts of 64 x 64   (256 threads, two workgroups per CU), slabs of 64, 2 stages
 //   TILE 256: 4 x 4 wavefronts of 64 x 64  (1024 threads, one workgroup per CU: the same four wavefronts
-//             per SIMD as two 128 tiles, but every operand panel fetched from L2 serves twice the flops)
+//             per SIMD as two 128 tiles, but every operand panel fetched from L2 serves twice the flops),
+//             slabs of 32 in 5 stages = the 160 KB of the CU: the loads run two slabs of 64 ahead
 template <int TILE>
 struct HCfg {
     static constexpr int WT = TILE == 64 ? 32 : 64;
     static constexpr int WC = TILE / WT;
     static constexpr int NT = 64 * WC * WC;
     static constexpr int OCC = TILE == 256 ? 1 : 2;        // workgroups per CU the kernel is built for
+#ifndef DASH_H256_BK
+#define DASH_H256_BK 64
+#define DASH_H256_NS 2
+#endif
+    static constexpr int HBK = TILE == 256 ? DASH_H256_BK : 64;
+    static constexpr int NS = TILE == 256 ? DASH_H256_NS : 2;
 };
 constexpr int HNUM_XCD = 8;
 
-// An operand slab is TILE x 64 elements = TILE/8 chunks of 1 KB; one chunk is one wavefront-wide direct load.
+// An operand slab is TILE x HBK elements, moved as chunks of 1 KB; one chunk is one wavefront-wide direct load.
 template <int TILE>
 struct HDma {
+    static constexpr int HBK = HCfg<TILE>::HBK;
+    static constexpr int HKQ = HBK / 8;                 // 16-byte cells per row of a KC slab
+    static constexpr int RPC = 64 / HKQ;                // rows of a KC slab per chunk
     static constexpr int NW = HCfg<TILE>::NT / 64;      // wavefronts of the workgroup
-    static constexpr int CHUNKS = TILE / 8;
-    static constexpr int NV = CHUNKS / NW;              // loads per wavefront, operand and slab: 2, 4, 2
+    static constexpr int CHUNKS = TILE * HBK / 512;
+    static constexpr int NV = CHUNKS / NW;              // loads per wavefront, operand and slab: 2, 4, 1
     static constexpr int CPR = TILE / 8;                // 16-byte cells per k-line of a KR slab
     static constexpr int LPC = 64 / CPR;                // k-lines of a KR slab per chunk
     static constexpr int SLAB = TILE * HBK * 2;         // bytes of one operand slab
+    static_assert(CHUNKS % NW == 0 && NV >= 1, "chunks must divide over the wavefronts");
 };
 
 // Swizzles (a direct load cannot pad rows, but every lane picks its own source cell):
-//   KC  cell q of row r sits at cell q ^ ((r / 2) % 8) of the row: sixteen consecutive rows at one q - what
+//   KC  cell q of row r sits at cell q ^ kc_swizzle(r) of the row: sixteen consecutive rows at one q - what
 //       sixteen lanes of an operand read touch - fall into sixteen different 16-byte bank groups;
 //   KR  cell c of k-line k sits at cell c ^ kr_swizzle(k) of the line: the four k-lines x four cells that
 //       thirty-two lanes of a transposing read touch fall into sixteen different bank groups.
-__device__ __forceinline__ int kc_swizzle(int row) { return (row >> 1) & 7; }
+template <int TILE>
+__device__ __forceinline__ int kc_swizzle(int row) { return HDma<TILE>::HKQ == 8 ? (row >> 1) & 7 : (row >> 2) & 3; }
 template <int TILE>
 __device__ __forceinline__ int kr_swizzle(int k) { return HDma<TILE>::CPR >= 16 ? 4 * (k & 3) : 4 * ((k >> 1) & 1); }
 
@@ -122,9 +133,9 @@ __device__ __forceinline__ void hdma_offsets(int ld, int row0, int wave, int lan
 #pragma unroll
     for (int u = 0; u < D::NV; ++u) {
         const int ch = wave + D::NW * u;
-        if (KC) {           // element (row, k) at base[row*ld + k]: a chunk is eight rows
-            const int row = 8 * ch + (lane >> 3);
-            const int q = (lane & 7) ^ kc_swizzle(row);
+        if (KC) {           // element (row, k) at base[row*ld + k]: a chunk is RPC rows
+            const int row = D::RPC * ch + lane / D::HKQ;
+            const int q = (lane % D::HKQ) ^ kc_swizzle<TILE>(row);
             off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 8u * q) * 2u;
         } else {            // element (row, k) at base[k*ld + row]: a chunk is LPC k-lines
             const int k = D::LPC * ch + lane / D::CPR;
@@ -141,15 +152,22 @@ __device__ __forceinline__ size_t hslab_base(int ld, int k0) {
 }
 
 // request one operand slab: global memory -> LDS, no registers in between.  `wave` must be uniform.
+// Written as assembly on purpose: the compiler tracks direct loads it knows of and, where control flow
+// merges, makes LDS reads of OTHER stages wait for all of them (vmcnt(0) right after a request = the whole
+// memory latency exposed).  Here every wait is explicit instead: wait_vm_lgkm before the barrier that opens a
+// slab.  The "memory" clobber keeps LDS accesses on their side of the request.
 template <int TILE>
 __device__ __forceinline__ void hdma_load(const char* __restrict__ slab, const unsigned (&off)[HDma<TILE>::NV],
                                           char* __restrict__ dst, int wave) {
     typedef HDma<TILE> D;
 #pragma unroll
-    for (int u = 0; u < D::NV; ++u)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(slab + off[u]),
-                                         (__attribute__((address_space(3))) void*)(dst + (wave + D::NW * u) * 1024),
-                                         16, 0, 0);
+    for (int u = 0; u < D::NV; ++u) {
+        const unsigned lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(dst + (wave + D::NW * u) * 1024);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(lds), "v"(off[u]), "s"(slab)
+                     : "memory", "m0");
+    }
 }
 
 // Per-lane LDS byte offsets of the operand fragments of a wavefront's MT sub-tiles of 32 rows, the first at
@@ -158,12 +176,15 @@ __device__ __forceinline__ void hdma_load(const char* __restrict__ slab, const u
 // swizzle depends on it), the step adds an immediate.
 template <int TILE, bool KC, int MT>
 struct HFrag {
-    int base[KC ? 4 : MT];
+    typedef HDma<TILE> D;
+    static constexpr int STEPS = D::HBK / 16;
+    int base[KC ? STEPS : MT];
     __device__ __forceinline__ void init(int r0, int lane) {
         if (KC) {
             const int row = r0 + (lane & 31);
 #pragma unroll
-            for (int st = 0; st < 4; ++st) base[st] = row * 128 + (((2 * st + (lane >> 5)) ^ kc_swizzle(row)) << 4);
+            for (int st = 0; st < STEPS; ++st)
+                base[st] = row * (D::HBK * 2) + (((2 * st + (lane >> 5)) ^ kc_swizzle<TILE>(row)) << 4);
         } else {
             // sixteen lanes j = L%16 read the patch k-lines kk .. kk+3 x rows rs .. rs+15: lane j supplies the
             // address of line kk + j/4, rows rs + 4 (j%4) .. +3, and receives row rs + j of all four lines
@@ -172,21 +193,29 @@ struct HFrag {
 #pragma unroll
             for (int i = 0; i < MT; ++i) {
                 const int rs = r0 + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
-                base[i] = (kk * HDma<TILE>::CPR + ((rs >> 3) ^ kr_swizzle<TILE>(kk))) * 16 + 8 * (j & 1);
+                base[i] = (kk * D::CPR + ((rs >> 3) ^ kr_swizzle<TILE>(kk))) * 16 + 8 * (j & 1);
             }
         }
     }
     __device__ __forceinline__ v4u read(const char* __restrict__ s, int i, int st) const {
-        if (KC) return *reinterpret_cast<const v4u*>(s + base[st] + i * (32 * 128));
+        if (KC) return *reinterpret_cast<const v4u*>(s + base[st] + i * (32 * D::HBK * 2));
         typedef short v4h __attribute__((ext_vector_type(4)));
         typedef v4h __attribute__((address_space(3))) * lptr;
-        const char* p = s + base[i] + st * (16 * HDma<TILE>::CPR * 16);
+        const char* p = s + base[i] + st * (16 * D::CPR * 16);
         union { v4h h[2]; v4u u; } x;
         x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
-        x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 4 * HDma<TILE>::CPR * 16));
+        x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 4 * D::CPR * 16));
         return x.u;
     }
 };
+
+// s_waitcnt: at most N vector-memory operations of this wavefront still in flight, and none of its LDS
+// operations (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at "do not wait", lgkmcnt 11:8)
+template <int N>
+__device__ __forceinline__ void wait_vm_lgkm() {
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));
+}
 
 template <typename H, int TILE, bool TA, bool TB>
 __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_kernel(GemmLaunch g) {
@@ -195,11 +224,25 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     constexpr bool B_KC = TB;
     constexpr int NV = HDma<TILE>::NV;
     constexpr int SLAB = HDma<TILE>::SLAB;
+    constexpr int HBK = HCfg<TILE>::HBK;
+    constexpr int NS = HCfg<TILE>::NS;
+    static_assert(NS >= 2 && NS <= 5, "two to five stages");
 
-    // one object per stage: the compiler then knows that fragment reads of one stage cannot touch the other,
-    // into which the next slab is in flight, and does not wait for those loads before the reads
+    // one object per stage: the compiler then knows that fragment reads of one stage cannot touch the others,
+    // into which later slabs are in flight, and does not wait for those loads before the reads
     __shared__ __attribute__((aligned(1024))) char stage0[2 * SLAB];
     __shared__ __attribute__((aligned(1024))) char stage1[2 * SLAB];
+    __shared__ __attribute__((aligned(1024))) char stage2[NS > 2 ? 2 * SLAB : 1024];
+    __shared__ __attribute__((aligned(1024))) char stage3[NS > 3 ? 2 * SLAB : 1024];
+    __shared__ __attribute__((aligned(1024))) char stage4[NS > 4 ? 2 * SLAB : 1024];
+    auto stage = [&](auto S) -> char* {
+        constexpr int st = decltype(S)::value;
+        if constexpr (st == 0) return stage0;
+        else if constexpr (st == 1) return stage1;
+        else if constexpr (st == 2) return stage2;
+        else if constexpr (st == 3) return stage3;
+        else return stage4;
+    };
 
     const int64_t W = gridDim.x;
     const int64_t bid = blockIdx.x;
@@ -278,45 +321,64 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
             pb = reinterpret_cast<const char*>(seg_next == 1 ? Blo : Bhi);
         }
     };
-    // multiply a slab out of its stage
-    auto compute = [&](const char* sa) {
-        const char* sb = sa + SLAB;
-        // operand fragments of step st+1 are requested from LDS before the MFMAs of step st issue
-        v4u fa[2][MT], fb[2][MT];
+    // Fragments of MFMA step st live in register set st % 2; those of step st + 1 are requested before the MFMAs
+    // of step st issue.
+    constexpr int STEPS = HBK / 16;
+    v4u fa[2][MT], fb[2][MT];
+    auto frags = [&](const char* sa, auto ST) {
+        constexpr int st = decltype(ST)::value, b = st & 1;
 #pragma unroll
-        for (int i = 0; i < MT; ++i) fa[0][i] = fra.read(sa, i, 0);
+        for (int i = 0; i < MT; ++i) fa[b][i] = fra.read(sa, i, st);
 #pragma unroll
-        for (int j = 0; j < MT; ++j) fb[0][j] = frb.read(sb, j, 0);
-#pragma unroll
-        for (int st = 0; st < HBK / 16; ++st) {
-            const int cur = st & 1, nxt = cur ^ 1;
-            if (st + 1 < HBK / 16) {
-#pragma unroll
-                for (int i = 0; i < MT; ++i) fa[nxt][i] = fra.read(sa, i, st + 1);
-#pragma unroll
-                for (int j = 0; j < MT; ++j) fb[nxt][j] = frb.read(sb, j, st + 1);
-            }
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < MT; ++j)
-                    acc[i][j] = H::mfma(fa[cur][i], fb[cur][j], acc[i][j]);
-        }
+        for (int j = 0; j < MT; ++j) fb[b][j] = frb.read(sa + SLAB, j, st);
     };
-    load_next(stage0);
-    __syncthreads();                    // waits for the direct loads as well
-    // One iteration per slab, unrolled by two so that the stage of a slab is a compile-time constant.  The
-    // next slab is requested into the other stage, which every wavefront left before the last barrier.
-    for (int kt = 0; kt < KT; kt += 2) {
-        if (kt + 1 < KT) load_next(stage1);
-        compute(stage0);
-        __syncthreads();
-        if (kt + 1 < KT) {
-            if (kt + 2 < KT) load_next(stage0);
-            compute(stage1);
-            __syncthreads();
-        }
+    auto mfmas = [&](auto ST) {
+        constexpr int b = decltype(ST)::value & 1;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < MT; ++j)
+                acc[i][j] = H::mfma(fa[b][i], fb[b][j], acc[i][j]);
+    };
+    // Ring of NS stages.  The barrier that opens slab h + 1 sits before the LAST MFMA step of slab h: by then
+    // a wavefront holds all its fragments of slab h in registers, so (a) the stage of slab h is free and slab
+    // h + NS is requested into it right after the barrier, (b) the first fragments of slab h + 1 are
+    // requested right after the barrier and the MFMAs of the last step of slab h cover the moment when all
+    // wavefronts of the workgroup hit the LDS together.  Before the barrier a wavefront waits until its own
+    // loads of slab h + 1 have landed (those of later slabs may still be under way: the counter retires loads
+    // in order) and its fragment reads are complete.  The ring is unrolled so that the stage of a slab is a
+    // compile-time constant.
+    constexpr int LATER = 2 * NV * (NS - 2);        // loads of one wavefront that may stay in flight at a barrier
+    static_for<NS - 1>([&](auto S) {
+        if (decltype(S)::value < KT) load_next(stage(S));
+    });
+    if (NS - 2 < KT) wait_vm_lgkm<LATER>();
+    else wait_vm_lgkm<0>();
+    __builtin_amdgcn_s_barrier();
+    if (NS - 1 < KT) load_next(stage(std::integral_constant<int, NS - 1>{}));
+    frags(stage0, std::integral_constant<int, 0>{});
+    for (int h0 = 0; h0 < KT; h0 += NS) {
+        static_for<NS>([&](auto S) {
+            constexpr int sg = decltype(S)::value;
+            const int h = h0 + sg;
+            if (h < KT) {
+                const char* cur = stage(S);
+                static_for<STEPS - 1>([&](auto ST) {
+                    frags(cur, std::integral_constant<int, decltype(ST)::value + 1>{});
+                    mfmas(ST);
+                });
+                if (h + 1 < KT) {
+                    if (h + NS - 1 < KT) wait_vm_lgkm<LATER>();
+                    else wait_vm_lgkm<0>();
+                    __builtin_amdgcn_s_barrier();
+                    if (h + NS < KT) load_next(stage(S));
+                    frags(stage(std::integral_constant<int, (sg + 1) % NS>{}), std::integral_constant<int, 0>{});
+                }
+                mfmas(std::integral_constant<int, STEPS - 1>{});
+            }
+        });
     }
+    __syncthreads();                    // every wavefront has left the last slab: LDS is free for the epilogue
 
     // ---- epilogue, staged through LDS (free after the last barrier of the main loop) ----
     // The MFMA leaves a lane with one column and scattered rows; storing from there means 4-byte (or
@@ -337,10 +399,11 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     constexpr int WT = HCfg<TILE>::WT;            // columns of a wavefront's strip
     constexpr int QPR = WT / 4;                   // quads per strip row
     constexpr int RPI = 64 / QPR;                 // strip rows one pass of the wavefront covers
-    static_assert((HCfg<TILE>::NT / 64) * 16 * WT * 4 <= 2 * SLAB, "strips must fit one stage");
+    constexpr int SPS = 2 * SLAB / (16 * WT * 4);     // strips one stage holds
+    static_assert(SPS >= 1 && (HCfg<TILE>::NT / 64 + SPS - 1) / SPS <= 2, "strips must fit the first two stages");
     // strip rows are not padded; rows whose bit 2 is set swap their column halves instead, which keeps the two
     // rows (r, r + 4) that one MFMA register spreads over the lane halves in different banks
-    float* strip = reinterpret_cast<float*>(stage0) + wave * 16 * WT;
+    float* strip = reinterpret_cast<float*>(wave < SPS ? stage0 : stage1) + (wave % SPS) * 16 * WT;
     auto swz = [](int row) { return (WT / 2) * ((row >> 2) & 1); };
     bool bad = false;
     static_for<2 * MT>([&](auto IH) {
