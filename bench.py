@@ -61,16 +61,19 @@ def cpu_baseline(sample_blocks: int, B: int, beta: float, eps: float, p: int, re
                        f"blocks, precondition) on {sample_blocks} of the 16 gradient blocks, B={B}")
 
 
-def sweep(dash):
+def sweep(dash, only_16bit=False):
     """Throughput of the inverse root alone on the shapes of the other workload configurations
     (cfg1: 16 x 128; cfg4: 256 x 256, 64 x 512, 4 x 2048; cfg5: 1024 x 1024), every method and
     precision.  Timing does not depend on the values, so the stacks are well-conditioned random SPD
     blocks; accuracy on the configurations' own spectra is the business of tests/test_gpu_configs.py.
-    Returns a list of records; `mfma_frac` prices the executed flops against the peak of the operand type."""
+    Returns a list of records; `mfma_frac` prices the executed flops against the peak of the operand type.
+    `only_16bit` keeps the five 16-bit cases on the cfg5 shape (short enough to run under a kernel trace)."""
     import torch
     from paper_2602_02016_amd import chebyshev_fit
     rows = []
     shapes = [("cfg1", 16, 128), ("cfg4", 256, 256), ("cfg4", 64, 512), ("cfg4", 4, 2048), ("cfg5", 1024, 1024)]
+    if only_16bit:
+        shapes = shapes[-1:]
     for cfg, N, B in shapes:
         gen = torch.Generator(device="cuda")
         gen.manual_seed(N + B)
@@ -91,6 +94,8 @@ def sweep(dash):
         if cfg == "cfg5":
             cases += [("newton_db", 4, 10, "bf16"), ("newton_db", 4, 10, "fp16"), ("newton_db", 4, 10, "bf16x3"),
                       ("coupled_newton", 4, 10, "fp16"), ("chebyshev", 4, 16, "fp16")]
+        if only_16bit:
+            cases = [c for c in cases if c[3] != "fp32"]
         for method, pp, it, prec in cases:
             kw = dict(method=method, p=pp, iters=it, eps=1e-6, precision=prec)
             if method == "chebyshev":
@@ -185,6 +190,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline step: inverse-root throughput on the shapes of the other "
                          "configurations, all methods and precisions (table on stderr, one JSON line)")
+    ap.add_argument("--sweep-16bit", action="store_true",
+                    help="as --sweep, but only the 16-bit cases on 1024 blocks of 1024 (bf16, fp16, split bf16)")
     ap.add_argument("--hbm-kernels", action="store_true",
                     help="instead of the headline step: achieved bandwidth of the memory-bound kernels on a "
                          "1 GiB stack (table on stderr, one JSON line)")
@@ -209,8 +216,8 @@ def main():
         print(json.dumps({"hbm_kernels": hbm_kernels(dash), "peak_tb_per_s": 8.0, "n_gpus": 1, "data": "synthetic"}))
         return
 
-    if args.sweep:
-        print(json.dumps({"sweep": sweep(dash), "unit": "blocks/s", "n_gpus": 1, "data": "synthetic",
+    if args.sweep or args.sweep_16bit:
+        print(json.dumps({"sweep": sweep(dash, only_16bit=args.sweep_16bit), "unit": "blocks/s", "n_gpus": 1, "data": "synthetic",
                           "symmetric_products": not args.full_products}))
         return
 
