@@ -29,7 +29,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 # HBM bytes the matmul kernel moves per block product on this workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size
 # (profiles/gemm_f32_cfg2_hbm_traffic.txt); the algorithmic figure is 12*B^2 = 12.58e6.
-MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 15.30e6
+MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 14.02e6
 
 
 def log(*a):

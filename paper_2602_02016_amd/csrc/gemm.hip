@@ -7,19 +7,22 @@
 //     C_b = mult_b * (alpha * op(A_b) op(B_b) + beta * D_b + gamma * I)
 //
 // Design (CDNA4): one workgroup of 256 threads (four 64-wide wavefronts in a 2 x 2
-// arrangement) owns one TM x TN output tile of one block.  K is walked in slabs of 16
-// that are staged through LDS (double buffered, one barrier per slab) while the next
-// slab is already in flight from global memory into registers.  Each wavefront
+// arrangement) owns one TM x TN output tile of one block.  K is walked in slabs of BK
+// that go from global memory straight into LDS (global_load_lds_dwordx4: a wavefront-wide
+// load fills 1 KB of LDS in lane order, every lane picks its own 16-byte source cell), two
+// stages, the next slab in flight while the current one is multiplied.  Each wavefront
 // accumulates its (TM/2) x (TN/2) sub-tile with v_mfma_f32_32x32x2_f32.
 //
-// Operand staging.  An MFMA operand wants, per lane, the element (row = lane%32,
+// Operand layouts.  An MFMA operand wants, per lane, the element (row = lane%32,
 // k = lane/32).  Depending on which index is contiguous in global memory a slab is
-// kept in one of two LDS layouts, both filled with 16-byte stores straight from
-// 16-byte global loads:
-//   KC  [row][k]  (k contiguous; row pitch 20 floats): one 16-byte LDS read gives a lane
-//       its operand for four consecutive MFMAs (k = 4*(lane/32) + s, s = 0..3);
-//   RC  [k][row]  (row contiguous; k pitch TILE+8 floats): four 4-byte reads, one per
-//       MFMA, lanes reading consecutive addresses.
+// kept in one of two LDS layouts (a direct load cannot pad rows; cells are swizzled
+// instead, by the choice of the source cell):
+//   KC  [row][k]  (k contiguous; rows of BK floats, cell q of row r at q ^ swizzle(r)):
+//       one 16-byte LDS read gives a lane its operand for four consecutive MFMAs
+//       (k = 4*(lane/32) + s, s = 0..3);
+//   RC  [k][row]  (row contiguous; k-lines of TILE floats, the 32-float halves of the
+//       lines with bit 2 of k set swapped): four 4-byte reads, one per MFMA, lanes
+//       reading consecutive addresses.
 // Both layouts use the same k <-> (lane half, step) assignment, so any combination of
 // transposed / non-transposed operands contracts over matching k.
 //
@@ -27,9 +30,24 @@
 // workgroup ids to the 8 XCDs round-robin; the id is remapped so that each XCD works
 // through a contiguous range of blocks and the tiles of one block (which share the
 // A and B panels) meet in one XCD's L2.
+#include "direct_load.h"
 #include "kernels.h"
 
+#include <type_traits>
+#include <utility>
+
 namespace dash {
+
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <typename F, int... Is>
+__device__ __forceinline__ void fstatic_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void fstatic_for(F&& f) {
+    fstatic_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -38,38 +56,47 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #define DASH_BK 16
 #endif
 constexpr int BK = DASH_BK;        // K slab (16 or 32)
-constexpr int KC_PITCH = BK + 4;   // floats per row in the k-contiguous layout (4 floats of padding)
-constexpr int KQ = BK / 4;         // float4 per row of a k-contiguous slab
+constexpr int KQ = BK / 4;         // 16-byte cells per row of a k-contiguous slab
 constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
 
+// An operand slab is TILE x BK floats, moved as chunks of 1 KB (64 cells of 16 bytes): one chunk is one
+// wavefront-wide direct load.
 template <int TILE>
-struct Lds {
-    static constexpr int RC_PITCH = TILE + 8;
-    static constexpr int KC_SIZE = TILE * KC_PITCH;
-    static constexpr int RC_SIZE = BK * RC_PITCH;
-    static constexpr int SIZE = KC_SIZE > RC_SIZE ? KC_SIZE : RC_SIZE;  // floats per operand slab
+struct Dma {
+    static constexpr int SLAB = TILE * BK;              // floats per operand slab
+    static constexpr int CHUNKS = TILE * BK / 256;
+    static constexpr int NV = CHUNKS / 4;               // loads per wavefront, operand and slab
+    static constexpr int RPC = 64 / KQ;                 // rows of a KC slab per chunk
+    static constexpr int CPR = TILE / 4;                // cells per k-line of an RC slab
+    static constexpr int LPC = 64 / CPR;                // k-lines of an RC slab per chunk
+    static_assert(CHUNKS % 4 == 0 && NV >= 1, "chunks must divide over the four wavefronts");
 };
 
-// ---- global -> registers ------------------------------------------------------------
-// A slab holds TILE*BK floats = TILE*KQ float4; each thread carries TILE*KQ/256 of them.  Their byte offsets
-// inside the block, without the part that moves with the slab, are fixed for the whole tile: computed once
-// (32 bits suffice: a block has at most 16384^2 * 4 bytes), so that every load is "uniform base of the slab +
-// per-thread offset" and the address arithmetic stays out of the K loop.
+// KC: cell q of row r sits at q ^ kc_swizzle(r): sixteen consecutive rows at one q - what sixteen lanes of a
+// 16-byte operand read touch - fall into sixteen different 16-byte bank groups.
+__device__ __forceinline__ int kc_swizzle(int row) { return KQ == 8 ? (row >> 1) & 7 : (row >> 2) & 3; }
+// RC: float r of k-line k sits at r ^ rc_swizzle(k): the two lines k and k + 4 that the lane halves of a
+// 4-byte operand read touch fall into different halves of the 64 banks.
+__device__ __forceinline__ int rc_swizzle(int k) { return 32 * ((k >> 2) & 1); }
+
+// Byte offsets, inside the block and without the part that moves with the slab, of the cells one lane
+// fetches: fixed for the whole tile, computed once (32 bits suffice: a block has at most 16384^2 * 4 bytes),
+// so that every load is "uniform base of the slab + per-lane offset".
 template <int TILE, bool KC>
-__device__ __forceinline__ void slab_offsets(int ld, int row0, unsigned (&off)[TILE * KQ / NTHREADS]) {
-    constexpr int NV = TILE * KQ / NTHREADS;
-    const int t = threadIdx.x;
+__device__ __forceinline__ void dma_offsets(int ld, int row0, int wave, int lane, unsigned (&off)[Dma<TILE>::NV]) {
+    typedef Dma<TILE> D;
 #pragma unroll
-    for (int u = 0; u < NV; ++u) {
-        const int f = t + NTHREADS * u;
-        if (KC) {   // element (row, k) at base[row*ld + k]
-            const int row = f / KQ, kq = f % KQ;
-            off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 4u * kq) * 4u;
-        } else {    // element (row, k) at base[k*ld + row]
-            constexpr int QPR = TILE / 4;   // float4 per k-line
-            const int k = f / QPR, rq = f % QPR;
-            off[u] = ((unsigned)k * (unsigned)ld + row0 + 4u * rq) * 4u;
+    for (int u = 0; u < D::NV; ++u) {
+        const int ch = wave + 4 * u;
+        if (KC) {   // element (row, k) at base[row*ld + k]: a chunk is RPC rows
+            const int row = D::RPC * ch + lane / KQ;
+            const int q = (lane % KQ) ^ kc_swizzle(row);
+            off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 4u * q) * 4u;
+        } else {    // element (row, k) at base[k*ld + row]: a chunk is LPC k-lines
+            const int k = D::LPC * ch + lane / D::CPR;
+            const int r = (4 * (lane % D::CPR)) ^ rc_swizzle(k);
+            off[u] = ((unsigned)k * (unsigned)ld + row0 + r) * 4u;
         }
     }
 }
@@ -80,50 +107,46 @@ __device__ __forceinline__ size_t slab_base(int ld, int k0) {
     return KC ? (size_t)k0 * 4 : (size_t)k0 * ld * 4;
 }
 
+// request one operand slab: global memory -> LDS.  `wave` must be uniform.
 template <int TILE>
-__device__ __forceinline__ void load_slab(const char* __restrict__ slab, const unsigned (&off)[TILE * KQ / NTHREADS],
-                                          v4f (&r)[TILE * KQ / NTHREADS]) {
+__device__ __forceinline__ void dma_load(const char* __restrict__ slab, const unsigned (&off)[Dma<TILE>::NV],
+                                         float* __restrict__ dst, int wave) {
 #pragma unroll
-    for (int u = 0; u < TILE * KQ / NTHREADS; ++u) r[u] = *reinterpret_cast<const v4f*>(slab + off[u]);
-}
-
-// ---- registers -> LDS ----------------------------------------------------------------
-template <int TILE, bool KC>
-__device__ __forceinline__ void store_slab(float* __restrict__ s, const v4f (&r)[TILE * KQ / NTHREADS]) {
-    constexpr int NV = TILE * KQ / NTHREADS;
-    const int t = threadIdx.x;
-#pragma unroll
-    for (int u = 0; u < NV; ++u) {
-        const int f = t + NTHREADS * u;
-        if (KC) {
-            const int row = f / KQ, kq = f % KQ;
-            *reinterpret_cast<v4f*>(s + row * KC_PITCH + 4 * kq) = r[u];
-        } else {
-            constexpr int QPR = TILE / 4;
-            const int k = f / QPR, rq = f % QPR;
-            *reinterpret_cast<v4f*>(s + k * Lds<TILE>::RC_PITCH + 4 * rq) = r[u];
-        }
-    }
+    for (int u = 0; u < Dma<TILE>::NV; ++u)
+        direct_load16(slab, off[u], reinterpret_cast<char*>(dst) + (wave + 4 * u) * 1024);
 }
 
 // ---- LDS -> MFMA operand fragments for one chunk of 8 k --------------------------------
-// Returns, for the 32-row sub-tile starting at r0, the four operand values this lane
-// feeds to MFMA steps s = 0..3 of chunk c: element (r0 + lane%32, 8c + 4*(lane/32) + s).
-template <int TILE, bool KC>
-__device__ __forceinline__ v4f read_frag(const float* __restrict__ s, int r0, int c, int lane) {
-    const int rr = r0 + (lane & 31), kh = 8 * c + 4 * (lane >> 5);
-    if (KC) {
-        return *reinterpret_cast<const v4f*>(s + rr * KC_PITCH + kh);
-    } else {
-        constexpr int P = Lds<TILE>::RC_PITCH;
+// For the MT sub-tiles of 32 rows of a wavefront, the first at r0: the four operand values a lane feeds to
+// MFMA steps s = 0..3 of chunk c are the elements (r0 + 32 i + lane%32, 8c + 4*(lane/32) + s).  Per-lane float
+// offsets are set up once; KC: one per chunk (the swizzle depends on it), the sub-tile adds a constant;
+// RC: one per sub-tile (the swizzle flips bit 5 of the row), the chunk and the step add constants.
+template <int TILE, bool KC, int MT>
+struct Frag {
+    int fo[KC ? BK / 8 : MT];
+    __device__ __forceinline__ void init(int r0, int lane) {
+        if (KC) {
+            const int rr = r0 + (lane & 31);
+#pragma unroll
+            for (int c = 0; c < BK / 8; ++c) fo[c] = rr * BK + 4 * ((2 * c + (lane >> 5)) ^ kc_swizzle(rr));
+        } else {
+            // k = 8c + 4 (lane/32) + s: bit 2 of k is lane/32, whatever c and s
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                fo[i] = 4 * (lane >> 5) * TILE + ((r0 + 32 * i + (lane & 31)) ^ (32 * (lane >> 5)));
+        }
+    }
+    __device__ __forceinline__ v4f read(const float* __restrict__ s, int i, int c) const {
+        if (KC) return *reinterpret_cast<const v4f*>(s + fo[c] + i * 32 * BK);      // row + 32: same swizzle
+        const float* p = s + fo[i] + 8 * c * TILE;
         v4f v;
-        v[0] = s[(kh + 0) * P + rr];
-        v[1] = s[(kh + 1) * P + rr];
-        v[2] = s[(kh + 2) * P + rr];
-        v[3] = s[(kh + 3) * P + rr];
+        v[0] = p[0 * TILE];
+        v[1] = p[1 * TILE];
+        v[2] = p[2 * TILE];
+        v[3] = p[3 * TILE];
         return v;
     }
-}
+};
 
 // TILE x TILE output tile per workgroup; each of the 4 waves owns (TILE/2) x (TILE/2),
 // i.e. MT x MT MFMA tiles of 32 x 32 with MT = TILE/64.
@@ -135,10 +158,12 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     constexpr int MT = TILE / 64;
     constexpr bool A_KC = !TA;   // op(A)(i,k): k contiguous unless transposed
     constexpr bool B_KC = TB;    // op(B)(k,j): j contiguous unless transposed
-    constexpr int NV = TILE * KQ / NTHREADS;
-    constexpr int SLAB = Lds<TILE>::SIZE;
+    constexpr int NV = Dma<TILE>::NV;
+    constexpr int SLAB = Dma<TILE>::SLAB;         // floats per operand slab; a stage is the A slab and the B slab
+    constexpr int STRIPS = 4 * 32 * (TILE / 2 + 4);                       // floats the epilogue strips need
+    constexpr int LDSF = 2 * 2 * SLAB > STRIPS ? 2 * 2 * SLAB : STRIPS;
 
-    __shared__ __attribute__((aligned(16))) float lds[2 * 2 * SLAB];
+    __shared__ __attribute__((aligned(1024))) float lds[LDSF];
 
     // ---- which tile am I (XCD-aware remap of the 1-D grid) ----
     const int64_t W = gridDim.x;
@@ -176,7 +201,7 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     const float* __restrict__ Bb = static_cast<const float*>(P.B) + (size_t)blk * Kd * Nd;
     const int lda = TA ? Md : Kd, ldb = TB ? Kd : Nd;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
 
     v16f acc[MT][MT];
@@ -187,49 +212,71 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    v4f ra[NV], rb[NV];
     unsigned offa[NV], offb[NV];
-    slab_offsets<TILE, A_KC>(lda, row0, offa);
-    slab_offsets<TILE, B_KC>(ldb, col0, offb);
-    const char* __restrict__ Ac = reinterpret_cast<const char*>(Ab);
-    const char* __restrict__ Bc = reinterpret_cast<const char*>(Bb);
-    load_slab<TILE>(Ac, offa, ra);
-    load_slab<TILE>(Bc, offb, rb);
-    store_slab<TILE, A_KC>(lds, ra);
-    store_slab<TILE, B_KC>(lds + SLAB, rb);
-    __syncthreads();
-
+    dma_offsets<TILE, A_KC>(lda, row0, wave, lane, offa);
+    dma_offsets<TILE, B_KC>(ldb, col0, wave, lane, offb);
+    Frag<TILE, A_KC, MT> fra;
+    Frag<TILE, B_KC, MT> frb;
+    fra.init(wm, lane);
+    frb.init(wn, lane);
+    // uniform base addresses of the next slab to request, stepped: the K loop holds no address set-up
+    const char* pa = reinterpret_cast<const char*>(Ab);
+    const char* pb = reinterpret_cast<const char*>(Bb);
+    const size_t stepa = slab_base<A_KC>(lda, BK), stepb = slab_base<B_KC>(ldb, BK);
+    auto load_next = [&](float* stage) {
+        dma_load<TILE>(pa, offa, stage, wave);
+        dma_load<TILE>(pb, offb, stage + SLAB, wave);
+        pa += stepa;
+        pb += stepb;
+    };
+    // Fragments of chunk c live in register set c % 2; those of chunk c + 1 are requested before the MFMAs of
+    // chunk c issue.
+    constexpr int CH = BK / 8;
+    v4f fa[2][MT], fb[2][MT];
+    auto frags = [&](const float* sa, auto C) {
+        constexpr int c = decltype(C)::value, b = c & 1;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) fa[b][i] = fra.read(sa, i, c);
+#pragma unroll
+        for (int j = 0; j < MT; ++j) fb[b][j] = frb.read(sa + SLAB, j, c);
+    };
+    auto mfmas = [&](auto C) {
+        constexpr int b = decltype(C)::value & 1;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < MT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[b][i][s], fb[b][j][s], acc[i][j], 0, 0, 0);
+    };
+    // Two stages.  The barrier that opens slab h + 1 sits before the LAST chunk of slab h: by then a wavefront
+    // holds all its fragments of slab h in registers, so the stage of slab h is free and slab h + 2 is requested
+    // into it right after the barrier, and the first fragments of slab h + 1 are requested right after the
+    // barrier while the MFMAs of the last chunk of slab h still run.  Before the barrier a wavefront waits until
+    // its own loads of slab h + 1 have landed and its fragment reads are complete.
     const int KT = Kd / BK;
-    for (int kt = 0; kt < KT; ++kt) {
-        const float* sa = lds + (kt & 1) * 2 * SLAB;
-        const float* sb = sa + SLAB;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            load_slab<TILE>(Ac + slab_base<A_KC>(lda, (kt + 1) * BK), offa, ra);
-            load_slab<TILE>(Bc + slab_base<B_KC>(ldb, (kt + 1) * BK), offb, rb);
+    load_next(lds);
+    wait_vm_lgkm<0>();
+    __builtin_amdgcn_s_barrier();
+    if (1 < KT) load_next(lds + 2 * SLAB);
+    frags(lds, std::integral_constant<int, 0>{});
+    for (int h = 0; h < KT; ++h) {
+        float* cur = lds + (h & 1) * 2 * SLAB;
+        float* nxt = lds + ((h + 1) & 1) * 2 * SLAB;
+        fstatic_for<CH - 1>([&](auto C) {
+            frags(cur, std::integral_constant<int, decltype(C)::value + 1>{});
+            mfmas(C);
+        });
+        if (h + 1 < KT) {
+            wait_vm_lgkm<0>();
+            __builtin_amdgcn_s_barrier();
+            if (h + 2 < KT) load_next(cur);
+            frags(nxt, std::integral_constant<int, 0>{});
         }
-#pragma unroll
-        for (int c = 0; c < BK / 8; ++c) {
-            v4f fa[MT], fb[MT];
-#pragma unroll
-            for (int i = 0; i < MT; ++i) fa[i] = read_frag<TILE, A_KC>(sa, wm + 32 * i, c, lane);
-#pragma unroll
-            for (int j = 0; j < MT; ++j) fb[j] = read_frag<TILE, B_KC>(sb, wn + 32 * j, c, lane);
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int i = 0; i < MT; ++i)
-#pragma unroll
-                    for (int j = 0; j < MT; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][s], fb[j][s], acc[i][j], 0, 0, 0);
-        }
-        if (more) {
-            float* da = lds + ((kt + 1) & 1) * 2 * SLAB;
-            store_slab<TILE, A_KC>(da, ra);
-            store_slab<TILE, B_KC>(da + SLAB, rb);
-        }
-        __syncthreads();
+        mfmas(std::integral_constant<int, CH - 1>{});
     }
+    __syncthreads();                    // every wavefront has left the last slab: LDS is free for the epilogue
 
     // ---- epilogue: C = mult * (alpha*acc + beta*D + gamma*I), staged through LDS ----
     // The MFMA leaves a lane with one column and scattered rows (register r of lane l holds row
@@ -251,7 +298,7 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     constexpr int SP = WT + 4;                    // strip pitch in floats
     constexpr int QPR = WT / 4;                   // quads per strip row
     constexpr int RPI = 64 / QPR;                 // strip rows one pass of the wavefront covers
-    static_assert(4 * 32 * SP <= 2 * 2 * SLAB, "strips must fit the operand buffers");
+    static_assert(4 * 32 * SP <= LDSF, "strips must fit the LDS array");
     float* strip = lds + wave * 32 * SP;
     bool bad = false;
 #pragma unroll

@@ -22,6 +22,7 @@
 //       (cells swizzled inside the line) and the operand is assembled by two transposing reads
 //       (ds_read_b64_tr_b16: sixteen lanes read a 4 x 16 patch of 16-bit values and each gets
 //       one column of it).
+#include "direct_load.h"
 #include "kernels.h"
 
 #include <type_traits>
@@ -152,22 +153,12 @@ __device__ __forceinline__ size_t hslab_base(int ld, int k0) {
 }
 
 // request one operand slab: global memory -> LDS, no registers in between.  `wave` must be uniform.
-// Written as assembly on purpose: the compiler tracks direct loads it knows of and, where control flow
-// merges, makes LDS reads of OTHER stages wait for all of them (vmcnt(0) right after a request = the whole
-// memory latency exposed).  Here every wait is explicit instead: wait_vm_lgkm before the barrier that opens a
-// slab.  The "memory" clobber keeps LDS accesses on their side of the request.
 template <int TILE>
 __device__ __forceinline__ void hdma_load(const char* __restrict__ slab, const unsigned (&off)[HDma<TILE>::NV],
                                           char* __restrict__ dst, int wave) {
     typedef HDma<TILE> D;
 #pragma unroll
-    for (int u = 0; u < D::NV; ++u) {
-        const unsigned lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(dst + (wave + D::NW * u) * 1024);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :
-                     : "s"(lds), "v"(off[u]), "s"(slab)
-                     : "memory", "m0");
-    }
+    for (int u = 0; u < D::NV; ++u) direct_load16(slab, off[u], dst + (wave + D::NW * u) * 1024);
 }
 
 // Per-lane LDS byte offsets of the operand fragments of a wavefront's MT sub-tiles of 32 rows, the first at
@@ -208,14 +199,6 @@ struct HFrag {
         return x.u;
     }
 };
-
-// s_waitcnt: at most N vector-memory operations of this wavefront still in flight, and none of its LDS
-// operations (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at "do not wait", lgkmcnt 11:8)
-template <int N>
-__device__ __forceinline__ void wait_vm_lgkm() {
-    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));
-}
 
 template <typename H, int TILE, bool TA, bool TB>
 __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_kernel(GemmLaunch g) {
