@@ -57,7 +57,18 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #endif
 constexpr int BK = DASH_BK;        // K slab (16 or 32)
 constexpr int KQ = BK / 4;         // 16-byte cells per row of a k-contiguous slab
-constexpr int NTHREADS = 256;
+// workgroup shape per tile edge: WC x WC wavefronts, each computing a WT x WT part of the tile
+//   TILE  64: 2 x 2 wavefronts of 32 x 32;  TILE 128: 2 x 2 wavefronts of 64 x 64 (256 threads);
+//   (TILE 256 = 4 x 4 wavefronts of 64 x 64, 1024 threads, one workgroup per CU, also builds from this template: half the bytes
+//   through the load path per flop; measured 2-3 % faster on launches of 128 blocks of 1024 and no faster on 32,
+//   not used)
+template <int TILE>
+struct Cfg {
+    static constexpr int WT = TILE == 64 ? 32 : 64;
+    static constexpr int WC = TILE / WT;
+    static constexpr int NW = WC * WC;
+    static constexpr int NT = 64 * NW;
+};
 constexpr int NUM_XCD = 8;
 
 // An operand slab is TILE x BK floats, moved as chunks of 1 KB (64 cells of 16 bytes): one chunk is one
@@ -66,11 +77,12 @@ template <int TILE>
 struct Dma {
     static constexpr int SLAB = TILE * BK;              // floats per operand slab
     static constexpr int CHUNKS = TILE * BK / 256;
-    static constexpr int NV = CHUNKS / 4;               // loads per wavefront, operand and slab
+    static constexpr int NW = Cfg<TILE>::NW;
+    static constexpr int NV = CHUNKS / NW;              // loads per wavefront, operand and slab
     static constexpr int RPC = 64 / KQ;                 // rows of a KC slab per chunk
     static constexpr int CPR = TILE / 4;                // cells per k-line of an RC slab
     static constexpr int LPC = 64 / CPR;                // k-lines of an RC slab per chunk
-    static_assert(CHUNKS % 4 == 0 && NV >= 1, "chunks must divide over the four wavefronts");
+    static_assert(CHUNKS % NW == 0 && NV >= 1, "chunks must divide over the wavefronts");
 };
 
 // KC: cell q of row r sits at q ^ kc_swizzle(r): sixteen consecutive rows at one q - what sixteen lanes of a
@@ -88,7 +100,7 @@ __device__ __forceinline__ void dma_offsets(int ld, int row0, int wave, int lane
     typedef Dma<TILE> D;
 #pragma unroll
     for (int u = 0; u < D::NV; ++u) {
-        const int ch = wave + 4 * u;
+        const int ch = wave + D::NW * u;
         if (KC) {   // element (row, k) at base[row*ld + k]: a chunk is RPC rows
             const int row = D::RPC * ch + lane / KQ;
             const int q = (lane % KQ) ^ kc_swizzle(row);
@@ -113,7 +125,7 @@ __device__ __forceinline__ void dma_load(const char* __restrict__ slab, const un
                                          float* __restrict__ dst, int wave) {
 #pragma unroll
     for (int u = 0; u < Dma<TILE>::NV; ++u)
-        direct_load16(slab, off[u], reinterpret_cast<char*>(dst) + (wave + 4 * u) * 1024);
+        direct_load16(slab, off[u], reinterpret_cast<char*>(dst) + (wave + Dma<TILE>::NW * u) * 1024);
 }
 
 // ---- LDS -> MFMA operand fragments for one chunk of 8 k --------------------------------
@@ -148,19 +160,18 @@ struct Frag {
     }
 };
 
-// TILE x TILE output tile per workgroup; each of the 4 waves owns (TILE/2) x (TILE/2),
-// i.e. MT x MT MFMA tiles of 32 x 32 with MT = TILE/64.
+// TILE x TILE output tile per workgroup; each wavefront owns WT x WT of it, i.e. MT x MT MFMA tiles of 32 x 32.
 template <int TILE, bool TA, bool TB, bool RECT = false>
 #ifndef DASH_MIN_WG
 #define DASH_MIN_WG 2
 #endif
-__global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLaunch g) {
-    constexpr int MT = TILE / 64;
+__global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void gemm_f32_kernel(GemmLaunch g) {
+    constexpr int MT = Cfg<TILE>::WT / 32;
     constexpr bool A_KC = !TA;   // op(A)(i,k): k contiguous unless transposed
     constexpr bool B_KC = TB;    // op(B)(k,j): j contiguous unless transposed
     constexpr int NV = Dma<TILE>::NV;
     constexpr int SLAB = Dma<TILE>::SLAB;         // floats per operand slab; a stage is the A slab and the B slab
-    constexpr int STRIPS = 4 * 32 * (TILE / 2 + 4);                       // floats the epilogue strips need
+    constexpr int STRIPS = Cfg<TILE>::NW * 32 * (Cfg<TILE>::WT + 4);      // floats the epilogue strips need
     constexpr int LDSF = 2 * 2 * SLAB > STRIPS ? 2 * 2 * SLAB : STRIPS;
 
     __shared__ __attribute__((aligned(1024))) float lds[LDSF];
@@ -202,7 +213,7 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     const int lda = TA ? Md : Kd, ldb = TB ? Kd : Nd;
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = (wave >> 1) * (TILE / 2), wn = (wave & 1) * (TILE / 2);
+    const int wm = (wave / Cfg<TILE>::WC) * Cfg<TILE>::WT, wn = (wave % Cfg<TILE>::WC) * Cfg<TILE>::WT;
 
     v16f acc[MT][MT];
 #pragma unroll
@@ -294,11 +305,11 @@ __global__ __launch_bounds__(NTHREADS, DASH_MIN_WG) void gemm_f32_kernel(GemmLau
     const float a2 = P.a2, g2 = P.g2;
     // symmetric mode: an off-diagonal tile (ti < tj) is also written transposed to (tj, ti)
     const bool mirror = g.sym && ti != tj;
-    constexpr int WT = TILE / 2;                  // columns of a wavefront's strip
+    constexpr int WT = Cfg<TILE>::WT;             // columns of a wavefront's strip
     constexpr int SP = WT + 4;                    // strip pitch in floats
     constexpr int QPR = WT / 4;                   // quads per strip row
     constexpr int RPI = 64 / QPR;                 // strip rows one pass of the wavefront covers
-    static_assert(4 * 32 * SP <= LDSF, "strips must fit the LDS array");
+    static_assert(Cfg<TILE>::NW * 32 * SP <= LDSF, "strips must fit the LDS array");
     float* strip = lds + wave * 32 * SP;
     bool bad = false;
 #pragma unroll
@@ -366,7 +377,7 @@ static hipError_t launch_tile(const GemmLaunch& g, hipStream_t stream) {
     if (W > 0x7fffffffLL) return hipErrorInvalidValue;
     // both products of a launch must use the same transpose flags (one kernel instance)
     const int ta = g.prob[0].transA, tb = g.prob[0].transB;
-    dim3 grid((unsigned)W), block(NTHREADS);
+    dim3 grid((unsigned)W), block(Cfg<TILE>::NT);
     if (g.M || g.N || g.K) {
         if (!ta && !tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, false, true>), grid, block, 0, stream, g);
         else if (!ta && tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, true, true>), grid, block, 0, stream, g);
