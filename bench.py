@@ -327,6 +327,10 @@ def main():
                     algorithmic_bytes=12.0 * B * B * st["variant_block_products"][0] / max(launches, 1),
                     launches_per_step=launches / args.steps,
                     mean_launch_ms=mm_ms / max(launches, 1),
+                    launch_note="a launch whose last round of 128-tile workgroups would be under half full (the "
+                                "36-tile symmetric residual on 32 blocks) is issued as two kernels: the blocks that "
+                                "fill whole rounds with this kernel, the remaining blocks with its <64, ...> "
+                                "instance; the HIP events bracket both",
                     matmul_share_of_step=mm_ms / (dt * 1e3))
 
     # the paper's own matmul count for the root (3k-2 per call, two calls) prices the

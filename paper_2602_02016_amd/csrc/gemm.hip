@@ -189,7 +189,7 @@ __global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void 
     const int Md = RECT && g.M ? g.M : g.B, Nd = RECT && g.N ? g.N : Md, Kd = RECT && g.K ? g.K : Md;
     const int tiles = Md / TILE, tiles_n = Nd / TILE;
     const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles_n;
-    const int64_t blk = lid / ((int64_t)g.nprob * T);
+    const int64_t blk = g.blk0 + lid / ((int64_t)g.nprob * T);
     const int r1 = (int)(lid % ((int64_t)g.nprob * T));
     const int pi = r1 / T;
     const int tile = r1 % T;
@@ -401,7 +401,17 @@ hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
     if (g.nprob == 2 && (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
         return hipErrorInvalidValue;
     if (g.half != HALF_NONE) return launch_gemm_half(g, stream);
-    return gemm_tile_edge(g) == 128 ? launch_tile<128>(g, stream) : launch_tile<64>(g, stream);
+    if (gemm_tile_edge(g) != 128) return launch_tile<64>(g, stream);
+    const int64_t na = gemm_split_blocks(g);
+    if (na == g.nblocks) return launch_tile<128>(g, stream);
+    // whole rounds with 128 tiles, then the last blocks with 64 tiles (same result bit for bit: an output
+    // element is accumulated over k in the same order whatever the tile)
+    GemmLaunch a = g, b = g;
+    a.nblocks = na;
+    b.blk0 = g.blk0 + na;
+    b.nblocks = g.nblocks - na;
+    const hipError_t e = launch_tile<128>(a, stream);
+    return e != hipSuccess ? e : launch_tile<64>(b, stream);
 }
 
 // 128-wide tiles when they still give the chip enough workgroups, else 64-wide
@@ -413,11 +423,37 @@ int gemm_tile_edge(const GemmLaunch& g) {
     return big ? 128 : 64;
 }
 
-// fraction of the B x B output tiles a launch computes (1, or (t+1)/(2t) in symmetric mode)
+// A launch of 128 tiles runs in rounds of RESIDENT workgroups (four per CU).  When the last round would be
+// less than half full - every CU then ends with one lonely workgroup, or none - the blocks that fill whole
+// rounds keep the 128 tiles and the remaining blocks are computed with 64 tiles, which spread over all CUs.
+// Returns the number of blocks of the first part (nblocks: no split).
+int64_t gemm_split_blocks(const GemmLaunch& g) {
+    constexpr int64_t RESIDENT = 4 * 256;
+    if (g.half != HALF_NONE || gemm_tile_edge(g) != 128) return g.nblocks;
+    const int64_t tm = (g.M ? g.M : g.B) / 128, tn = (g.N ? g.N : g.B) / 128;
+    const int64_t per_block = g.nprob * (g.sym ? tm * (tm + 1) / 2 : tm * tn);
+    const int64_t W = g.nblocks * per_block;
+    const int64_t full = W / RESIDENT, rem = W % RESIDENT;
+    if (full < 1 || rem == 0 || rem > RESIDENT / 2) return g.nblocks;
+    const int64_t na = full * RESIDENT / per_block;
+    return na >= 1 && na < g.nblocks ? na : g.nblocks;
+}
+
+// fraction of the B x B output tiles a launch computes (1, or (t+1)/(2t) in symmetric mode, t = tiles per edge)
 double gemm_tile_fraction(const GemmLaunch& g) {
     if (!g.sym) return 1.0;
-    const int t = (g.M ? g.M : g.B) / (g.half != HALF_NONE ? gemm_half_tile_edge(g) : gemm_tile_edge(g));
-    return (double)(t + 1) / (2.0 * t);
+    const int Md = g.M ? g.M : g.B;
+    if (g.half != HALF_NONE) {
+        const int t = Md / gemm_half_tile_edge(g);
+        return (double)(t + 1) / (2.0 * t);
+    }
+    const int t = Md / gemm_tile_edge(g);
+    const double f = (double)(t + 1) / (2.0 * t);
+    const int64_t na = gemm_split_blocks(g);
+    if (na == g.nblocks) return f;
+    const int t64 = Md / 64;
+    const double f64 = (double)(t64 + 1) / (2.0 * t64);
+    return (f * (double)na + f64 * (double)(g.nblocks - na)) / (double)g.nblocks;
 }
 
 }  // namespace dash

@@ -236,7 +236,7 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     const int B = g.B;
     const int tiles = B / TILE;
     const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles;
-    const int64_t blk = lid / ((int64_t)g.nprob * T);
+    const int64_t blk = g.blk0 + lid / ((int64_t)g.nprob * T);
     const int r1 = (int)(lid % ((int64_t)g.nprob * T));
     const int pi = r1 / T;
     const int tile = r1 % T;
