@@ -51,6 +51,24 @@ def test_accumulate_is_bit_identical(dashes, N, B):
     assert ff == 2 * N * 2.0 * B ** 3 and fs < ff
 
 
+def test_split_launch_equals_its_parts(dashes):
+    """32 blocks of 1024 in symmetric mode are 1152 workgroups of 128 tiles: the library computes the
+    blocks that fill whole rounds (28) with 128 tiles and the last 4 with 64 tiles.  Every block must
+    come out bit for bit as when it is computed in a launch that is not split."""
+    import torch
+    sym, _ = dashes
+    N, B = 32, 1024
+    G = _to_gpu(workloads.gradient_stack(N, B, 85))
+    S = torch.zeros(2 * N, B, B, device="cuda")
+    sym.accumulate_factors(G, S[:N], S[N:], 0.95)
+    for lo, hi in ((0, 28), (28, 32), (5, 9)):
+        n = hi - lo
+        P = torch.zeros(2 * n, B, B, device="cuda")
+        sym.accumulate_factors(G[lo:hi].contiguous(), P[:n], P[n:], 0.95)
+        torch.cuda.synchronize()
+        assert torch.equal(P[:n], S[lo:hi]) and torch.equal(P[n:], S[N + lo:N + hi])
+
+
 @pytest.mark.parametrize("p", [2, 4])
 @pytest.mark.parametrize("N,B,lo", [(4, 128, -3.0), (3, 256, -1.0), (2, 512, -2.0), (9, 1024, -1.0)])
 def test_ndb_both_modes_meet_the_same_bar(dashes, N, B, lo, p):
