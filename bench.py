@@ -187,6 +187,9 @@ def main():
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc: one device copy of known size, then three launches of the "
                          "matmul kernel on the workload's 32-block stack; prints nothing else")
+    ap.add_argument("--pmc-probe-16bit", action="store_true",
+                    help="as --pmc-probe with the 16-bit kernel: a device copy of known size, then three launches "
+                         "of the bf16-operand matmul on 256 blocks (fp32 result)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline step: inverse-root throughput on the shapes of the other "
                          "configurations, all methods and precisions (table on stderr, one JSON line)")
@@ -219,6 +222,25 @@ def main():
     if args.sweep or args.sweep_16bit:
         print(json.dumps({"sweep": sweep(dash, only_16bit=args.sweep_16bit), "unit": "blocks/s", "n_gpus": 1, "data": "synthetic",
                           "symmetric_products": not args.full_products}))
+        return
+
+    if args.pmc_probe_16bit:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1)
+        nb = 256
+        A = torch.randn(nb, B, B, device=dev, generator=gen)
+        Bm = torch.randn(nb, B, B, device=dev, generator=gen)
+        Cm = torch.empty_like(A)
+        dash.gemm_batched(A[:8], Bm[:8], Cm[:8], precision="bf16")      # sizes the workspace
+        torch.cuda.synchronize()
+        Cm[:32].copy_(A[:32])                   # reference: reads 128 MiB, writes 128 MiB
+        torch.cuda.synchronize()
+        for _ in range(3):
+            # casts the operands to bf16 (elementwise kernel), then the 16-bit matmul kernel:
+            # algorithmic reads 2 x 512 MiB of bf16, writes 1 GiB of fp32
+            dash.gemm_batched(A, Bm, Cm, precision="bf16")
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe_16bit": "copy of %d bytes then 3 bf16 matmul launches on %d blocks" % (32 * B * B * 4, nb)}))
         return
 
     if args.pmc_probe:
