@@ -346,13 +346,12 @@ __global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void 
             if (mirror) *reinterpret_cast<v4f*>(strip + rl * SP + c) = v;      // final values for phase C
         }
         __syncthreads();
-        // phase C (mirrored tiles only): back in the MFMA layout a lane holds four consecutive rows of
-        // one column = four consecutive elements of a row of the transposed tile: one 16-byte store
+        // phase C (mirrored tiles only): a column of the strip is 32 consecutive elements of a row of the
+        // transposed tile = one 128-byte line; eight lanes write it, four rows of the column each
         if (mirror) {
 #pragma unroll 2
-            for (int jq = 0; jq < MT * 4; ++jq) {
-                const int j = jq >> 2, q = jq & 3;
-                const int rl = 8 * q + 4 * (lane >> 5), cl = 32 * j + (lane & 31);
+            for (int t = 0; t < WT / 8; ++t) {
+                const int cl = (lane >> 3) + 8 * t, rl = 4 * (lane & 7);
                 v4f v, v2;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
