@@ -32,6 +32,7 @@
 // A and B panels) meet in one XCD's L2.
 #include "direct_load.h"
 #include "kernels.h"
+#include "lds_layout.h"
 
 #include <type_traits>
 #include <utility>
@@ -56,7 +57,6 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #define DASH_BK 16
 #endif
 constexpr int BK = DASH_BK;        // K slab (16 or 32)
-constexpr int KQ = BK / 4;         // 16-byte cells per row of a k-contiguous slab
 // workgroup shape per tile edge: WC x WC wavefronts, each computing a WT x WT part of the tile
 //   TILE  64: 2 x 2 wavefronts of 32 x 32;  TILE 128: 2 x 2 wavefronts of 64 x 64 (256 threads);
 //   (TILE 256 = 4 x 4 wavefronts of 64 x 64, 1024 threads, one workgroup per CU, also builds from this template: half the bytes
@@ -71,46 +71,18 @@ struct Cfg {
 };
 constexpr int NUM_XCD = 8;
 
-// An operand slab is TILE x BK floats, moved as chunks of 1 KB (64 cells of 16 bytes): one chunk is one
-// wavefront-wide direct load.
+// LDS layout of the operand slabs (lds_layout.h): chunks of 1 KB, one per wavefront-wide direct load; KC (k
+// contiguous in memory) and RC (row contiguous) with their swizzles.
 template <int TILE>
-struct Dma {
-    static constexpr int SLAB = TILE * BK;              // floats per operand slab
-    static constexpr int CHUNKS = TILE * BK / 256;
-    static constexpr int NW = Cfg<TILE>::NW;
-    static constexpr int NV = CHUNKS / NW;              // loads per wavefront, operand and slab
-    static constexpr int RPC = 64 / KQ;                 // rows of a KC slab per chunk
-    static constexpr int CPR = TILE / 4;                // cells per k-line of an RC slab
-    static constexpr int LPC = 64 / CPR;                // k-lines of an RC slab per chunk
-    static_assert(CHUNKS % NW == 0 && NV >= 1, "chunks must divide over the wavefronts");
-};
-
-// KC: cell q of row r sits at q ^ kc_swizzle(r): sixteen consecutive rows at one q - what sixteen lanes of a
-// 16-byte operand read touch - fall into sixteen different 16-byte bank groups.
-__device__ __forceinline__ int kc_swizzle(int row) { return KQ == 8 ? (row >> 1) & 7 : (row >> 2) & 3; }
-// RC: float r of k-line k sits at r ^ rc_swizzle(k): the two lines k and k + 4 that the lane halves of a
-// 4-byte operand read touch fall into different halves of the 64 banks.
-__device__ __forceinline__ int rc_swizzle(int k) { return 32 * ((k >> 2) & 1); }
+using Dma = layout::F32<TILE, BK, Cfg<TILE>::NW>;
 
 // Byte offsets, inside the block and without the part that moves with the slab, of the cells one lane
-// fetches: fixed for the whole tile, computed once (32 bits suffice: a block has at most 16384^2 * 4 bytes),
-// so that every load is "uniform base of the slab + per-lane offset".
+// fetches: fixed for the whole tile, computed once, so that every load is "uniform base of the slab + per-lane
+// offset".
 template <int TILE, bool KC>
 __device__ __forceinline__ void dma_offsets(int ld, int row0, int wave, int lane, unsigned (&off)[Dma<TILE>::NV]) {
-    typedef Dma<TILE> D;
 #pragma unroll
-    for (int u = 0; u < D::NV; ++u) {
-        const int ch = wave + D::NW * u;
-        if (KC) {   // element (row, k) at base[row*ld + k]: a chunk is RPC rows
-            const int row = D::RPC * ch + lane / KQ;
-            const int q = (lane % KQ) ^ kc_swizzle(row);
-            off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 4u * q) * 4u;
-        } else {    // element (row, k) at base[k*ld + row]: a chunk is LPC k-lines
-            const int k = D::LPC * ch + lane / D::CPR;
-            const int r = (4 * (lane % D::CPR)) ^ rc_swizzle(k);
-            off[u] = ((unsigned)k * (unsigned)ld + row0 + r) * 4u;
-        }
-    }
+    for (int u = 0; u < Dma<TILE>::NV; ++u) off[u] = Dma<TILE>::load_offset(KC, ld, row0, wave, lane, u);
 }
 
 // uniform byte offset of the slab starting at k0
@@ -125,7 +97,7 @@ __device__ __forceinline__ void dma_load(const char* __restrict__ slab, const un
                                          float* __restrict__ dst, int wave) {
 #pragma unroll
     for (int u = 0; u < Dma<TILE>::NV; ++u)
-        direct_load16(slab, off[u], reinterpret_cast<char*>(dst) + (wave + Dma<TILE>::NW * u) * 1024);
+        direct_load16(slab, off[u], reinterpret_cast<char*>(dst) + Dma<TILE>::chunk(wave, u) * 1024);
 }
 
 // ---- LDS -> MFMA operand fragments for one chunk of 8 k --------------------------------
@@ -135,21 +107,19 @@ __device__ __forceinline__ void dma_load(const char* __restrict__ slab, const un
 // RC: one per sub-tile (the swizzle flips bit 5 of the row), the chunk and the step add constants.
 template <int TILE, bool KC, int MT>
 struct Frag {
+    typedef Dma<TILE> D;
     int fo[KC ? BK / 8 : MT];
     __device__ __forceinline__ void init(int r0, int lane) {
         if (KC) {
-            const int rr = r0 + (lane & 31);
 #pragma unroll
-            for (int c = 0; c < BK / 8; ++c) fo[c] = rr * BK + 4 * ((2 * c + (lane >> 5)) ^ kc_swizzle(rr));
+            for (int c = 0; c < BK / 8; ++c) fo[c] = D::frag_kc(r0, lane, c);
         } else {
-            // k = 8c + 4 (lane/32) + s: bit 2 of k is lane/32, whatever c and s
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
-                fo[i] = 4 * (lane >> 5) * TILE + ((r0 + 32 * i + (lane & 31)) ^ (32 * (lane >> 5)));
+            for (int i = 0; i < MT; ++i) fo[i] = D::frag_rc(r0, i, lane);
         }
     }
     __device__ __forceinline__ v4f read(const float* __restrict__ s, int i, int c) const {
-        if (KC) return *reinterpret_cast<const v4f*>(s + fo[c] + i * 32 * BK);      // row + 32: same swizzle
+        if (KC) return *reinterpret_cast<const v4f*>(s + fo[c] + i * D::KC_SUB);
         const float* p = s + fo[i] + 8 * c * TILE;
         v4f v;
         v[0] = p[0 * TILE];

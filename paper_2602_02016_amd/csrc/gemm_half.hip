@@ -24,6 +24,7 @@
 //       one column of it).
 #include "direct_load.h"
 #include "kernels.h"
+#include "lds_layout.h"
 
 #include <type_traits>
 #include <utility>
@@ -84,7 +85,7 @@ namespace {
 //   TILE 128: 2 x 2 wavefronts of 64 x 64   (256 threads, two workgroups per CU), slabs of 64, 2 stages
 //   TILE 256: 4 x 4 wavefronts of 64 x 64  (1024 threads, one workgroup per CU: the same four wavefronts
 //             per SIMD as two 128 tiles, but every operand panel fetched from L2 serves twice the flops),
-//             slabs of 32 in 5 stages = the 160 KB of the CU: the loads run two slabs of 64 ahead
+//             slabs of 64, 2 stages (slabs of 32 in rings of 3 to 5 stages build as well and measured slower)
 template <int TILE>
 struct HCfg {
     static constexpr int WT = TILE == 64 ? 32 : 64;
@@ -100,50 +101,18 @@ struct HCfg {
 };
 constexpr int HNUM_XCD = 8;
 
-// An operand slab is TILE x HBK elements, moved as chunks of 1 KB; one chunk is one wavefront-wide direct load.
+// LDS layout of the operand slabs (lds_layout.h): chunks of 1 KB, one per wavefront-wide direct load; KC (k
+// contiguous in memory) and KR (row contiguous) with their swizzles.
 template <int TILE>
-struct HDma {
-    static constexpr int HBK = HCfg<TILE>::HBK;
-    static constexpr int HKQ = HBK / 8;                 // 16-byte cells per row of a KC slab
-    static constexpr int RPC = 64 / HKQ;                // rows of a KC slab per chunk
-    static constexpr int NW = HCfg<TILE>::NT / 64;      // wavefronts of the workgroup
-    static constexpr int CHUNKS = TILE * HBK / 512;
-    static constexpr int NV = CHUNKS / NW;              // loads per wavefront, operand and slab: 2, 4, 1
-    static constexpr int CPR = TILE / 8;                // 16-byte cells per k-line of a KR slab
-    static constexpr int LPC = 64 / CPR;                // k-lines of a KR slab per chunk
-    static constexpr int SLAB = TILE * HBK * 2;         // bytes of one operand slab
-    static_assert(CHUNKS % NW == 0 && NV >= 1, "chunks must divide over the wavefronts");
-};
-
-// Swizzles (a direct load cannot pad rows, but every lane picks its own source cell):
-//   KC  cell q of row r sits at cell q ^ kc_swizzle(r) of the row: sixteen consecutive rows at one q - what
-//       sixteen lanes of an operand read touch - fall into sixteen different 16-byte bank groups;
-//   KR  cell c of k-line k sits at cell c ^ kr_swizzle(k) of the line: the four k-lines x four cells that
-//       thirty-two lanes of a transposing read touch fall into sixteen different bank groups.
-template <int TILE>
-__device__ __forceinline__ int kc_swizzle(int row) { return HDma<TILE>::HKQ == 8 ? (row >> 1) & 7 : (row >> 2) & 3; }
-template <int TILE>
-__device__ __forceinline__ int kr_swizzle(int k) { return HDma<TILE>::CPR >= 16 ? 4 * (k & 3) : 4 * ((k >> 1) & 1); }
+using HDma = layout::Half<TILE, HCfg<TILE>::HBK, HCfg<TILE>::NT / 64>;
 
 // Byte offsets, inside the block and without the part that moves with the slab, of the cells one lane
-// fetches: fixed for the whole tile, computed once (32 bits suffice: a block has at most 16384^2 * 2 bytes),
-// so that every load is "uniform base of the slab + per-lane offset".
+// fetches: fixed for the whole tile, computed once, so that every load is "uniform base of the slab + per-lane
+// offset".
 template <int TILE, bool KC>
 __device__ __forceinline__ void hdma_offsets(int ld, int row0, int wave, int lane, unsigned (&off)[HDma<TILE>::NV]) {
-    typedef HDma<TILE> D;
 #pragma unroll
-    for (int u = 0; u < D::NV; ++u) {
-        const int ch = wave + D::NW * u;
-        if (KC) {           // element (row, k) at base[row*ld + k]: a chunk is RPC rows
-            const int row = D::RPC * ch + lane / D::HKQ;
-            const int q = (lane % D::HKQ) ^ kc_swizzle<TILE>(row);
-            off[u] = ((unsigned)(row0 + row) * (unsigned)ld + 8u * q) * 2u;
-        } else {            // element (row, k) at base[k*ld + row]: a chunk is LPC k-lines
-            const int k = D::LPC * ch + lane / D::CPR;
-            const int c = (lane % D::CPR) ^ kr_swizzle<TILE>(k);
-            off[u] = ((unsigned)k * (unsigned)ld + row0 + 8u * c) * 2u;
-        }
-    }
+    for (int u = 0; u < HDma<TILE>::NV; ++u) off[u] = HDma<TILE>::load_offset(KC, ld, row0, wave, lane, u);
 }
 
 // uniform byte offset of slab k0 inside the block
@@ -158,44 +127,33 @@ __device__ __forceinline__ void hdma_load(const char* __restrict__ slab, const u
                                           char* __restrict__ dst, int wave) {
     typedef HDma<TILE> D;
 #pragma unroll
-    for (int u = 0; u < D::NV; ++u) direct_load16(slab, off[u], dst + (wave + D::NW * u) * 1024);
+    for (int u = 0; u < D::NV; ++u) direct_load16(slab, off[u], dst + D::chunk(wave, u) * 1024);
 }
 
 // Per-lane LDS byte offsets of the operand fragments of a wavefront's MT sub-tiles of 32 rows, the first at
-// r0.  Lane L holds row L%32 of the sub-tile and k = 16 st + 8 (L/32) + 0..7 of MFMA step st.  KC: one offset
-// per step (the swizzle depends on the step), the sub-tile adds an immediate; KR: one offset per sub-tile (the
-// swizzle depends on it), the step adds an immediate.
+// r0.  KC: one offset per MFMA step (the swizzle depends on the step), the sub-tile adds an immediate; KR: one
+// offset per sub-tile (the swizzle depends on it), the step adds an immediate.
 template <int TILE, bool KC, int MT>
 struct HFrag {
     typedef HDma<TILE> D;
-    static constexpr int STEPS = D::HBK / 16;
-    int base[KC ? STEPS : MT];
+    int base[KC ? D::STEPS : MT];
     __device__ __forceinline__ void init(int r0, int lane) {
         if (KC) {
-            const int row = r0 + (lane & 31);
 #pragma unroll
-            for (int st = 0; st < STEPS; ++st)
-                base[st] = row * (D::HBK * 2) + (((2 * st + (lane >> 5)) ^ kc_swizzle<TILE>(row)) << 4);
+            for (int st = 0; st < D::STEPS; ++st) base[st] = D::frag_kc(r0, lane, st);
         } else {
-            // sixteen lanes j = L%16 read the patch k-lines kk .. kk+3 x rows rs .. rs+15: lane j supplies the
-            // address of line kk + j/4, rows rs + 4 (j%4) .. +3, and receives row rs + j of all four lines
-            const int j = lane & 15;
-            const int kk = 8 * (lane >> 5) + (j >> 2);
 #pragma unroll
-            for (int i = 0; i < MT; ++i) {
-                const int rs = r0 + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
-                base[i] = (kk * D::CPR + ((rs >> 3) ^ kr_swizzle<TILE>(kk))) * 16 + 8 * (j & 1);
-            }
+            for (int i = 0; i < MT; ++i) base[i] = D::frag_kr(r0, i, lane);
         }
     }
     __device__ __forceinline__ v4u read(const char* __restrict__ s, int i, int st) const {
-        if (KC) return *reinterpret_cast<const v4u*>(s + base[st] + i * (32 * D::HBK * 2));
+        if (KC) return *reinterpret_cast<const v4u*>(s + base[st] + i * D::KC_SUB);
         typedef short v4h __attribute__((ext_vector_type(4)));
         typedef v4h __attribute__((address_space(3))) * lptr;
-        const char* p = s + base[i] + st * (16 * D::CPR * 16);
+        const char* p = s + base[i] + st * D::KR_STEP;
         union { v4h h[2]; v4u u; } x;
         x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
-        x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 4 * D::CPR * 16));
+        x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + D::KR_HALF));
         return x.u;
     }
 };
