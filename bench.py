@@ -29,7 +29,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 # HBM bytes the matmul kernel moves per block product on this workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size
 # (profiles/gemm_f32_cfg2_hbm_traffic.txt); the algorithmic figure is 12*B^2 = 12.58e6.
-MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 14.02e6
+MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 14.0e6
 
 
 def log(*a):
@@ -350,9 +350,8 @@ def main():
                     launches_per_step=launches / args.steps,
                     mean_launch_ms=mm_ms / max(launches, 1),
                     launch_note="a launch whose last round of 128-tile workgroups would be under half full (the "
-                                "36-tile symmetric residual on 32 blocks) is issued as two kernels: the blocks that "
-                                "fill whole rounds with this kernel, the remaining blocks with its <64, ...> "
-                                "instance; the HIP events bracket both",
+                                "36-tile symmetric residual on 32 blocks) computes the blocks that fill whole rounds "
+                                "with 128 tiles and the remaining blocks with 64 tiles, in the same kernel launch",
                     matmul_share_of_step=mm_ms / (dt * 1e3))
 
     # the paper's own matmul count for the root (3k-2 per call, two calls) prices the

@@ -130,28 +130,24 @@ struct Frag {
     }
 };
 
-// TILE x TILE output tile per workgroup; each wavefront owns WT x WT of it, i.e. MT x MT MFMA tiles of 32 x 32.
-template <int TILE, bool TA, bool TB, bool RECT = false>
-#ifndef DASH_MIN_WG
-#define DASH_MIN_WG 2
-#endif
-__global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void gemm_f32_kernel(GemmLaunch g) {
+// floats of LDS a workgroup of TILE needs: two stages of two operand slabs, or the epilogue strips
+template <int TILE>
+struct LdsNeed {
+    static constexpr int STAGES = 2 * 2 * Dma<TILE>::SLAB;
+    static constexpr int STRIPS = Cfg<TILE>::NW * 32 * (Cfg<TILE>::WT + 4);
+    static constexpr int FLOATS = STAGES > STRIPS ? STAGES : STRIPS;
+};
+
+// One TILE x TILE output tile: workgroup `lid` of a part of a launch whose blocks start at blk_first.  Each
+// wavefront owns WT x WT of the tile, i.e. MT x MT MFMA tiles of 32 x 32.  `lds` is the workgroup's LDS.
+template <int TILE, bool TA, bool TB, bool RECT>
+__device__ __forceinline__ void gemm_f32_tile(const GemmLaunch& g, int64_t lid, int64_t blk_first, float* lds) {
     constexpr int MT = Cfg<TILE>::WT / 32;
     constexpr bool A_KC = !TA;   // op(A)(i,k): k contiguous unless transposed
     constexpr bool B_KC = TB;    // op(B)(k,j): j contiguous unless transposed
     constexpr int NV = Dma<TILE>::NV;
     constexpr int SLAB = Dma<TILE>::SLAB;         // floats per operand slab; a stage is the A slab and the B slab
-    constexpr int STRIPS = Cfg<TILE>::NW * 32 * (Cfg<TILE>::WT + 4);      // floats the epilogue strips need
-    constexpr int LDSF = 2 * 2 * SLAB > STRIPS ? 2 * 2 * SLAB : STRIPS;
-
-    __shared__ __attribute__((aligned(1024))) float lds[LDSF];
-
-    // ---- which tile am I (XCD-aware remap of the 1-D grid) ----
-    const int64_t W = gridDim.x;
-    const int64_t bid = blockIdx.x;
-    const int64_t xcd = bid % NUM_XCD, local = bid / NUM_XCD;
-    const int64_t per = W / NUM_XCD, rem = W % NUM_XCD;
-    const int64_t lid = xcd * per + (xcd < rem ? xcd : rem) + local;
+    constexpr int LDSF = LdsNeed<TILE>::FLOATS;
 
     // op(A) is Md x Kd, op(B) is Kd x Nd, C is Md x Nd (all equal to g.B unless a rectangular launch
     // sets g.M, g.N, g.K: ragged gradient blocks, paper Section 4.1 "rest" blocks)
@@ -159,7 +155,7 @@ __global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void 
     const int Md = RECT && g.M ? g.M : g.B, Nd = RECT && g.N ? g.N : Md, Kd = RECT && g.K ? g.K : Md;
     const int tiles = Md / TILE, tiles_n = Nd / TILE;
     const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles_n;
-    const int64_t blk = g.blk0 + lid / ((int64_t)g.nprob * T);
+    const int64_t blk = blk_first + lid / ((int64_t)g.nprob * T);
     const int r1 = (int)(lid % ((int64_t)g.nprob * T));
     const int pi = r1 / T;
     const int tile = r1 % T;
@@ -338,10 +334,51 @@ __global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void 
     if (g.nonfinite && pi == 0 && bad) g.nonfinite[blk] = 1;
 }
 
+// XCD-aware remap of a 1-D range of W workgroup ids: hardware hands consecutive ids to the 8 XCDs round-robin;
+// the remapped id makes each XCD walk a contiguous range
+__device__ __forceinline__ int64_t xcd_remap(int64_t bid, int64_t W) {
+    const int64_t xcd = bid % NUM_XCD, local = bid / NUM_XCD;
+    const int64_t per = W / NUM_XCD, rem = W % NUM_XCD;
+    return xcd * per + (xcd < rem ? xcd : rem) + local;
+}
+
+// The launch: workgroups [0, g.w_main) compute TILE tiles of the first g.n_main blocks; when the launch is split
+// (TILE 128, square products), workgroups from g.w_main on compute 64 tiles of the remaining blocks.  They have
+// the same 256 threads and fit the same LDS, so they fill the CUs as the big tiles drain.
+template <int TILE, bool TA, bool TB, bool RECT = false>
+#ifndef DASH_MIN_WG
+#define DASH_MIN_WG 2
+#endif
+__global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void gemm_f32_kernel(GemmLaunch g) {
+    __shared__ __attribute__((aligned(1024))) float lds[LdsNeed<TILE>::FLOATS];
+    const int64_t bid = blockIdx.x;
+    if (TILE == 128 && !RECT) {
+        static_assert(TILE != 128 || LdsNeed<64>::FLOATS <= LdsNeed<TILE>::FLOATS, "the 64 tile must fit");
+        if (bid >= g.w_main) {
+            gemm_f32_tile<64, TA, TB, false>(g, xcd_remap(bid - g.w_main, (int64_t)gridDim.x - g.w_main),
+                                             g.blk0 + g.n_main, lds);
+            return;
+        }
+        gemm_f32_tile<TILE, TA, TB, RECT>(g, xcd_remap(bid, g.w_main), g.blk0, lds);
+    } else {
+        gemm_f32_tile<TILE, TA, TB, RECT>(g, xcd_remap(bid, gridDim.x), g.blk0, lds);
+    }
+}
+
+// workgroups of nblocks blocks computed with TILE tiles
 template <int TILE>
-static hipError_t launch_tile(const GemmLaunch& g, hipStream_t stream) {
-    const int tiles = (g.M ? g.M : g.B) / TILE, tiles_n = (g.N ? g.N : g.B) / TILE;
-    const int64_t W = g.nblocks * g.nprob * (g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles_n);
+static int64_t tile_count(const GemmLaunch& g, int64_t nblocks) {
+    const int64_t tiles = (g.M ? g.M : g.B) / TILE, tiles_n = (g.N ? g.N : g.B) / TILE;
+    return nblocks * g.nprob * (g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles_n);
+}
+
+// n_main blocks with TILE tiles; the remaining blocks (TILE 128 only) with 64 tiles in the same launch
+template <int TILE>
+static hipError_t launch_tile(const GemmLaunch& g0, int64_t n_main, hipStream_t stream) {
+    GemmLaunch g = g0;
+    g.n_main = n_main;
+    g.w_main = tile_count<TILE>(g, n_main);
+    const int64_t W = g.w_main + (n_main < g.nblocks ? tile_count<64>(g, g.nblocks - n_main) : 0);
     if (W <= 0) return hipSuccess;
     if (W > 0x7fffffffLL) return hipErrorInvalidValue;
     // both products of a launch must use the same transpose flags (one kernel instance)
@@ -370,17 +407,10 @@ hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
     if (g.nprob == 2 && (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
         return hipErrorInvalidValue;
     if (g.half != HALF_NONE) return launch_gemm_half(g, stream);
-    if (gemm_tile_edge(g) != 128) return launch_tile<64>(g, stream);
-    const int64_t na = gemm_split_blocks(g);
-    if (na == g.nblocks) return launch_tile<128>(g, stream);
-    // whole rounds with 128 tiles, then the last blocks with 64 tiles (same result bit for bit: an output
-    // element is accumulated over k in the same order whatever the tile)
-    GemmLaunch a = g, b = g;
-    a.nblocks = na;
-    b.blk0 = g.blk0 + na;
-    b.nblocks = g.nblocks - na;
-    const hipError_t e = launch_tile<128>(a, stream);
-    return e != hipSuccess ? e : launch_tile<64>(b, stream);
+    if (gemm_tile_edge(g) != 128) return launch_tile<64>(g, g.nblocks, stream);
+    // whole rounds with 128 tiles; the last blocks, if any, with 64 tiles behind them in the same launch (same
+    // result bit for bit: an output element is accumulated over k in the same order whatever the tile)
+    return launch_tile<128>(g, gemm_split_blocks(g), stream);
 }
 
 // 128-wide tiles when they still give the chip enough workgroups, else 64-wide
@@ -398,7 +428,7 @@ int gemm_tile_edge(const GemmLaunch& g) {
 // Returns the number of blocks of the first part (nblocks: no split).
 int64_t gemm_split_blocks(const GemmLaunch& g) {
     constexpr int64_t RESIDENT = 4 * 256;
-    if (g.half != HALF_NONE || gemm_tile_edge(g) != 128) return g.nblocks;
+    if (g.half != HALF_NONE || g.M || g.N || g.K || gemm_tile_edge(g) != 128) return g.nblocks;
     const int64_t tm = (g.M ? g.M : g.B) / 128, tn = (g.N ? g.N : g.B) / 128;
     const int64_t per_block = g.nprob * (g.sym ? tm * (tm + 1) / 2 : tm * tn);
     const int64_t W = g.nblocks * per_block;

@@ -46,6 +46,7 @@ struct GemmLaunch {
                            // (contiguous stacks; fp32 launches only; symmetric mode needs M == N)
     int64_t nblocks;       // blocks in this launch
     int64_t blk0;          // index of the launch's first block inside the stacks the pointers name (normally 0)
+    int64_t n_main, w_main;   // set by launch_gemm: blocks and workgroups of the launch's first part (fp32 split launches)
     int32_t* nonfinite;    // per-block flag for prob[0]'s output, or null
     int half;              // HALF_NONE: fp32 MFMA operands; HALF_BF16 / HALF_FP16: 16-bit operands
     int sym;               // 1: every product of the launch is symmetric in exact arithmetic:
