@@ -46,7 +46,8 @@ struct GemmLaunch {
                            // (contiguous stacks; fp32 launches only; symmetric mode needs M == N)
     int64_t nblocks;       // blocks in this launch
     int64_t blk0;          // index of the launch's first block inside the stacks the pointers name (normally 0)
-    int64_t n_main, w_main;   // set by launch_gemm: blocks and workgroups of the launch's first part (fp32 split launches)
+    int64_t n_main, w_main;   // filled in by launch_gemm: blocks and workgroups computed with the launch's own tile edge;
+                              // the remaining blocks of an fp32 launch are computed with 64 tiles by its last workgroups
     int32_t* nonfinite;    // per-block flag for prob[0]'s output, or null
     int half;              // HALF_NONE: fp32 MFMA operands; HALF_BF16 / HALF_FP16: 16-bit operands
     int sym;               // 1: every product of the launch is symmetric in exact arithmetic:
@@ -54,10 +55,10 @@ struct GemmLaunch {
 };
 
 hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream);
-int gemm_tile_edge(const GemmLaunch& g);          // tile edge launch_gemm picks for fp32 (64 or 128)
-int gemm_half_tile_edge(const GemmLaunch& g);     // tile edge of a 16-bit launch (64 or 128)
+int gemm_tile_edge(const GemmLaunch& g);          // tile edge launch_gemm picks for fp32 (64 or 128; see gemm_split_blocks)
+int gemm_half_tile_edge(const GemmLaunch& g);     // tile edge of a 16-bit launch (64, 128 or 256)
 double gemm_tile_fraction(const GemmLaunch& g);   // share of output tiles actually computed
-int64_t gemm_split_blocks(const GemmLaunch& g);   // fp32: blocks computed with 128 tiles before the rest goes to 64 tiles
+int64_t gemm_split_blocks(const GemmLaunch& g);   // fp32: blocks a launch computes with 128 tiles; the rest (if any) with 64
 hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream);   // gemm_half.hip
 
 // partial[b*P + q] = sum over the q-th row slab of block b of (A + eps I)^2 (mode 0)
