@@ -127,3 +127,38 @@ def test_precondition(dash, N, B):
     torch.cuda.synchronize()
     assert torch.equal(U, U2)
     d2.close()
+
+
+@pytest.mark.parametrize("N,B", [(1, 4096), (1, 8192)])
+def test_gemm_large_block_edges_sampled(dash, N, B):
+    """Block edges far above the benchmark's: the per-lane byte offsets of the direct loads are 32-bit and a
+    block of 8192^2 fp32 is 256 MiB.  A float64 product of that size is out of reach for the oracle side, so
+    sampled rows and columns are checked: C[r, :] = A[r, :] B and C[:, c] = A B[:, c], fp32 and bf16 operands,
+    one transposed form."""
+    import torch
+    print(f"gemm large N={N} B={B}", flush=True)
+    rng = np.random.default_rng(B)
+    A = (rng.standard_normal((N, B, B)) / np.sqrt(B)).astype(np.float32)
+    Bm = (rng.standard_normal((N, B, B)) / np.sqrt(B)).astype(np.float32)
+    At, Bt = torch.from_numpy(A).cuda(), torch.from_numpy(Bm).cuda()
+    C = torch.empty_like(At)
+    rows = [0, 1, 127, 128, B // 2 + 5, B - 1]
+    cols = [0, 63, 64, B // 3, B - 2, B - 1]
+    A64, B64 = A[0].astype(np.float64), Bm[0].astype(np.float64)
+
+    def check(Cn, opA, opB, tol):
+        for r in rows:
+            ref = opA[r, :] @ opB
+            assert np.linalg.norm(Cn[r, :] - ref) <= tol * np.linalg.norm(ref), r
+        for c in cols:
+            ref = opA @ opB[:, c]
+            assert np.linalg.norm(Cn[:, c] - ref) <= tol * np.linalg.norm(ref), c
+
+    dash.gemm_batched(At, Bt, C)
+    check(C[0].cpu().numpy().astype(np.float64), A64, B64, 2e-5)
+    dash.gemm_batched(At, Bt, C, transA=True)
+    check(C[0].cpu().numpy().astype(np.float64), A64.T, B64, 2e-5)
+    dash.gemm_batched(At, Bt, C, precision="bf16")
+    Ab = At[0].bfloat16().float().cpu().numpy().astype(np.float64)
+    Bb = Bt[0].bfloat16().float().cpu().numpy().astype(np.float64)
+    check(C[0].cpu().numpy().astype(np.float64), Ab, Bb, 2e-5)
