@@ -169,6 +169,17 @@ dash_status dash_block_layer(dash_ctx* ctx, const float* W, int64_t m, int64_t n
 dash_status dash_unblock_layer(dash_ctx* ctx, float* W, int64_t m, int64_t n, int B,
                                const float* full, const float* row_rest, const float* col_rest,
                                const float* corner);
+/* The same with the rest extents rounded up inside the stacks: with pm = rm rounded up to a multiple of pad_m
+ * and pn = rn rounded up to a multiple of pad_n the groups are row_rest [Nn][pm][B], col_rest [Nm][B][pn],
+ * corner [1][pm][pn]; blocking fills the padding with zeros, unblocking ignores it.  pad_m, pad_n >= 1 must
+ * divide B.  Zero rows and columns of a gradient block change nothing in the part of its factors, roots and
+ * update that belongs to the real entries (the factors stay block diagonal, the padded diagonal block is
+ * eps I), which is how layers of any shape go through the product kernels (block edges multiples of 64). */
+dash_status dash_block_layer_padded(dash_ctx* ctx, const float* W, int64_t m, int64_t n, int B, int pad_m, int pad_n,
+                                    float* full, float* row_rest, float* col_rest, float* corner);
+dash_status dash_unblock_layer_padded(dash_ctx* ctx, float* W, int64_t m, int64_t n, int B, int pad_m, int pad_n,
+                                      const float* full, const float* row_rest, const float* col_rest,
+                                      const float* corner);
 
 /* A layer whose dimensions are not multiples of B leaves "rest" gradient blocks of shape Bm x Bn
  * (the paper's example: (2, 256, 1024) with L_rest (2, 256, 256) and R_rest (2, 1024, 1024)).
@@ -253,7 +264,7 @@ dash_status dash_graft_update(dash_ctx* ctx, const float* G, const float* U, flo
  * (U_scaled may equal U, or be NULL).  Used for ragged blocks and vectors (Section 4.1). */
 dash_status dash_graft_scale(dash_ctx* ctx, const float* G, const float* U, float* Acc, int64_t N,
                              int64_t elems, float beta_g, float eps_g, float* U_scaled, float* s_out);
-/* theta <- theta - lr * update over n floats (Algorithm 1, parameter update); n a multiple of 4,
+/* theta <- theta - lr * update over n floats (Algorithm 1, parameter update); any n >= 0,
  * both pointers dev, 16-byte aligned. */
 dash_status dash_apply_update(dash_ctx* ctx, float* theta, const float* update, int64_t n, float lr);
 
@@ -297,8 +308,10 @@ dash_status dash_step(dash_ctx* ctx, const dash_step_args* args);
  * stack(L_full, R_full, R_rest) of 126 blocks of 1024 and L_rest of 2 blocks of 256).  Between refreshes
  * (the paper's recomputation frequency f > 1) the stored roots are reused.
  * A layer is m x n row-major; n = 0 marks a 1-D parameter (normalisation layer) of m entries, which is cut
- * into vectors of B entries with a left factor only and root p_vec (the paper uses 2).  m mod B, n mod B
- * must be multiples of 64 (DASH_ERR_UNSUPPORTED otherwise). */
+ * into vectors of B entries with a left factor only and root p_vec (the paper uses 2).  Layers of any
+ * shape are accepted: rest extents (m mod B, n mod B) that are not multiples of 64 are rounded up to the next
+ * one inside the model's stacks, zero filled (see dash_block_layer_padded); dash_model_get_bucket reports the
+ * padded block shapes. */
 typedef struct { int64_t m, n; } dash_layer_shape;
 typedef struct dash_model dash_model;
 typedef struct {

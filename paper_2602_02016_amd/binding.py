@@ -115,6 +115,8 @@ def load_library(path: str = LIB_PATH):
     lib.dash_precondition_vector.argtypes = [vp, vp, vp, vp, i64, i32]
     lib.dash_block_layer.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.dash_unblock_layer.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.dash_block_layer_padded.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    lib.dash_unblock_layer_padded.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.dash_model_create.argtypes = [vp, C.POINTER(_LayerShape), i32, i32, i32, i32, C.POINTER(vp)]
     lib.dash_model_destroy.argtypes = [vp]
     lib.dash_model_last_error.argtypes = [vp]
@@ -138,7 +140,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_apply_update.argtypes = [vp, vp, vp, i64, f32]
     for name in ("dash_create", "dash_destroy", "dash_set_stream", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
                  "dash_set_symmetric", "dash_set_power_iteration", "dash_accumulate_factors_rect",
-                 "dash_block_layer", "dash_unblock_layer", "dash_graft_scale", "dash_apply_update", "dash_model_create", "dash_model_destroy",
+                 "dash_block_layer", "dash_unblock_layer", "dash_block_layer_padded", "dash_unblock_layer_padded", "dash_graft_scale", "dash_apply_update", "dash_model_create", "dash_model_destroy",
                  "dash_model_get_info", "dash_model_get_bucket", "dash_model_get_stack", "dash_model_set_arena",
                  "dash_model_step",
                  "dash_precondition_rect", "dash_accumulate_vector", "dash_precondition_vector",
@@ -159,11 +161,13 @@ def chebyshev_fit(p: int, degree: int, a: float, b: float, n_points: int = 10000
     return list(out)
 
 
-def layer_plan(m: int, n: int, B: int) -> dict:
-    """Stack shapes block() gives for a [m, n] layer (host arithmetic only; see dash_block_layer)."""
+def layer_plan(m: int, n: int, B: int, pad_m: int = 1, pad_n: int = 1) -> dict:
+    """Stack shapes block() gives for a [m, n] layer (host arithmetic only; see dash_block_layer and, for
+    pad_m, pad_n > 1, dash_block_layer_padded: the rest extents are rounded up inside the stacks)."""
     Nm, Nn, rm, rn = m // B, n // B, m % B, n % B
-    return dict(full=(Nm * Nn, B, B), row_rest=(Nn if rm else 0, rm, B), col_rest=(Nm if rn else 0, B, rn),
-                corner=(1 if rm and rn else 0, rm, rn))
+    pm, pn = -(-rm // pad_m) * pad_m, -(-rn // pad_n) * pad_n
+    return dict(full=(Nm * Nn, B, B), row_rest=(Nn if rm else 0, pm, B), col_rest=(Nm if rn else 0, B, pn),
+                corner=(1 if rm and rn else 0, pm, pn))
 
 
 def _enum(table, v):
@@ -307,27 +311,28 @@ class Dash:
         self._check(self.lib.dash_accumulate_factors(self.h, self._stack(G, "G"), self._stack(L, "L", n, b),
                                                      self._stack(R, "R", n, b), n, b, beta, alpha))
 
-    def block_layer(self, W, B: int):
+    def block_layer(self, W, B: int, pad_m: int = 1, pad_n: int = 1):
         """block() of a [m, n] layer: returns dict(full, row_rest, col_rest, corner) of device stacks
-        (None for an empty group)."""
+        (None for an empty group).  pad_m, pad_n > 1: rest extents rounded up, padding zero filled."""
         torch = self._torch
         m, n = W.shape
-        shapes = layer_plan(m, n, B)
+        shapes = layer_plan(m, n, B, pad_m, pad_n)
         out = {k: (torch.empty(sh, dtype=torch.float32, device=self.device) if sh[0] * sh[1] * sh[2] > 0 else None)
                for k, sh in shapes.items()}
         ptr = lambda t: C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(None)
-        self._check(self.lib.dash_block_layer(self.h, self._dense(W, "W", (m, n)), m, n, B, ptr(out["full"]),
-                                              ptr(out["row_rest"]), ptr(out["col_rest"]), ptr(out["corner"])))
+        self._check(self.lib.dash_block_layer_padded(self.h, self._dense(W, "W", (m, n)), m, n, B, pad_m, pad_n,
+                                                     ptr(out["full"]), ptr(out["row_rest"]), ptr(out["col_rest"]),
+                                                     ptr(out["corner"])))
         return out
 
-    def unblock_layer(self, W, B: int, groups: dict):
+    def unblock_layer(self, W, B: int, groups: dict, pad_m: int = 1, pad_n: int = 1):
         m, n = W.shape
-        shapes = layer_plan(m, n, B)
+        shapes = layer_plan(m, n, B, pad_m, pad_n)
         ptrs = []
         for k in ("full", "row_rest", "col_rest", "corner"):
             sh, t = shapes[k], groups.get(k)
             ptrs.append(self._dense(t, k, sh) if sh[0] * sh[1] * sh[2] > 0 else C.c_void_p(None))
-        self._check(self.lib.dash_unblock_layer(self.h, self._dense(W, "W", (m, n)), m, n, B, *ptrs))
+        self._check(self.lib.dash_unblock_layer_padded(self.h, self._dense(W, "W", (m, n)), m, n, B, pad_m, pad_n, *ptrs))
         return W
 
     def accumulate_factors_rect(self, G, L, R, beta: float, alpha: Optional[float] = None):

@@ -788,31 +788,48 @@ dash_status dash_precondition_rect(dash_ctx* c, const float* Linv, const float* 
 }
 
 // ---- block() and its inverse (Section 4.1) ----
-static dash_status block_layer_impl(dash_ctx* c, float* W, int64_t m, int64_t n, int B, float* full, float* row_rest,
-                                    float* col_rest, float* corner, bool scatter) {
+static int64_t round_up(int64_t v, int64_t to) { return (v + to - 1) / to * to; }
+
+static dash_status block_layer_impl(dash_ctx* c, float* W, int64_t m, int64_t n, int B, int pad_m, int pad_n,
+                                    float* full, float* row_rest, float* col_rest, float* corner, bool scatter) {
     if (!c) return DASH_ERR_INVALID_ARG;
     if (m < 0 || n < 0 || B <= 0) return fail(c, DASH_ERR_INVALID_ARG, "need m, n >= 0 and B > 0 (m=%lld n=%lld B=%d)", (long long)m, (long long)n, B);
+    if (pad_m < 1 || pad_n < 1 || B % pad_m || B % pad_n)
+        return fail(c, DASH_ERR_INVALID_ARG, "the padding units must divide B (pad_m=%d pad_n=%d B=%d)", pad_m, pad_n, B);
     if (m == 0 || n == 0) return DASH_OK;
     const int64_t Nm = m / B, Nn = n / B;
     const int rm = (int)(m % B), rn = (int)(n % B);
+    const int pm = (int)round_up(rm, pad_m), pn = (int)round_up(rn, pad_n);      // rest extents inside the stacks
     if (!W || (Nm * Nn > 0 && !full) || (rm && Nn && !row_rest) || (rn && Nm && !col_rest) || (rm && rn && !corner))
         return fail(c, DASH_ERR_INVALID_ARG, "null pointer for a non-empty group");
     HIP_TRY(c, hipSetDevice(c->device));
-    HIP_TRY(c, launch_block_copy(W, full, n, 0, 0, B, B, B, Nm, Nn, scatter, c->stream));
-    if (rm) HIP_TRY(c, launch_block_copy(W, row_rest, n, Nm * B, 0, B, rm, B, 1, Nn, scatter, c->stream));
-    if (rn) HIP_TRY(c, launch_block_copy(W, col_rest, n, 0, Nn * B, B, B, rn, Nm, 1, scatter, c->stream));
-    if (rm && rn) HIP_TRY(c, launch_block_copy(W, corner, n, Nm * B, Nn * B, B, rm, rn, 1, 1, scatter, c->stream));
+    HIP_TRY(c, launch_block_copy(W, full, n, 0, 0, B, B, B, B, B, Nm, Nn, scatter, c->stream));
+    if (rm) HIP_TRY(c, launch_block_copy(W, row_rest, n, Nm * B, 0, B, rm, B, pm, B, 1, Nn, scatter, c->stream));
+    if (rn) HIP_TRY(c, launch_block_copy(W, col_rest, n, 0, Nn * B, B, B, rn, B, pn, Nm, 1, scatter, c->stream));
+    if (rm && rn) HIP_TRY(c, launch_block_copy(W, corner, n, Nm * B, Nn * B, B, rm, rn, pm, pn, 1, 1, scatter, c->stream));
     return DASH_OK;
 }
 
 dash_status dash_block_layer(dash_ctx* c, const float* W, int64_t m, int64_t n, int B, float* full, float* row_rest,
                              float* col_rest, float* corner) {
-    return block_layer_impl(c, const_cast<float*>(W), m, n, B, full, row_rest, col_rest, corner, false);
+    return block_layer_impl(c, const_cast<float*>(W), m, n, B, 1, 1, full, row_rest, col_rest, corner, false);
 }
 
 dash_status dash_unblock_layer(dash_ctx* c, float* W, int64_t m, int64_t n, int B, const float* full,
                                const float* row_rest, const float* col_rest, const float* corner) {
-    return block_layer_impl(c, W, m, n, B, const_cast<float*>(full), const_cast<float*>(row_rest),
+    return block_layer_impl(c, W, m, n, B, 1, 1, const_cast<float*>(full), const_cast<float*>(row_rest),
+                            const_cast<float*>(col_rest), const_cast<float*>(corner), true);
+}
+
+dash_status dash_block_layer_padded(dash_ctx* c, const float* W, int64_t m, int64_t n, int B, int pad_m, int pad_n,
+                                    float* full, float* row_rest, float* col_rest, float* corner) {
+    return block_layer_impl(c, const_cast<float*>(W), m, n, B, pad_m, pad_n, full, row_rest, col_rest, corner, false);
+}
+
+dash_status dash_unblock_layer_padded(dash_ctx* c, float* W, int64_t m, int64_t n, int B, int pad_m, int pad_n,
+                                      const float* full, const float* row_rest, const float* col_rest,
+                                      const float* corner) {
+    return block_layer_impl(c, W, m, n, B, pad_m, pad_n, const_cast<float*>(full), const_cast<float*>(row_rest),
                             const_cast<float*>(col_rest), const_cast<float*>(corner), true);
 }
 
@@ -1049,7 +1066,7 @@ dash_status dash_graft_scale(dash_ctx* c, const float* G, const float* U, float*
 
 dash_status dash_apply_update(dash_ctx* c, float* theta, const float* update, int64_t n, float lr) {
     if (!c) return DASH_ERR_INVALID_ARG;
-    if (n < 0 || n % 4) return fail(c, DASH_ERR_INVALID_ARG, "element count must be a non-negative multiple of 4");
+    if (n < 0) return fail(c, DASH_ERR_INVALID_ARG, "element count must not be negative");
     if (n == 0) return DASH_OK;
     if (!theta || !update) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     if (((uintptr_t)theta | (uintptr_t)update) % 16) return fail(c, DASH_ERR_INVALID_ARG, "pointers must be 16-byte aligned");

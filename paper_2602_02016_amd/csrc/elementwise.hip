@@ -218,7 +218,12 @@ __global__ __launch_bounds__(NT) void graft_apply_kernel(const float* U, float* 
 }
 
 // y -= a * x over n floats (n a multiple of 4, 16-byte aligned); four independent quads per thread and pass
-__global__ __launch_bounds__(NT) void axpy_kernel(float* __restrict__ y, const float* __restrict__ x, int64_t n4, float a) {
+__global__ __launch_bounds__(NT) void axpy_kernel(float* __restrict__ y, const float* __restrict__ x, int64_t n, float a) {
+    const int64_t n4 = n / 4;
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(n - 4 * n4)) {      // the up to three elements past the quads
+        const int64_t e = 4 * n4 + threadIdx.x;
+        y[e] -= a * x[e];
+    }
     const int64_t stride = (int64_t)gridDim.x * NT;
     int64_t f = blockIdx.x * (int64_t)NT + threadIdx.x;
     for (; f + 3 * stride < n4; f += 4 * stride) {
@@ -285,26 +290,37 @@ __global__ __launch_bounds__(NT) void matvec_kernel(const float* __restrict__ X,
 }
 
 // ---- block() / its inverse (paper Section 4.1): sub-matrices of a row-major layer <-> a stack ----
-// stack[(im*nn + in)][r][c] <-> W[(r0 + im*B + r) * ld + c0 + in*B + c], r < bm, c < bn.
-// VEC = 4: 16-byte accesses (needs ld, c0, B, bn multiples of 4 and aligned bases); VEC = 1: any shape.
-// grid = (ceil(bm*bn/VEC / NT), nm*nn)
+// stack[(im*nn + in)][r][c] <-> W[(r0 + im*B + r) * ld + c0 + in*B + c], r < bm, c < bn.  A stack block is
+// pm x pn >= bm x bn: gathering fills the padding with zeros, scattering ignores it.
+// VEC = 4: 16-byte accesses (needs ld, c0, B, bn, pn multiples of 4 and aligned bases); VEC = 1: any shape.
+// grid = (ceil(pm*pn/VEC / NT), nm*nn)
 template <int VEC, bool SCATTER>
 __global__ __launch_bounds__(NT) void block_copy_kernel(float* __restrict__ W, float* __restrict__ stack, int64_t ld,
-                                                       int64_t r0, int64_t c0, int B, int bm, int bn, int nn) {
+                                                       int64_t r0, int64_t c0, int B, int bm, int bn, int pm, int pn,
+                                                       int nn) {
     const int64_t blk = blockIdx.y;
     const int64_t im = blk / nn, in = blk % nn;
-    const int per_row = bn / VEC;
+    const int per_row = pn / VEC;
     const int64_t f = (int64_t)blockIdx.x * NT + threadIdx.x;
-    if (f >= (int64_t)bm * per_row) return;
+    if (f >= (int64_t)pm * per_row) return;
     const int r = (int)(f / per_row), c = (int)(f % per_row) * VEC;
+    const bool inside = r < bm && c < bn;              // bn is a multiple of VEC: a quad is inside or outside
     float* w = W + (r0 + im * B + r) * ld + c0 + in * B + c;
-    float* s = stack + blk * bm * bn + (int64_t)r * bn + c;
+    float* s = stack + blk * pm * pn + (int64_t)r * pn + c;
     if (VEC == 4) {
-        if (SCATTER) *reinterpret_cast<v4f*>(w) = *reinterpret_cast<const v4f*>(s);
-        else *reinterpret_cast<v4f*>(s) = *reinterpret_cast<const v4f*>(w);
+        if (SCATTER) {
+            if (inside) *reinterpret_cast<v4f*>(w) = *reinterpret_cast<const v4f*>(s);
+        } else {
+            v4f v = {0.f, 0.f, 0.f, 0.f};
+            if (inside) v = *reinterpret_cast<const v4f*>(w);
+            *reinterpret_cast<v4f*>(s) = v;
+        }
     } else {
-        if (SCATTER) *w = *s;
-        else *s = *w;
+        if (SCATTER) {
+            if (inside) *w = *s;
+        } else {
+            *s = inside ? *w : 0.f;
+        }
     }
 }
 
@@ -368,27 +384,25 @@ hipError_t launch_matvec(const float* X, const float* g, float* u, int64_t nbloc
 }
 
 hipError_t launch_block_copy(float* W, float* stack, int64_t ld, int64_t r0, int64_t c0, int B, int bm, int bn,
-                             int64_t nm, int64_t nn, bool scatter, hipStream_t stream) {
+                             int pm, int pn, int64_t nm, int64_t nn, bool scatter, hipStream_t stream) {
     if (nm <= 0 || nn <= 0 || bm <= 0 || bn <= 0) return hipSuccess;
-    if (nn > 0x7fffffff) return hipErrorInvalidValue;
-    const bool vec = ld % 4 == 0 && c0 % 4 == 0 && B % 4 == 0 && bn % 4 == 0 && (uintptr_t)W % 16 == 0 &&
-                     (uintptr_t)stack % 16 == 0;
+    if (nn > 0x7fffffff || pm < bm || pn < bn) return hipErrorInvalidValue;
+    const bool vec = ld % 4 == 0 && c0 % 4 == 0 && B % 4 == 0 && bn % 4 == 0 && pn % 4 == 0 &&
+                     (uintptr_t)W % 16 == 0 && (uintptr_t)stack % 16 == 0;
     const int V = vec ? 4 : 1;
-    const unsigned gx = (unsigned)(((int64_t)bm * (bn / V) + NT - 1) / NT);
-    const int64_t total = nm * nn;
+    const unsigned gx = (unsigned)(((int64_t)pm * (pn / V) + NT - 1) / NT);
     // grid.y is limited to 65535: whole rows of blocks per launch (all of them in the usual case)
     const int64_t rows_per = nn > 65535 ? 0 : 65535 / nn;
     if (rows_per == 0) return hipErrorInvalidValue;
-    (void)total;
     for (int64_t m0 = 0; m0 < nm; m0 += rows_per) {
         const int64_t mr = nm - m0 < rows_per ? nm - m0 : rows_per;
         dim3 grid(gx, (unsigned)(mr * nn)), block(NT);
-        float* st = stack + m0 * nn * bm * bn;
+        float* st = stack + m0 * nn * pm * pn;
         const int64_t rr = r0 + m0 * B;
-        if (vec && scatter) hipLaunchKernelGGL((block_copy_kernel<4, true>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, (int)nn);
-        else if (vec) hipLaunchKernelGGL((block_copy_kernel<4, false>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, (int)nn);
-        else if (scatter) hipLaunchKernelGGL((block_copy_kernel<1, true>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, (int)nn);
-        else hipLaunchKernelGGL((block_copy_kernel<1, false>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, (int)nn);
+        if (vec && scatter) hipLaunchKernelGGL((block_copy_kernel<4, true>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, pm, pn, (int)nn);
+        else if (vec) hipLaunchKernelGGL((block_copy_kernel<4, false>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, pm, pn, (int)nn);
+        else if (scatter) hipLaunchKernelGGL((block_copy_kernel<1, true>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, pm, pn, (int)nn);
+        else hipLaunchKernelGGL((block_copy_kernel<1, false>), grid, block, 0, stream, W, st, ld, rr, c0, B, bm, bn, pm, pn, (int)nn);
     }
     return hipGetLastError();
 }
@@ -431,10 +445,9 @@ hipError_t launch_graft_apply(const float* U, float* theta, const float* partial
 
 hipError_t launch_axpy(float* y, const float* x, int64_t n, float a, hipStream_t stream) {
     if (n <= 0) return hipSuccess;
-    if (n % 4) return hipErrorInvalidValue;
     const int64_t n4 = n / 4;
     const int64_t want = (n4 + NT - 1) / NT;
-    hipLaunchKernelGGL(axpy_kernel, dim3((unsigned)(want < 8192 ? want : 8192)), dim3(NT), 0, stream, y, x, n4, a);
+    hipLaunchKernelGGL(axpy_kernel, dim3((unsigned)(want < 1 ? 1 : want < 8192 ? want : 8192)), dim3(NT), 0, stream, y, x, n, a);
     return hipGetLastError();
 }
 

@@ -98,7 +98,7 @@ hipError_t launch_matvec(const float* X, const float* g, float* u, int64_t nbloc
 // origin (r0, c0) and pitch B in both directions <-> stack [nm*nn][bm][bn] (row-major block order).
 // scatter = false: W -> stack; true: stack -> W.
 hipError_t launch_block_copy(float* W, float* stack, int64_t ld, int64_t r0, int64_t c0, int B, int bm, int bn,
-                             int64_t nm, int64_t nn, bool scatter, hipStream_t stream);
+                             int pm, int pn, int64_t nm, int64_t nn, bool scatter, hipStream_t stream);
 
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
 

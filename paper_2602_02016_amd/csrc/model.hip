@@ -77,6 +77,10 @@ dash_status lib(dash_model* m, dash_status st) {
 
 float* at(const dash_model* m, size_t off) { return reinterpret_cast<float*>(m->arena + off); }
 
+// rest extents are rounded up to the block-edge granularity of the product kernels; the padding is zero
+constexpr int PAD = 64;
+int64_t pad64(int64_t v) { return (v + PAD - 1) / PAD * PAD; }
+
 }  // namespace
 
 extern "C" {
@@ -117,14 +121,12 @@ dash_status dash_model_create(dash_ctx* ctx, const dash_layer_shape* layers, int
         }
         if (nn == 0) {          // 1-D: m / B vectors of B entries and one of m mod B
             const int64_t nv = mm / B;
-            const int r = (int)(mm % B);
-            if (r % 64) { delete m; return DASH_ERR_UNSUPPORTED; }
+            const int r = (int)pad64(mm % B);         // the remainder, zero padded to the next multiple of 64
             L.part[1] = place(B, 0, nv);
             L.part[3] = place(r, 0, r ? 1 : 0);
         } else {
             const int64_t Nm = mm / B, Nn = nn / B;
-            const int rm = (int)(mm % B), rn = (int)(nn % B);
-            if (rm % 64 || rn % 64) { delete m; return DASH_ERR_UNSUPPORTED; }
+            const int rm = (int)pad64(mm % B), rn = (int)pad64(nn % B);     // rest extents inside the stacks
             L.part[0] = place(B, B, Nm * Nn);
             L.part[1] = place(rm, B, rm ? Nn : 0);
             L.part[2] = place(B, rn, rn ? Nm : 0);
@@ -253,8 +255,8 @@ dash_status dash_model_step(dash_model* m, const dash_model_step_args* a) {
     for (int l = 0; l < nl; ++l) {
         const Layer& L = m->layers[l];
         const int64_t mm = L.n ? L.m : 1, nn = L.n ? L.n : L.m;
-        dash_status st = lib(m, dash_block_layer(c, a->grads[l], mm, nn, B, group(L, 0, false), group(L, 1, false),
-                                                 group(L, 2, false), group(L, 3, false)));
+        dash_status st = lib(m, dash_block_layer_padded(c, a->grads[l], mm, nn, B, L.n ? PAD : 1, PAD, group(L, 0, false),
+                                                        group(L, 1, false), group(L, 2, false), group(L, 3, false)));
         if (st != DASH_OK) return st;
     }
     // 2. Kronecker factors, one call per bucket, written straight into the factor stacks
@@ -313,8 +315,8 @@ dash_status dash_model_step(dash_model* m, const dash_model_step_args* a) {
     for (int l = 0; l < nl; ++l) {
         const Layer& L = m->layers[l];
         const int64_t mm = L.n ? L.m : 1, nn = L.n ? L.n : L.m;
-        dash_status st = lib(m, dash_unblock_layer(c, a->updates[l], mm, nn, B, group(L, 0, true), group(L, 1, true),
-                                                   group(L, 2, true), group(L, 3, true)));
+        dash_status st = lib(m, dash_unblock_layer_padded(c, a->updates[l], mm, nn, B, L.n ? PAD : 1, PAD, group(L, 0, true),
+                                                          group(L, 1, true), group(L, 2, true), group(L, 3, true)));
         if (st != DASH_OK) return st;
         // Algorithm 1, parameter update
         if (a->thetas && a->thetas[l]) {

@@ -8,8 +8,8 @@
 extern "C" {
 const char* dash_last_error(const dash_ctx*) { return ""; }
 size_t dash_workspace_bytes(int64_t n, int B, dash_method, int, dash_precision) { return (size_t)n * B * B * 20; }
-dash_status dash_block_layer(dash_ctx*, const float*, int64_t, int64_t, int, float*, float*, float*, float*) { return DASH_OK; }
-dash_status dash_unblock_layer(dash_ctx*, float*, int64_t, int64_t, int, const float*, const float*, const float*, const float*) { return DASH_OK; }
+dash_status dash_block_layer_padded(dash_ctx*, const float*, int64_t, int64_t, int, int, int, float*, float*, float*, float*) { return DASH_OK; }
+dash_status dash_unblock_layer_padded(dash_ctx*, float*, int64_t, int64_t, int, int, int, const float*, const float*, const float*, const float*) { return DASH_OK; }
 dash_status dash_accumulate_factors(dash_ctx*, const float*, float*, float*, int64_t, int, float, float) { return DASH_OK; }
 dash_status dash_accumulate_factors_rect(dash_ctx*, const float*, float*, float*, int64_t, int, int, float, float) { return DASH_OK; }
 dash_status dash_accumulate_vector(dash_ctx*, const float*, float*, int64_t, int, float, float) { return DASH_OK; }
@@ -27,14 +27,18 @@ int main() {
         dash_layer_shape L[12];
         int B = 64 * (1 + (s = s * 1664525u + 1013904223u) % 8);
         for (int i = 0; i < nl; ++i) {
-            L[i].m = 64 * (1 + (s = s * 1664525u + 1013904223u) % 40);
-            L[i].n = ((s = s * 1664525u + 1013904223u) % 4 == 0) ? 0 : 64 * (1 + (s = s * 1664525u + 1013904223u) % 40);
+            const int unit = (trial & 1) ? 1 + (s = s * 1664525u + 1013904223u) % 97 : 64;     // odd trials: any shape
+            L[i].m = unit * (1 + (s = s * 1664525u + 1013904223u) % 40);
+            L[i].n = ((s = s * 1664525u + 1013904223u) % 4 == 0) ? 0 : unit * (1 + (s = s * 1664525u + 1013904223u) % 40);
         }
         dash_model* m = nullptr;
         if (dash_model_create((dash_ctx*)0x10, L, nl, B, 4, 2, &m) != DASH_OK) { printf("create failed\n"); return 1; }
         dash_model_info info; dash_model_get_info(m, &info);
         int64_t blocks = 0;
-        for (int i = 0; i < info.n_buckets; ++i) { int32_t bm, bn; int64_t c; dash_model_get_bucket(m, i, &bm, &bn, &c); blocks += c; }
+        for (int i = 0; i < info.n_buckets; ++i) {
+            int32_t bm, bn; int64_t c; dash_model_get_bucket(m, i, &bm, &bn, &c); blocks += c;
+            if (bm <= 0 || bm % 64 || bn % 64 || bm > B || bn > B) { printf("bucket %d x %d\n", bm, bn); return 1; }    // padded to the kernels' granularity
+        }
         if (blocks != info.n_gradient_blocks) { printf("count mismatch\n"); return 1; }
         // step through the whole sequence with a fake arena (stubs touch nothing)
         void* arena = aligned_alloc(256, 256);

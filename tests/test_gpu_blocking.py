@@ -45,6 +45,43 @@ def test_block_unblock_bit_exact(dash, m, n, B):
     assert np.array_equal(W2.cpu().numpy(), W)
 
 
+@pytest.mark.parametrize("m,n,B,pm,pn", [(300, 250, 128, 64, 64), (333, 205, 64, 16, 32), (131, 257, 128, 64, 64),
+                                         (1, 190, 128, 1, 64), (1000, 2048, 256, 64, 64), (77, 61, 64, 64, 64)])
+def test_block_unblock_padded(dash, m, n, B, pm, pn):
+    """Padded blocking: the rest extents are rounded up inside the stacks, the real entries are where the
+    unpadded blocking puts them, the padding is zero, and unblocking ignores it."""
+    import torch
+    print(f"padded block m={m} n={n} B={B} pad=({pm},{pn})", flush=True)
+    W = np.arange(m * n, dtype=np.float32).reshape(m, n) * 0.5 + 1.0
+    ref = oblocking.block_layer(W, B)
+    got = dash.block_layer(_to_gpu(W), B, pm, pn)
+    for k, v in ref.items():
+        if v.size == 0:
+            assert got[k] is None
+            continue
+        g = got[k].cpu().numpy()
+        assert g.shape[0] == v.shape[0] and g.shape[1] % (pm if k != "col_rest" else 1) == 0 and g.shape[1] >= v.shape[1]
+        assert g.shape[2] >= v.shape[2] and g.shape[2] - v.shape[2] < pn
+        assert np.array_equal(g[:, :v.shape[1], :v.shape[2]], v), k
+        pad = g.copy(); pad[:, :v.shape[1], :v.shape[2]] = 0.0
+        assert not pad.any(), k
+        got[k][:, v.shape[1]:, :] = 3.0                 # poison the padding: unblocking must not look at it
+        got[k][:, :, v.shape[2]:] = 3.0
+    W2 = torch.full((m, n), -1.0, device="cuda")
+    dash.unblock_layer(W2, B, got, pm, pn)
+    assert np.array_equal(W2.cpu().numpy(), W)
+
+
+def test_apply_update_any_length(dash):
+    import torch
+    for n in (1, 3, 4, 5, 1023, 4099, 77 * 61):
+        rng = np.random.default_rng(n)
+        t, u = rng.standard_normal(n).astype(np.float32), rng.standard_normal(n).astype(np.float32)
+        tg = torch.from_numpy(t).cuda()
+        dash.apply_update(tg, torch.from_numpy(u).cuda(), 0.25)
+        assert np.array_equal(tg.cpu().numpy(), t - np.float32(0.25) * u), n
+
+
 def test_block_empty_layer(dash):
     import torch
     got = dash.block_layer(torch.zeros(0, 64, device="cuda"), 64)
@@ -187,7 +224,9 @@ def test_invalid_arguments_of_the_new_entry_points(dash):
     with pytest.raises(DashError):
         dash.graft_scale(z(2, 3, 2), z(2, 3, 2), z(2, 3, 2))                    # 6 elements per block: not a multiple of 4
     with pytest.raises(DashError):
-        dash.apply_update(z(6), z(6), 0.1)                                      # 6 floats: not a multiple of 4
+        dash.apply_update(z(8)[1:], z(8)[1:], 0.1)                              # pointers not 16-byte aligned
+    with pytest.raises(DashError):
+        dash.block_layer(z(100, 100), 64, 48, 1)                                # the padding unit must divide B
     with pytest.raises(DashError):
         dash.precondition_rect(z(1, 64, 64), z(1, 64, 128), z(1, 64, 64))       # Rinv must be 128 x 128
     # null pointers reach the library and come back as status 1, not as a fault

@@ -108,11 +108,57 @@ def test_model_step_with_grafting_and_parameter_update(dash):
     model.close()
 
 
+ODD_LAYERS = [(300, 250), (131, 257), (64, 100), (190,), (77,)]
+
+
+def test_model_step_any_layer_shape(dash):
+    """Layers whose rest extents are not multiples of 64: the model pads them with zeros inside its stacks
+    (rest blocks of 44 x 122 become 64 x 128, ...), which leaves the real part of factors, roots and updates
+    what it is.  Against the oracle, which works on the exact shapes; with grafting and the parameter update."""
+    import torch
+    from paper_2602_02016_amd import DashModel
+    model = DashModel(dash, ODD_LAYERS, B, p=4, p_vec=2)
+    print("plan", model.plan["buckets"], model.plan["stacks"], flush=True)
+    assert all(bm % 64 == 0 and bn % 64 == 0 for bm, bn, _ in model.plan["buckets"])
+    beta, eps, k, beta_g, eps_g, lr = 0.9, 1e-5, 30, float(np.float32(0.999)), 1e-8, 0.01
+    b32 = float(np.float32(beta)); a32 = float(np.float32(1.0) - np.float32(beta))
+    state = [None] * len(ODD_LAYERS)
+    accs = [np.zeros(s) for s in ODD_LAYERS]
+    rng = np.random.default_rng(123)
+    theta_np = [rng.standard_normal(s).astype(np.float32) for s in ODD_LAYERS]
+    thetas = [torch.from_numpy(t).cuda() for t in theta_np]
+    theta_ref = [t.astype(np.float64) for t in theta_np]
+    nf = torch.ones(model.plan["info"]["n_factor_blocks"], dtype=torch.int32, device="cuda")
+    for step in range(3):
+        g_np = [(rng.standard_normal(s) * (1e-2 if len(s) == 2 else 3e-3)).astype(np.float32) for s in ODD_LAYERS]
+        grads = [torch.from_numpy(g).cuda() for g in g_np]
+        ups = [torch.full_like(g, 7.0) for g in grads]
+        model.step(grads, ups, beta=beta, eps=eps, method="newton_db", iters=k, graft=True, beta_g=beta_g, eps_g=eps_g,
+                   thetas=thetas, lr=lr, nonfinite_out=nf)
+        assert int(nf.sum().item()) == 0
+        for i, g in enumerate(g_np):
+            f, r = state[i] if state[i] is not None else (None, None)
+            if g.ndim == 2:
+                u, f, r = oblocking.layer_step_cached(g, f, r, B, b32, eps, 4, a32, True)
+            else:
+                u, f, r = oblocking.vector_param_step_cached(g, f, r, B, b32, eps, 2, a32, True)
+            state[i] = (f, r)
+            ug, accs[i] = oblocking.graft_layer(g, u, accs[i], B, beta_g, eps_g)
+            theta_ref[i] = theta_ref[i] - float(np.float32(lr)) * ug
+            got = ups[i].cpu().numpy()
+            e = np.linalg.norm(got - ug) / np.linalg.norm(ug)
+            assert e < 2e-4, (step, i, ODD_LAYERS[i], e)
+            assert np.abs(thetas[i].cpu().numpy() - theta_ref[i]).max() < 1e-5, (step, i)
+    print("odd-shaped model step ok", flush=True)
+    model.close()
+
+
 def test_model_errors(dash):
     import torch
     from paper_2602_02016_amd import DashModel, DashError
-    with pytest.raises(DashError):
-        DashModel(dash, [(100, 128)], 128)                 # 100 is not a multiple of 64
+    padded = DashModel(dash, [(100, 128)], 128)            # 100 rows: one rest block, padded to 128 x 128
+    assert padded.plan["buckets"] == [(128, 128, 1)]
+    padded.close()
     model = DashModel(dash, [(128, 128)], 128)
     g = torch.zeros(128, 128, device="cuda")
     with pytest.raises(DashError):

@@ -135,8 +135,11 @@ def test_model_plan_matches_paper_example_and_counts():
     assert dict((s, c) for s, p, c in plan["stacks"] if p == 4) == {1024: sum(x["S_full"][0] for x in sh), 256: 4}
     assert [(s, p, c) for s, p, c in plan["stacks"] if p == 2] == [(1024, 2, 4)]
     assert plan["info"]["n_gradient_blocks"] == sum(x["G_full"][0] for x in sh) + 2 + 2 + 4
-    with pytest.raises(Exception):
-        model_plan([(1000, 2048)], 1024)            # 1000 mod 1024 is not a multiple of 64
+    # a rest extent that is not a multiple of 64 is rounded up inside the model's stacks (zero padding):
+    # 1000 rows -> one row of rest blocks padded to 1024 x 1024; 100 rows, 130 columns -> 128 x 1024, 1024 x 64, 128 x 64
+    assert model_plan([(1000, 2048)], 1024)["buckets"] == [(1024, 1024, 2)]
+    assert model_plan([(1124, 1154)], 1024)["buckets"] == [(1024, 1024, 1), (128, 1024, 1), (1024, 192, 1), (128, 192, 1)]
+    assert model_plan([(1100,)], 1024)["buckets"] == [(1024, 0, 1), (128, 0, 1)]
 
 
 def test_graft_layer_against_stack_grafting_and_norm_property():
