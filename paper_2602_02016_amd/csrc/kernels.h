@@ -112,7 +112,7 @@ hipError_t launch_graft_partials(const float* G, const float* U, float* Acc, int
 // may equal U); s_out may be null
 hipError_t launch_graft_apply(const float* U, float* theta, const float* partial, int64_t nblocks,
                               int64_t elems, float lr, float* s_out, float* scaled, hipStream_t stream);
-// y -= a * x over n floats (n a multiple of 4)
+// y -= a * x over n floats (any n; pointers 16-byte aligned)
 hipError_t launch_axpy(float* y, const float* x, int64_t n, float a, hipStream_t stream);
 
 }  // namespace dash
