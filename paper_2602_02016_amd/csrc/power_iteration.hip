@@ -72,6 +72,8 @@ __host__ __device__ inline int pi_q_floats(int B) { return POOL + 2 * POOL * pi_
 // V holds the un-normalised product of the previous sweep; its columns are scaled to unit length on the
 // way in, with the norms the previous sweep left as per-workgroup partial sums in qprev -- so a sweep is
 // one launch, and it leaves its own partial sums (norms and Rayleigh quotients of its output) in qnext.
+// STREAM: the stack is larger than the 256 MB last-level cache, so A is read with the non-temporal hint (+5 %)
+template <bool STREAM>
 __global__ __launch_bounds__(PNT, 2) void pi_sweep_kernel(const float* __restrict__ A, const float* __restrict__ V,
                                                          float* __restrict__ W, int B, float eps,
                                                          const float* __restrict__ qprev, float* __restrict__ qnext) {
@@ -104,8 +106,9 @@ __global__ __launch_bounds__(PNT, 2) void pi_sweep_kernel(const float* __restric
         const int k0 = 16 * c;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            if (valid) x.a[s] = *reinterpret_cast<const v4f*>(acol + (size_t)(k0 + s) * B);
-            else x.a[s] = v4f{0.f, 0.f, 0.f, 0.f};
+            if (!valid) x.a[s] = v4f{0.f, 0.f, 0.f, 0.f};
+            else if (STREAM) x.a[s] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(acol + (size_t)(k0 + s) * B));
+            else x.a[s] = *reinterpret_cast<const v4f*>(acol + (size_t)(k0 + s) * B);
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) x.v[u] = *reinterpret_cast<const v4f*>(vrow + k0 + 4 * u);
@@ -234,8 +237,12 @@ hipError_t launch_power_iteration(const float* A, int64_t nblocks, int B, float 
         hipLaunchKernelGGL(pi_init_kernel, dim3(nb), dim3(PNT), 0, stream, V0, pool, B, src);
         hipLaunchKernelGGL(pi_unit_norms_kernel, dim3(nb), dim3(256), 0, stream, qa, B);
         for (int t = 1; t <= sweeps; ++t) {
-            hipLaunchKernelGGL(pi_sweep_kernel, dim3((B + 127) / 128, nb), dim3(PNT), 0, stream,
-                               A + (size_t)b0 * B * B, src, dst, B, eps, qa, qb);
+            if ((size_t)nblocks * B * B * sizeof(float) >= ((size_t)256 << 20))
+                hipLaunchKernelGGL(pi_sweep_kernel<true>, dim3((B + 127) / 128, nb), dim3(PNT), 0, stream,
+                                   A + (size_t)b0 * B * B, src, dst, B, eps, qa, qb);
+            else
+                hipLaunchKernelGGL(pi_sweep_kernel<false>, dim3((B + 127) / 128, nb), dim3(PNT), 0, stream,
+                                   A + (size_t)b0 * B * B, src, dst, B, eps, qa, qb);
             float* tv = src; src = dst; dst = tv;
             float* tq = qa; qa = qb; qb = tq;
         }
