@@ -413,13 +413,24 @@ hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
     return launch_tile<128>(g, gemm_split_blocks(g), stream);
 }
 
-// 128-wide tiles when they still give the chip enough workgroups, else 64-wide
+// 128-wide tiles when they still give the chip enough workgroups, else 64-wide.  A launch of fewer 128-tile
+// workgroups than fit the chip at once (1024) is resident as a whole, and it takes as long as the CU with the most
+// workgroups: when the workgroups fill less than 86 % of whole layers of one per CU (a Clenshaw product on 64
+// blocks of 512 is 640 workgroups: 2.5 per CU), 64 tiles, four times as many and dealt out as slots free up,
+// balance better than the bigger tile is faster (measured 10-16 % on such launches).
 int gemm_tile_edge(const GemmLaunch& g) {
     const int Md = g.M ? g.M : g.B, Nd = g.N ? g.N : g.B, Kd = g.K ? g.K : g.B;
     (void)Kd;                                     // the K loop only needs K % 16 == 0
     const bool big = Md % 128 == 0 && Nd % 128 == 0 &&
                      g.nblocks * g.nprob * (int64_t)(Md / 128) * (Nd / 128) >= 256;
-    return big ? 128 : 64;
+    if (!big) return 64;
+    const int64_t tm = Md / 128, tn = Nd / 128;
+    const int64_t w = g.nblocks * g.nprob * (g.sym ? tm * (tm + 1) / 2 : tm * tn);     // 128-tile workgroups
+    if (w < 1024) {
+        const int64_t layers = (w + 255) / 256;
+        if (100 * w < 86 * 256 * layers) return 64;
+    }
+    return 128;
 }
 
 // A launch of 128 tiles runs in rounds of RESIDENT workgroups (four per CU).  When the last round would be
