@@ -41,6 +41,20 @@ def test_scale_matches_oracle(dash, N, B, pool, sweeps):
     assert np.all(s > 0)
 
 
+def test_scale_on_a_stack_larger_than_the_cache(dash):
+    """From 256 MiB on the sweep reads the blocks with the non-temporal hint (a second instance of the kernel)."""
+    N, B, pool, sweeps, eps = 65, 1024, 16, 4, 1e-3
+    print(f"pi scale N={N} B={B} (streaming form)", flush=True)
+    A32, _, lam = workloads.spd_stack(N, B, -3.0, 0.0, seed=98, share_q=True)
+    V0 = workloads.start_vectors(B, pool, 99)
+    dash.set_power_iteration(_to_gpu(V0), sweeps)
+    s = dash.block_norms(_to_gpu(A32), eps=eps, scaling="power_iteration").cpu().numpy()
+    sample = [0, 31, N - 1]
+    s_ref = opi.power_iteration_scale(A32[sample].astype(np.float64), V0.astype(np.float64), sweeps, eps)
+    assert np.allclose(s[sample], s_ref, rtol=2e-5)
+    assert np.all(s <= 2 * (lam.max(axis=1) + eps) * (1 + 1e-5)) and np.all(s > 0)
+
+
 def test_scale_converges_to_twice_lambda_max(dash):
     N, B = 4, 256
     A32, _, lam = workloads.spd_stack(N, B, -2.0, 0.0, seed=95)

@@ -146,3 +146,43 @@ def test_step_chebyshev(dash):
                         inverse_root=lambda S_, p_, e_: ocheb.inverse_root_chebyshev(S_, p_, np.array(coef), a, b, eps=e_))
     assert rel_frobenius_error(X.cpu().numpy(), np.concatenate([ref["X_L"], ref["X_R"]])).max() < 1e-4
     assert rel_frobenius_error(U.cpu().numpy(), ref["U"]).max() < 1e-4
+
+
+def test_streaming_kernels_on_arrays_larger_than_the_caches(dash):
+    """Calls that touch more than the last-level cache holds take a second form of the HBM-bound kernels
+    (contiguous ranges per workgroup, non-temporal accesses).  80 blocks of 1024 x 1000 (ragged against the
+    range length) and of 1024 x 1024: grafting, parameter update of a length that is not a multiple of four,
+    Frobenius norms; against the float64 oracle on sampled blocks, the update bit for bit."""
+    import torch
+    N, B = 80, 1024
+    beta_g, eps_g = float(np.float32(0.999)), float(np.float32(1e-8))
+    rng = np.random.default_rng(3900)
+    sample = [0, 37, N - 1]
+    print("streaming forms: grafting", flush=True)
+    for cols in (1000, 1024):
+        G = (rng.standard_normal((N, B, cols)) * 1e-2).astype(np.float32)
+        U = rng.standard_normal((N, B, cols)).astype(np.float32)
+        A0 = (rng.random((N, B, cols)) * 1e-4).astype(np.float32)
+        Gd, Ud, Ad = _to_gpu(G), _to_gpu(U), _to_gpu(A0)
+        s_out = torch.zeros(N, device="cuda")
+        out = torch.empty_like(Ud)
+        dash.graft_scale(Gd, Ud, Ad, U_scaled=out, beta_g=beta_g, eps_g=eps_g, s_out=s_out)
+        torch.cuda.synchronize()
+        Acc_ref, s_ref = oshampoo.adam_graft(G[sample], U[sample], A0[sample], beta_g, eps_g)
+        assert np.allclose(Ad[sample].cpu().numpy(), Acc_ref, rtol=1e-6, atol=0)
+        assert np.allclose(s_out[sample].cpu().numpy(), s_ref, rtol=1e-5)
+        got = out[sample].cpu().numpy()
+        assert np.allclose(got, s_ref[:, None, None] * U[sample].astype(np.float64), rtol=2e-5, atol=0)
+        del Gd, Ud, Ad, out
+    print("streaming forms: parameter update", flush=True)
+    n = N * B * B - 5
+    t = rng.standard_normal(n).astype(np.float32)
+    tg = torch.from_numpy(t).cuda()
+    ug = _to_gpu(U).reshape(-1)[:n]
+    dash.apply_update(tg, ug, 0.25)
+    assert np.array_equal(tg.cpu().numpy(), t - np.float32(0.25) * U.reshape(-1)[:n])
+    print("streaming forms: norms", flush=True)
+    fro = dash.block_norms(_to_gpu(U), eps=1e-3, scaling="frobenius").cpu().numpy()
+    for b in sample:
+        ref = np.linalg.norm(U[b].astype(np.float64) + 1e-3 * np.eye(B))
+        assert abs(fro[b] - ref) <= 2e-6 * ref
