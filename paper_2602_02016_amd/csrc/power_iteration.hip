@@ -19,6 +19,7 @@
 //              A sweep also leaves, per workgroup, the partial sums of |w_j|^2 and v_j . w_j of its
 //              columns; the next sweep scales its input columns to unit length from them on the
 //              way in, so no pass over the vectors lies between two sweeps.
+//   pi_sweep16 the same sweep for pools of at most 16 vectors with v_mfma_f32_16x16x4_f32 (half the MFMA time)
 //   pi_finalize  per block, after the last sweep: q_j = v_j . w_j, s = 2 max_j q_j, 1/s and s^(-1/p)
 // Reductions are per block in a fixed order (no atomics): results do not depend on scheduling.
 #include "kernels.h"
@@ -180,6 +181,126 @@ __global__ __launch_bounds__(PNT, 2) void pi_sweep_kernel(const float* __restric
     }
 }
 
+// The same sweep for pools of at most 16 vectors, with v_mfma_f32_16x16x4_f32: half the matrix-core time per byte
+// of A, which is what limits the 32-wide form (its 32 x 32 products need about as long as the block needs on
+// HBM).  grid = (B/128, nblocks); the four wavefronts split K as above.  Lane (n', kq) of a wavefront loads, for
+// the half-chunk c of 16 k, the quads A[16c + 4kq + s][c0 + 64 hf + 4n' .. + 3] (s = 0..3, hf = 0, 1: 256 contiguous
+// bytes of four rows per load) and feeds element m of a quad to the MFMA of column group (hf, m); lane (j, kq)
+// supplies V[16c + 4kq + s][j], a quad of consecutive k of the pool-major vector.  MFMA step s contracts
+// k = 16c + 4kq + s over kq.  Accumulator register r of lane (n', kq) is pool row j = 4 kq + r, column
+// c0 + 64 hf + 4n' + m: the four groups of a half give a quad of consecutive columns again.  Pool rows 16..31 of V
+// and W are neither read nor written; their partial sums are written as zeros.
+template <bool STREAM>
+__global__ __launch_bounds__(PNT, 2) void pi_sweep16_kernel(const float* __restrict__ A, const float* __restrict__ V,
+                                                           float* __restrict__ W, int B, float eps,
+                                                           const float* __restrict__ qprev, float* __restrict__ qnext) {
+    constexpr int P16 = 16;
+    __shared__ float part[4][2][4][4][64];        // [wavefront][half][column group][accumulator register][lane]
+    __shared__ float inv_norm[P16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c0 = blockIdx.x * 128;
+    const int64_t b = blockIdx.y;
+    const int n = lane & 15, kq = lane >> 4;
+    const int QF = pi_q_floats(B), NG = pi_groups(B);
+    if (threadIdx.x < P16) {
+        const float* __restrict__ pp = qprev + b * QF + POOL;
+        float nn = 0.f;
+        for (int gidx = 0; gidx < NG; ++gidx) nn += pp[(size_t)gidx * 2 * POOL + threadIdx.x];
+        inv_norm[threadIdx.x] = nn > 0.f ? 1.f / sqrtf(nn) : 0.f;
+    }
+    __syncthreads();
+    const float my_inv = inv_norm[n];             // lane (j = n, kq) feeds pool column n
+    const bool valid1 = c0 + 64 < B;              // B is a multiple of 64: the last workgroup may own only 64 columns
+    const float* __restrict__ acol = A + (size_t)b * B * B + (size_t)(4 * kq) * B + c0 + 4 * n;
+    const float* __restrict__ Vb = V + (size_t)b * B * POOL;
+    const float* __restrict__ vrow = Vb + (size_t)n * B + 4 * kq;
+    v4f acc[2][4];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) acc[hf][m] = v4f{0.f, 0.f, 0.f, 0.f};
+    struct Half { v4f a[2][4]; v4f v; };          // four rows of A (a quad of columns in each half), four k of V
+    auto load = [&](int c, Half& x) {
+        const int k0 = 16 * c;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const float* p = acol + (size_t)(k0 + s) * B + 64 * hf;
+                if (hf == 1 && !valid1) x.a[hf][s] = v4f{0.f, 0.f, 0.f, 0.f};
+                else if (STREAM) x.a[hf][s] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+                else x.a[hf][s] = *reinterpret_cast<const v4f*>(p);
+            }
+        x.v = *reinterpret_cast<const v4f*>(vrow + k0);
+    };
+    auto mul = [&](const Half& x) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+                    acc[hf][m] = __builtin_amdgcn_mfma_f32_16x16x4f32(x.v[s] * my_inv, x.a[hf][s][m], acc[hf][m], 0, 0, 0);
+    };
+    const int nhalf = B / 16;
+    Half x0, x1;
+    int c = wave;
+    if (c < nhalf) load(c, x0);
+    while (c < nhalf) {
+        if (c + 4 < nhalf) load(c + 4, x1);
+        mul(x0);
+        c += 4;
+        if (c >= nhalf) break;
+        if (c + 4 < nhalf) load(c + 4, x0);
+        mul(x1);
+        c += 4;
+    }
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[wave][hf][m][r][lane] = acc[hf][m][r];
+    __syncthreads();
+    // wavefront w finishes accumulator register r = w: pool row j = 4 kq + w, one row per quarter-wavefront
+    float* __restrict__ Wb = W + (size_t)b * B * POOL;
+    float* __restrict__ qn = qnext + b * QF + POOL + (size_t)blockIdx.x * 2 * POOL;
+    const int r = wave, j = 4 * kq + r;
+    const float sj = inv_norm[j];
+    float nn = 0.f, vw = 0.f;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+        if (hf == 1 && !valid1) continue;
+        const size_t off = (size_t)j * B + c0 + 64 * hf + 4 * n;
+        v4f vhat = *reinterpret_cast<const v4f*>(Vb + off);
+        v4f out;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sum += part[w][hf][m][r][lane];
+            vhat[m] *= sj;
+            out[m] = sum + eps * vhat[m];
+            nn += out[m] * out[m];
+            vw += vhat[m] * out[m];
+        }
+        *reinterpret_cast<v4f*>(Wb + off) = out;
+    }
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) {
+        nn += __shfl_xor(nn, d);
+        vw += __shfl_xor(vw, d);
+    }
+    if (n == 0) {
+        qn[j] = nn;
+        qn[POOL + j] = vw;
+    }
+    if (threadIdx.x < POOL - P16) {               // the unused half of the pool
+        qn[P16 + threadIdx.x] = 0.f;
+        qn[POOL + P16 + threadIdx.x] = 0.f;
+    }
+}
+
 // grid = nblocks: q_j = v_j . w_j of the last sweep (unit v), s = 2 max_j q_j, 1/s and s^(-1/p)
 __global__ __launch_bounds__(64) void pi_finalize_kernel(float* __restrict__ qbuf, int B, int p, float* __restrict__ s,
                                                         float* __restrict__ inv_s, float* __restrict__ unscale) {
@@ -237,12 +358,16 @@ hipError_t launch_power_iteration(const float* A, int64_t nblocks, int B, float 
         hipLaunchKernelGGL(pi_init_kernel, dim3(nb), dim3(PNT), 0, stream, V0, pool, B, src);
         hipLaunchKernelGGL(pi_unit_norms_kernel, dim3(nb), dim3(256), 0, stream, qa, B);
         for (int t = 1; t <= sweeps; ++t) {
-            if ((size_t)nblocks * B * B * sizeof(float) >= ((size_t)256 << 20))
-                hipLaunchKernelGGL(pi_sweep_kernel<true>, dim3((B + 127) / 128, nb), dim3(PNT), 0, stream,
-                                   A + (size_t)b0 * B * B, src, dst, B, eps, qa, qb);
-            else
-                hipLaunchKernelGGL(pi_sweep_kernel<false>, dim3((B + 127) / 128, nb), dim3(PNT), 0, stream,
-                                   A + (size_t)b0 * B * B, src, dst, B, eps, qa, qb);
+            const bool big = (size_t)nblocks * B * B * sizeof(float) >= ((size_t)256 << 20);
+            const dim3 grid((B + 127) / 128, nb);
+            const float* Ab = A + (size_t)b0 * B * B;
+            if (pool <= 16) {
+                if (big) hipLaunchKernelGGL(pi_sweep16_kernel<true>, grid, dim3(PNT), 0, stream, Ab, src, dst, B, eps, qa, qb);
+                else hipLaunchKernelGGL(pi_sweep16_kernel<false>, grid, dim3(PNT), 0, stream, Ab, src, dst, B, eps, qa, qb);
+            } else {
+                if (big) hipLaunchKernelGGL(pi_sweep_kernel<true>, grid, dim3(PNT), 0, stream, Ab, src, dst, B, eps, qa, qb);
+                else hipLaunchKernelGGL(pi_sweep_kernel<false>, grid, dim3(PNT), 0, stream, Ab, src, dst, B, eps, qa, qb);
+            }
             float* tv = src; src = dst; dst = tv;
             float* tq = qa; qa = qb; qb = tq;
         }

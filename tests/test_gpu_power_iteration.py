@@ -41,9 +41,11 @@ def test_scale_matches_oracle(dash, N, B, pool, sweeps):
     assert np.all(s > 0)
 
 
-def test_scale_on_a_stack_larger_than_the_cache(dash):
-    """From 256 MiB on the sweep reads the blocks with the non-temporal hint (a second instance of the kernel)."""
-    N, B, pool, sweeps, eps = 65, 1024, 16, 4, 1e-3
+@pytest.mark.parametrize("pool", [16, 32])
+def test_scale_on_a_stack_larger_than_the_cache(dash, pool):
+    """From 256 MiB on the sweep reads the blocks with the non-temporal hint (second instances of the 16-wide and
+    of the 32-wide kernel)."""
+    N, B, sweeps, eps = 65, 1024, 4, 1e-3
     print(f"pi scale N={N} B={B} (streaming form)", flush=True)
     A32, _, lam = workloads.spd_stack(N, B, -3.0, 0.0, seed=98, share_q=True)
     V0 = workloads.start_vectors(B, pool, 99)
