@@ -426,7 +426,7 @@ int gemm_tile_edge(const GemmLaunch& g) {
     if (!big) return 64;
     const int64_t tm = Md / 128, tn = Nd / 128;
     const int64_t w = g.nblocks * g.nprob * (g.sym ? tm * (tm + 1) / 2 : tm * tn);     // 128-tile workgroups
-    if (w < 1024) {
+    if (g.half == HALF_NONE && w < 1024) {     // (fp32 launches: the 16-bit kernel has other residency)
         const int64_t layers = (w + 255) / 256;
         if (100 * w < 86 * 256 * layers) return 64;
     }
