@@ -1,7 +1,7 @@
 """Emulation of the mixed-precision recipe of the paper's Appendix A.3 (operands of each
 matmul rounded to half precision, accumulation and everything else in single precision),
-with fp16 (the paper's format), bf16, or split bf16 operands (two bf16 planes per operand,
-three products), applied to Newton-DB (Section 3.3) and Coupled-Newton (Section 3.2).
+with fp16 (the paper's format), bf16, or split bf16 operands (two bf16 planes per operand
+and three products, or three planes and six products), applied to Newton-DB (Section 3.3) and Coupled-Newton (Section 3.2).
 
 TEST INFRASTRUCTURE (see oracle/__init__.py).
 
@@ -66,9 +66,25 @@ def split_bf16(x):
     return hi, lo
 
 
+def split3_bf16(x):
+    """x ~ hi + mid + lo, three bf16 planes: hi = bf16(x), mid = bf16(x - hi), lo = bf16(x - hi - mid)
+    (as float32 values; the differences are exact in float32)."""
+    hi, mid = split_bf16(x)
+    with np.errstate(invalid="ignore"):
+        lo = round_bf16(_f32(_f32(x) - hi) - mid)
+    return hi, mid, lo
+
+
 def matmul_lowprec(A, B, fmt: str = "bf16") -> np.ndarray:
     """float32( half(A) @ half(B) ) with the product summed in float64.  fmt = 'bf16x3': both operands
-    split into two bf16 planes, product = A_lo B_hi + A_hi B_lo + A_hi B_hi (lo*lo dropped)."""
+    split into two bf16 planes, product = A_lo B_hi + A_hi B_lo + A_hi B_hi (lo*lo dropped).  fmt = 'bf16x6':
+    three planes each, the six plane products of weight 2^-16 and above:
+    A_lo B_hi + A_hi B_lo + A_mid B_mid + A_mid B_hi + A_hi B_mid + A_hi B_hi."""
+    if fmt == "bf16x6":
+        ah, am, al = (t.astype(np.float64) for t in split3_bf16(A))
+        bh, bm, bl = (t.astype(np.float64) for t in split3_bf16(B))
+        with np.errstate(over="ignore", invalid="ignore"):
+            return _f32(al @ bh + ah @ bl + am @ bm + am @ bh + ah @ bm + ah @ bh)
     if fmt == "bf16x3":
         ah, al = (t.astype(np.float64) for t in split_bf16(A))
         bh, bl = (t.astype(np.float64) for t in split_bf16(B))

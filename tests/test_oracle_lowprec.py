@@ -6,7 +6,7 @@ import torch
 import workloads
 from oracle import lowprec
 from oracle import newton_db as ondb
-from oracle.evd import rel_frobenius_error
+from oracle.evd import inverse_root_evd, rel_frobenius_error
 
 
 def test_round_bf16_exact_facts():
@@ -134,3 +134,40 @@ def test_split_product_is_far_closer_than_plain_bf16():
     full = (ah.astype(np.float64) + al) @ (bh.astype(np.float64) + bl)
     three = lowprec.matmul_lowprec(A, B, "bf16x3").astype(np.float64)
     assert np.allclose(three + al.astype(np.float64) @ bl, full, rtol=0, atol=1e-5)
+
+
+def test_split3_bf16_planes():
+    # three planes carry 24 significand bits: a float32 splits exactly (away from the subnormal range)
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(20000) * 10.0 ** rng.uniform(-6, 6, 20000)).astype(np.float32)
+    hi, mid, lo = lowprec.split3_bf16(x)
+    assert np.array_equal(hi, lowprec.round_bf16(x))
+    assert np.array_equal((hi.astype(np.float64) + mid) + lo, x.astype(np.float64))
+    assert np.all(np.abs(mid) <= np.abs(x) * 2.0 ** -8) and np.all(np.abs(lo) <= np.abs(x) * 2.0 ** -16)
+
+
+def test_six_term_product_reaches_float32_accuracy():
+    rng = np.random.default_rng(6)
+    A = rng.standard_normal((96, 96)).astype(np.float32)
+    B = rng.standard_normal((96, 96)).astype(np.float32)
+    exact = A.astype(np.float64) @ B.astype(np.float64)
+    e6 = rel_frobenius_error(lowprec.matmul_lowprec(A, B, "bf16x6"), exact)[0]
+    e3 = rel_frobenius_error(lowprec.matmul_lowprec(A, B, "bf16x3"), exact)[0]
+    e32 = rel_frobenius_error((A @ B).astype(np.float32), exact)[0]
+    assert e6 < 1.5e-7 and e6 < e3 / 30 and e6 < 4 * max(e32, 3e-8)
+    # the six terms are the product of the plane sums minus the three dropped ones (mid*lo, lo*mid, lo*lo)
+    ah, am, al = (t.astype(np.float64) for t in lowprec.split3_bf16(A))
+    bh, bm, bl = (t.astype(np.float64) for t in lowprec.split3_bf16(B))
+    six = al @ bh + ah @ bl + am @ bm + am @ bh + ah @ bm + ah @ bh
+    assert np.allclose(six + am @ bl + al @ bm + al @ bl, exact, rtol=0, atol=1e-12)
+    assert np.abs(six - exact).max() < 96 * 3 * 2.0 ** -24 * 16      # dropped terms: 2^-24 relative each
+
+
+def test_ndb_with_six_term_products_matches_the_float32_floor():
+    A32, _, _ = workloads.spd_stack(2, 64, -3.0, 0.0, seed=17)
+    X = inverse_root_evd(A32.astype(np.float64), 4)
+    e6 = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32, 4, 14, rounding="bf16x6"), X).max()
+    e32 = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32, 4, 14, rounding="none"), X).max()
+    e3 = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32, 4, 14, rounding="bf16x3"), X).max()
+    print(f"NDB p=4 k=14 kappa=1e3: no rounding {e32:.2e}, bf16x6 {e6:.2e}, bf16x3 {e3:.2e}")
+    assert e6 < 3 * e32 + 1e-6 and e3 > 3 * e6
