@@ -93,6 +93,7 @@ def sweep(dash, only_16bit=False):
             cases.append(("coupled_newton", pp, 10, "fp32"))
         if cfg == "cfg5":
             cases += [("newton_db", 4, 10, "bf16"), ("newton_db", 4, 10, "fp16"), ("newton_db", 4, 10, "bf16x3"),
+                      ("newton_db", 4, 10, "bf16x6"),
                       ("coupled_newton", 4, 10, "fp16"), ("chebyshev", 4, 16, "fp16")]
         if only_16bit:
             cases = [c for c in cases if c[3] != "fp32"]
@@ -326,6 +327,32 @@ def main():
                       "rel_diff_to_headline_roots": diff}
         del Xp
 
+    # the same roots with three-plane split bf16 operands (DASH_BF16X6: six bf16 MFMA products per matmul, fp32
+    # accuracy; context, not the headline): time, difference to the fp32 roots, and the residual
+    # ||X^4 (A + eps I) - I||_F / sqrt(B) of both, formed in float64 on one block
+    x6_variant = None
+    if reps > 0:
+        X6 = torch.empty_like(S)
+        dash.inverse_root(S, X6, p=p, iters=k, eps=eps, precision="bf16x6", nonfinite_out=nf)
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(reps):
+            dash.inverse_root(S, X6, p=p, iters=k, eps=eps, precision="bf16x6", nonfinite_out=nf)
+        torch.cuda.synchronize()
+        x6_ms = (time.perf_counter() - t3) * 1e3 / reps
+
+        def residual(Xb, Ab):
+            X64 = Xb.double()
+            X2 = X64 @ X64
+            R = X2 @ X2 @ (Ab.double() + eps * torch.eye(B, device=dev, dtype=torch.float64)) - torch.eye(B, device=dev, dtype=torch.float64)
+            return float(R.norm() / B ** 0.5)
+        d6 = float(((X6[:2] - X[:2]).double().flatten(1).norm(dim=1) / X[:2].double().flatten(1).norm(dim=1)).max())
+        x6_variant = {"precision": "bf16x6 (operands as three bf16 planes, six plane products, fp32 accumulation)",
+                      "ndb_iters": k, "ms": x6_ms, "blocks_per_s": 2 * N / (x6_ms * 1e-3),
+                      "speedup_over_fp32_roots": root_ms / x6_ms, "rel_diff_to_headline_roots": d6,
+                      "residual_fp32": residual(X[0], S[0]), "residual_bf16x6": residual(X6[0], S[0])}
+        del X6
+
     ms_per_step = dt * 1e3 / args.steps
     blocks_per_s = 2 * N * args.steps / dt
 
@@ -388,6 +415,7 @@ def main():
                                       "it is a throughput figure, not a utilisation"},
     }
     out["inverse_root_power_iteration_scaling"] = pi_variant
+    out["inverse_root_bf16x6"] = x6_variant
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(min(args.cpu_sample_blocks, N), B, beta, eps, p, args.cpu_repeats)
     log(f"step {ms_per_step:.2f} ms, {blocks_per_s:.0f} factor blocks/s, matmul kernel {achieved_tflops:.1f} TFLOP/s "

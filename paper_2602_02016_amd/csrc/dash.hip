@@ -106,6 +106,7 @@ int f32_buffers(dash_method m, dash_precision prec) {
 int bf16_buffers(dash_method m, dash_precision prec) {
     if (prec == DASH_FP32) return 0;
     if (prec == DASH_BF16X3) return 10;            // Newton-DB only: five iterates, a high and a low plane each
+    if (prec == DASH_BF16X6) return 15;            // Newton-DB only: five iterates, three planes each
     if (m == DASH_COUPLED_NEWTON) return 9;
     return m == DASH_NEWTON_DB ? 5 : 3;
 }
@@ -165,7 +166,7 @@ dash_status collect_events(dash_ctx* c) {
 GemmProblem problem(const float* A, const float* B, const float* D, float* C, const float* mult, float alpha,
                     float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.C2 = nullptr; p.C2h = nullptr; p.A2 = nullptr; p.B2 = nullptr; p.Cl = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
+    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.C2 = nullptr; p.C2h = nullptr; p.A2 = nullptr; p.B2 = nullptr; p.Cl = nullptr; p.A3 = nullptr; p.B3 = nullptr; p.Cl2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
@@ -174,7 +175,7 @@ GemmProblem problem(const float* A, const float* B, const float* D, float* C, co
 GemmProblem problem_h(const bf16_t* Ah, const bf16_t* Bh, const float* D, float* C, bf16_t* Ch, const float* mult,
                       float alpha, float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.C2 = nullptr; p.C2h = nullptr; p.A2 = nullptr; p.B2 = nullptr; p.Cl = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
+    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.C2 = nullptr; p.C2h = nullptr; p.A2 = nullptr; p.B2 = nullptr; p.Cl = nullptr; p.A3 = nullptr; p.B3 = nullptr; p.Cl2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
@@ -326,19 +327,22 @@ dash_status ndb_call(dash_ctx* c, float* buf[5], int mi, int64_t n, int B, int i
 // and every epilogue (1.5 I - 0.5 Z Y, un-scaling) are fp32.
 // hb: five bf16 buffers; fy: one fp32 buffer.  mi: index in hb of the bf16 copy of M when
 // the call is chained (then fy holds M in fp32).
-dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], bf16_t** lb, float* fy, int mi, int64_t n, int B, int iters,
+dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], bf16_t** lb, bf16_t** lb2, float* fy, int mi, int64_t n, int B, int iters,
                           bool keepY, bool m_needs_init, const float* A_in, float eps, const float* inv_s,
                           float* final_out, const float* unscale, int32_t* nonfinite, int* out_idx) {
     // lb != null: split-operand mode, every iterate is kept as a high plane hb[i] and a low plane lb[i]
-    // (x ~ hi + lo), products are A_lo B_hi + A_hi B_lo + A_hi B_hi
+    // (x ~ hi + lo), products are A_lo B_hi + A_hi B_lo + A_hi B_hi; lb2 != null as well: three planes
+    // (x ~ hi + mid + lo, lb the middle and lb2 the lowest plane) and six-term products
     hipStream_t st = c->stream;
     bool used[5] = {false, false, false, false, false};
     auto grab = [&]() { for (int i = 0; i < 5; ++i) if (!used[i]) { used[i] = true; return i; } return -1; };
     auto lo = [&](int i) -> bf16_t* { return lb ? lb[i] : nullptr; };
+    auto lo2 = [&](int i) -> bf16_t* { return lb2 ? lb2[i] : nullptr; };
     // product of iterates ia, ib -> iterate ic (16-bit planes) and/or Cf (fp32)
     auto prod = [&](int ia, int ib, float* Cf, int ic, const float* mult, float alpha, float gamma) {
         GemmProblem p = problem_h(hb[ia], hb[ib], nullptr, Cf, ic >= 0 ? hb[ic] : nullptr, mult, alpha, 0.f, gamma);
         p.A2 = lo(ia); p.B2 = lo(ib); p.Cl = ic >= 0 ? lo(ic) : nullptr;
+        p.A3 = lo2(ia); p.B3 = lo2(ib); p.Cl2 = ic >= 0 ? lo2(ic) : nullptr;
         return p;
     };
     int y, z;
@@ -348,7 +352,7 @@ dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], bf16_t** lb, float* fy, in
         // the result (iters == 1, p == 2) its fp32 value goes to fy
         HIP_TRY(c, launch_scale_shift(A_in, n, B, eps, inv_s, 1.f, 0.f, nullptr, -0.5f, 1.5f,
                                       (iters == 1 && !keepY) ? fy : nullptr, hb[y], hb[z], nullptr, st, c->half_kind,
-                                      lo(y), lo(z)));
+                                      lo(y), lo(z), lo2(y), lo2(z)));
     } else {
         used[mi] = true; y = mi; z = grab();
         if (iters == 1 && !keepY && final_out) {
@@ -360,7 +364,7 @@ dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], bf16_t** lb, float* fy, in
             return DASH_OK;
         }
         HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, nullptr, -0.5f, 1.5f, nullptr, 0.f, 0.f, nullptr, hb[z], nullptr,
-                                      nullptr, st, c->half_kind, lo(z), nullptr));
+                                      nullptr, st, c->half_kind, lo(z), nullptr, lo2(z), nullptr));
     }
     if (iters == 1) {
         if (keepY) {
@@ -676,19 +680,21 @@ dash_status dash_gemm_batched(dash_ctx* c, int transA, int transB, const float* 
     if (N == 0) return DASH_OK;
     if (!A || !Bm || !C) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     if (!D && beta != 0.f) return fail(c, DASH_ERR_INVALID_ARG, "beta != 0 needs D");
-    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32 && precision != DASH_BF16X3)
+    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32 && precision != DASH_BF16X3 &&
+        precision != DASH_BF16X6)
         return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
     c->half_kind = precision == DASH_FP16_ACC32 ? HALF_FP16 : HALF_BF16;
-    const bool split = precision == DASH_BF16X3;
+    const bool planes3 = precision == DASH_BF16X6;
+    const bool split = precision == DASH_BF16X3 || planes3;
     const size_t bytes = (size_t)N * B * B * sizeof(float);
     if (overlap(C, A, bytes) || overlap(C, Bm, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "C overlaps an operand");
     if (D && D != C && overlap(C, D, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "D must equal C or be disjoint from it");
     HIP_TRY(c, hipSetDevice(c->device));
     if (precision == DASH_FP32)
         return gemm1(c, problem(A, Bm, D, C, nullptr, alpha, beta, gamma, transA ? 1 : 0, transB ? 1 : 0), N, B);
-    // 16-bit operands: round both operand stacks into the workspace (two 16-bit stacks per chunk, four in
-    // split mode: a high and a low plane each), then multiply
-    const size_t mat = (size_t)B * B, per = (split ? 4 : 2) * mat * sizeof(bf16_t);
+    // 16-bit operands: round both operand stacks into the workspace (two 16-bit stacks per chunk, four or six in
+    // the split modes: two or three planes each), then multiply
+    const size_t mat = (size_t)B * B, per = (planes3 ? 6 : split ? 4 : 2) * mat * sizeof(bf16_t);
     if (!c->ws || c->ws_bytes < per) return fail(c, DASH_ERR_WORKSPACE, "workspace holds %zu bytes, one block needs %zu", c->ws_bytes, per);
     int64_t chunk = (int64_t)(c->ws_bytes / per);
     if (chunk > N) chunk = N;
@@ -699,11 +705,14 @@ dash_status dash_gemm_batched(dash_ctx* c, int transA, int transB, const float* 
         bf16_t* Bh = Ah + (size_t)nb * mat;
         bf16_t* Al = split ? Bh + (size_t)nb * mat : nullptr;
         bf16_t* Bl = split ? Al + (size_t)nb * mat : nullptr;
-        HIP_TRY(c, launch_scale_shift(A + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Ah, nullptr, nullptr, c->stream, c->half_kind, Al, nullptr));
-        HIP_TRY(c, launch_scale_shift(Bm + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Bh, nullptr, nullptr, c->stream, c->half_kind, Bl, nullptr));
+        bf16_t* Al2 = planes3 ? Bl + (size_t)nb * mat : nullptr;
+        bf16_t* Bl2 = planes3 ? Al2 + (size_t)nb * mat : nullptr;
+        HIP_TRY(c, launch_scale_shift(A + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Ah, nullptr, nullptr, c->stream, c->half_kind, Al, nullptr, Al2, nullptr));
+        HIP_TRY(c, launch_scale_shift(Bm + o, nb, B, 0.f, nullptr, 1.f, 0.f, nullptr, 0.f, 0.f, nullptr, Bh, nullptr, nullptr, c->stream, c->half_kind, Bl, nullptr, Bl2, nullptr));
         GemmProblem pr = problem_h(Ah, Bh, D ? D + o : nullptr, C + o, nullptr, nullptr, alpha, beta, gamma,
                                    transA ? 1 : 0, transB ? 1 : 0);
         pr.A2 = Al; pr.B2 = Bl;
+        pr.A3 = Al2; pr.B3 = Bl2;
         DASH_TRY(gemm1(c, pr, nb, B, nullptr, 1));
     }
     return DASH_OK;
@@ -910,9 +919,10 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         return fail(c, DASH_ERR_INVALID_ARG, "bad method");
     if (method == DASH_COUPLED_NEWTON && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Coupled-Newton needs iters >= 1");
     if ((int)scaling < 0 || (int)scaling > 3) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
-    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32 && precision != DASH_BF16X3)
+    if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32 && precision != DASH_BF16X3 &&
+        precision != DASH_BF16X6)
         return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
-    if (precision == DASH_BF16X3 && method != DASH_NEWTON_DB)
+    if ((precision == DASH_BF16X3 || precision == DASH_BF16X6) && method != DASH_NEWTON_DB)
         return fail(c, DASH_ERR_UNSUPPORTED, "split-operand bf16 is built for Newton-DB only");
     c->half_kind = precision == DASH_FP16_ACC32 ? HALF_FP16 : HALF_BF16;
     if (method == DASH_NEWTON_DB && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Newton-DB needs iters >= 1");
@@ -948,7 +958,8 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         float* inv_s = sc.inv_s;
         float* unscale = sc.unscale;
         float* buf[9] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-        bf16_t* hbuf[10] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+        bf16_t* hbuf[15] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                            nullptr, nullptr, nullptr, nullptr, nullptr};
         for (int i = 0; i < nbuf; ++i) buf[i] = (float*)cv.take((size_t)nb * mat * sizeof(float));
         for (int i = 0; i < nhbuf; ++i) hbuf[i] = (bf16_t*)cv.take((size_t)nb * mat * sizeof(bf16_t));
         if (!sc_ok || (nbuf && !buf[nbuf - 1]) || (nhbuf && !hbuf[nhbuf - 1]))
@@ -968,13 +979,15 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
             DASH_TRY(cn_chunk(c, buf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf));
         } else if (lowp && method == DASH_NEWTON_DB) {
             int idx = -1;
-            bf16_t** lows = precision == DASH_BF16X3 ? hbuf + 5 : nullptr;     // low planes of the split mode
+            const bool planes3 = precision == DASH_BF16X6;
+            bf16_t** lows = precision == DASH_BF16X3 || planes3 ? hbuf + 5 : nullptr;     // low (middle) planes of the split modes
+            bf16_t** lows2 = planes3 ? hbuf + 10 : nullptr;                                // lowest planes of the three-plane mode
             if (p == 2) {
-                DASH_TRY(ndb_call_bf16(c, hbuf, lows, buf[0], -1, nb, B, iters, false, true, Ac, eps, inv_s, Xc, unscale, nf, &idx));
+                DASH_TRY(ndb_call_bf16(c, hbuf, lows, lows2, buf[0], -1, nb, B, iters, false, true, Ac, eps, inv_s, Xc, unscale, nf, &idx));
             } else {
-                DASH_TRY(ndb_call_bf16(c, hbuf, lows, buf[0], -1, nb, B, iters, true, true, Ac, eps, inv_s, nullptr, nullptr, nullptr, &idx));
+                DASH_TRY(ndb_call_bf16(c, hbuf, lows, lows2, buf[0], -1, nb, B, iters, true, true, Ac, eps, inv_s, nullptr, nullptr, nullptr, &idx));
                 int idx2 = -1;
-                DASH_TRY(ndb_call_bf16(c, hbuf, lows, buf[0], idx, nb, B, iters, false, false, nullptr, 0.f, nullptr, Xc, unscale, nf, &idx2));
+                DASH_TRY(ndb_call_bf16(c, hbuf, lows, lows2, buf[0], idx, nb, B, iters, false, false, nullptr, 0.f, nullptr, Xc, unscale, nf, &idx2));
             }
         } else if (lowp) {
             DASH_TRY(clenshaw_chunk_bf16(c, buf, hbuf, Ac, Xc, nb, B, iters, cheb_coeffs, cheb_a, cheb_b, eps, inv_s, unscale, nf));

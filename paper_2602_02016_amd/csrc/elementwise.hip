@@ -120,7 +120,9 @@ __global__ __launch_bounds__(NT) void scale_shift_kernel(const float* __restrict
                                                         float* __restrict__ out2, unsigned short* __restrict__ h1,
                                                         unsigned short* __restrict__ h2, int32_t* nonfinite, int half,
                                                         unsigned short* __restrict__ l1,
-                                                        unsigned short* __restrict__ l2) {
+                                                        unsigned short* __restrict__ l2,
+                                                        unsigned short* __restrict__ ll1,
+                                                        unsigned short* __restrict__ ll2) {
     const int64_t b = blockIdx.y;
     const int f = blockIdx.x * NT + threadIdx.x;     // float4 index inside the block
     const int qpr = B / 4;
@@ -165,6 +167,25 @@ __global__ __launch_bounds__(NT) void scale_shift_kernel(const float* __restrict
 #pragma unroll
         for (int i = 0; i < 4; ++i) t[i] = to_half(o2[i] - from_half(to_half(o2[i], half), half), half);
         *reinterpret_cast<v4s*>(l2 + off) = t;
+    }
+    // third planes, x ~ hi + mid + lo: lo = round(x - hi - mid)
+    if (ll1) {
+        v4s t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float r1 = o1[i] - from_half(to_half(o1[i], half), half);
+            t[i] = to_half(r1 - from_half(to_half(r1, half), half), half);
+        }
+        *reinterpret_cast<v4s*>(ll1 + off) = t;
+    }
+    if (ll2) {
+        v4s t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float r2 = o2[i] - from_half(to_half(o2[i], half), half);
+            t[i] = to_half(r2 - from_half(to_half(r2, half), half), half);
+        }
+        *reinterpret_cast<v4s*>(ll2 + off) = t;
     }
     if (nonfinite && bad) nonfinite[b] = 1;
 }
@@ -396,7 +417,8 @@ hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, i
 
 hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult, float a1,
                               float g1, float* out1, float a2, float g2, float* out2, void* h1, void* h2,
-                              int32_t* nonfinite, hipStream_t stream, int half, void* l1, void* l2) {
+                              int32_t* nonfinite, hipStream_t stream, int half, void* l1, void* l2, void* ll1,
+                              void* ll2) {
     const unsigned gx = (unsigned)(((size_t)B * B / 4 + NT - 1) / NT);
     for (int64_t b0 = 0; b0 < nblocks; b0 += 65535) {
         const int64_t nb = nblocks - b0 < 65535 ? nblocks - b0 : 65535;
@@ -406,7 +428,9 @@ hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps
                            out2 ? out2 + o : nullptr, h1 ? static_cast<unsigned short*>(h1) + o : nullptr,
                            h2 ? static_cast<unsigned short*>(h2) + o : nullptr, nonfinite ? nonfinite + b0 : nullptr,
                            half, l1 ? static_cast<unsigned short*>(l1) + o : nullptr,
-                           l2 ? static_cast<unsigned short*>(l2) + o : nullptr);
+                           l2 ? static_cast<unsigned short*>(l2) + o : nullptr,
+                           ll1 ? static_cast<unsigned short*>(ll1) + o : nullptr,
+                           ll2 ? static_cast<unsigned short*>(ll2) + o : nullptr);
     }
     return hipGetLastError();
 }

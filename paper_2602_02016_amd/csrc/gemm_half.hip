@@ -216,11 +216,21 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     // Split-operand mode (A2, B2 given): every operand is the sum of a high and a low 16-bit plane
     // (x ~ hi + lo, hi = round(x), lo = round(x - hi)) and the product is A_lo B_hi + A_hi B_lo + A_hi B_hi,
     // i.e. one product whose K runs over three segments with different plane pairs (lo*lo is dropped).
-    const int nseg = P.A2 ? 3 : 1;
-    const u16* __restrict__ Ahi = static_cast<const u16*>(P.A) + boff;
-    const u16* __restrict__ Bhi = static_cast<const u16*>(P.B) + boff;
-    const u16* __restrict__ Alo = P.A2 ? static_cast<const u16*>(P.A2) + boff : Ahi;
-    const u16* __restrict__ Blo = P.B2 ? static_cast<const u16*>(P.B2) + boff : Bhi;
+    // Three-plane mode (A3, B3 given as well, x ~ hi + mid + lo): the six plane products of weight 2^-16 and
+    // above, A_lo B_hi + A_hi B_lo + A_mid B_mid + A_mid B_hi + A_hi B_mid + A_hi B_hi.
+    // Segments are numbered so that every mode runs a tail of the same list, small terms first:
+    //   0: A3 B   1: A B3   2: A2 B2   3: A2 B   4: A B2   5: A B
+    const int nseg = P.A3 ? 6 : P.A2 ? 3 : 1;
+    // (the plane pointers are fetched from the launch arguments when a segment begins: six more pointers held
+    // in scalar registers through the K loop would not fit)
+    auto seg_a = [&](int sg) {
+        const void* q = sg == 0 ? P.A3 : (sg == 2 || sg == 3) ? P.A2 : P.A;
+        return static_cast<const char*>(q) + boff * sizeof(u16);
+    };
+    auto seg_b = [&](int sg) {
+        const void* q = sg == 1 ? P.B3 : (sg == 2 || sg == 4) ? P.B2 : P.B;
+        return static_cast<const char*>(q) + boff * sizeof(u16);
+    };
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = (wave / HCfg<TILE>::WC) * HCfg<TILE>::WT, wn = (wave % HCfg<TILE>::WC) * HCfg<TILE>::WT;
@@ -242,13 +252,13 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     HFrag<TILE, B_KC, MT> frb;
     fra.init(wm, lane);
     frb.init(wn, lane);
-    // The slabs are requested in order, segment after segment (the small terms are summed first:
-    // A_lo B_hi, A_hi B_lo, A_hi B_hi; a plain product is the last segment alone).  The uniform base
+    // The slabs are requested in order, segment after segment (the small terms are summed first; a plain
+    // product is the last segment alone).  The uniform base
     // addresses of the next slab are carried along and stepped, so the K loop holds no address set-up.
     const size_t stepa = hslab_base<A_KC>(B, HBK), stepb = hslab_base<B_KC>(B, HBK);
-    int seg_next = nseg == 1 ? 2 : 0, ks_next = 0;
-    const char* pa = reinterpret_cast<const char*>(seg_next == 0 ? Alo : Ahi);
-    const char* pb = reinterpret_cast<const char*>(Bhi);
+    int seg_next = 6 - nseg, ks_next = 0;
+    const char* pa = seg_a(seg_next);
+    const char* pb = seg_b(seg_next);
     auto load_next = [&](char* dst) {
         hdma_load<TILE>(pa, offa, dst, wave);
         hdma_load<TILE>(pb, offb, dst + SLAB, wave);
@@ -258,8 +268,8 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
         } else {
             ks_next = 0;
             ++seg_next;
-            pa = reinterpret_cast<const char*>(Ahi);
-            pb = reinterpret_cast<const char*>(seg_next == 1 ? Blo : Bhi);
+            pa = seg_a(seg_next);
+            pb = seg_b(seg_next);
         }
     };
     // Fragments of MFMA step st live in register set st % 2; those of step st + 1 are requested before the MFMAs
@@ -334,6 +344,7 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     u16* __restrict__ Hb = P.Ch ? static_cast<u16*>(P.Ch) + boff : nullptr;
     u16* __restrict__ H2b = P.C2h ? static_cast<u16*>(P.C2h) + boff : nullptr;
     u16* __restrict__ Lb = P.Cl ? static_cast<u16*>(P.Cl) + boff : nullptr;    // low plane of the result
+    u16* __restrict__ L2b = P.Cl2 ? static_cast<u16*>(P.Cl2) + boff : nullptr; // third plane (with Lb only)
     const float a2 = P.a2, g2 = P.g2;
     // symmetric mode: an off-diagonal tile is also written transposed
     const bool mirror = g.sym && ti != tj;
@@ -385,14 +396,17 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
                 }
                 if (Cb) *reinterpret_cast<v4f*>(Cb + off) = v;
                 if (Hb || Lb) {
-                    v4s h, lo;
+                    v4s h, lo, lo2;
 #pragma unroll
                     for (int m = 0; m < 4; ++m) {
                         h[m] = H::from_float(v[m]);
-                        lo[m] = H::from_float(v[m] - H::to_float(h[m]));
+                        const float rest = v[m] - H::to_float(h[m]);
+                        lo[m] = H::from_float(rest);
+                        lo2[m] = H::from_float(rest - H::to_float(lo[m]));
                     }
                     if (Hb) *reinterpret_cast<v4s*>(Hb + off) = h;
                     if (Lb) *reinterpret_cast<v4s*>(Lb + off) = lo;
+                    if (L2b) *reinterpret_cast<v4s*>(L2b + off) = lo2;
                 }
                 if (H2b) {
                     v4s h2;
@@ -420,14 +434,17 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
                 const size_t moff = (size_t)col * B + row;
                 if (Cb) *reinterpret_cast<v4f*>(Cb + moff) = v;
                 if (Hb || Lb) {
-                    v4s h, lo;
+                    v4s h, lo, lo2;
 #pragma unroll
                     for (int m = 0; m < 4; ++m) {
                         h[m] = H::from_float(v[m]);
-                        lo[m] = H::from_float(v[m] - H::to_float(h[m]));
+                        const float rest = v[m] - H::to_float(h[m]);
+                        lo[m] = H::from_float(rest);
+                        lo2[m] = H::from_float(rest - H::to_float(lo[m]));
                     }
                     if (Hb) *reinterpret_cast<v4s*>(Hb + moff) = h;
                     if (Lb) *reinterpret_cast<v4s*>(Lb + moff) = lo;
+                    if (L2b) *reinterpret_cast<v4s*>(L2b + moff) = lo2;
                 }
                 if (H2b) {
                     v4s h2;

@@ -30,6 +30,11 @@ struct GemmProblem {
     const void* A2;
     const void* B2;
     void* Cl;
+    // three-plane mode: A3, B3 are third (lowest) planes (null = two planes), Cl2 receives the third plane of
+    // the result; the product then has six segments (see gemm_half.hip)
+    const void* A3;
+    const void* B3;
+    void* Cl2;
     float a2, g2;
     const float* mult;
     float alpha, beta, gamma;
@@ -77,7 +82,8 @@ hipError_t launch_finalize_scale(const float* partial, int64_t nblocks, int P, i
 hipError_t launch_scale_shift(const float* in, int64_t nblocks, int B, float eps, const float* mult,
                               float a1, float g1, float* out1, float a2, float g2, float* out2,
                               void* h1, void* h2, int32_t* nonfinite, hipStream_t stream, int half = HALF_BF16,
-                              void* l1 = nullptr, void* l2 = nullptr);   // l1, l2: low planes of o1, o2 (split mode)
+                              void* l1 = nullptr, void* l2 = nullptr,    // l1, l2: low planes of o1, o2 (split mode)
+                              void* ll1 = nullptr, void* ll2 = nullptr); // third planes (three-plane mode)
 
 // Multi-Power-Iteration scaling (power_iteration.hip): s_b = 2 * lambda_PI(A_b + eps I) from
 // `sweeps` passes over the block with a pool of `pool` (<= 32) start vectors V0 ([B][pool]
