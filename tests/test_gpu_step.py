@@ -23,13 +23,15 @@ def _to_gpu(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+@pytest.mark.parametrize("precision", ["fp32", "bf16x6"])
 @pytest.mark.parametrize("N,B,warm", [(4, 128, 6), (3, 256, 4), (2, 512, 3)])
-def test_step_against_oracle(dash, N, B, warm):
+def test_step_against_oracle(dash, N, B, warm, precision):
     """Factors are EMAs of seeded N(0, 1e-2^2) gradients (Wishart-like, well conditioned once
     a few gradients are in); Newton-DB p=4 with k=12 is converged there, so the GPU step
-    must agree with the EVD-based oracle step to fp32 accuracy."""
+    must agree with the EVD-based oracle step to fp32 accuracy -- with fp32 MFMA operands and with
+    three-plane split bf16 operands, to the same bar."""
     import torch
-    print(f"step N={N} B={B}", flush=True)
+    print(f"step N={N} B={B} {precision}", flush=True)
     beta, eps = 0.95, 1e-6
     S = torch.zeros(2 * N, B, B, device="cuda")
     X = torch.zeros_like(S)
@@ -41,7 +43,7 @@ def test_step_against_oracle(dash, N, B, warm):
         dash.accumulate_factors(_to_gpu(G), S[:N], S[N:], beta)
         L64, R64 = oshampoo.accumulate_factors(G, L64, R64, beta)
     G = workloads.gradient_stack(N, B, 3000 + warm)
-    dash.step(_to_gpu(G), S, X, U, beta=beta, eps=eps, p=4, iters=12, nonfinite_out=nf)
+    dash.step(_to_gpu(G), S, X, U, beta=beta, eps=eps, p=4, iters=12, nonfinite_out=nf, precision=precision)
     ref = oshampoo.step(G, L64, R64, beta=beta, eps=eps, p=4)
     torch.cuda.synchronize()
     eS = rel_frobenius_error(S.cpu().numpy(), np.concatenate([ref["L"], ref["R"]])).max()
