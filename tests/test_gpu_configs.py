@@ -247,7 +247,16 @@ def test_config5_illconditioned_table(dash):
             Xj = X[sample[j]].cpu().numpy()
             assert bool(nf[sample[j]].item()) == (not np.isfinite(Xj).all())
             e16.append(rel_frobenius_error(Xj, (Q * lam ** (-1.0 / p)) @ Q.T)[0] if np.isfinite(Xj).all() else float("nan"))
+        # three-plane split bf16 operands: the same bar as fp32
+        torch.cuda.synchronize(); t1 = time.time()
+        dash.inverse_root(A, X, p=p, iters=k, eps=eps, precision="bf16x6", nonfinite_out=nf, workspace_max_bytes=ws_cap)
+        torch.cuda.synchronize(); ms6 = (time.time() - t1) * 1e3
+        assert int(nf.sum().item()) == 0
+        e6 = [rel_frobenius_error(X[sample[j]].cpu().numpy(), (Q * lam ** (-1.0 / p)) @ Q.T)[0]
+              for j, (lam, Q, s) in enumerate(eig)]
         print(f"cfg5: {k:2d} | {max(e32):.3e} | {max(emod):.3e} | {np.nanmax(e16) if not np.all(np.isnan(e16)) else float('nan'):.3e} "
-              f"| {flagged:4d} | {ms32:7.0f} | {ms16:7.0f}", flush=True)
+              f"| {flagged:4d} | {ms32:7.0f} | {ms16:7.0f} | bf16x6 vs EVD {max(e6):.3e} in {ms6:7.0f} ms", flush=True)
         for a_, m_ in zip(e32, emod):
             assert abs(a_ - m_) <= 0.1 * m_ + floor, (k, a_, m_, floor)
+        for a_, m_ in zip(e6, emod):
+            assert abs(a_ - m_) <= 0.1 * m_ + floor, ("bf16x6", k, a_, m_, floor)
