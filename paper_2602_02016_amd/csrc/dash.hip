@@ -106,7 +106,7 @@ int f32_buffers(dash_method m, dash_precision prec) {
 int bf16_buffers(dash_method m, dash_precision prec) {
     if (prec == DASH_FP32) return 0;
     if (prec == DASH_BF16X3) return 10;            // Newton-DB only: five iterates, a high and a low plane each
-    if (prec == DASH_BF16X6) return 15;            // Newton-DB only: five iterates, three planes each
+    if (prec == DASH_BF16X6) return m == DASH_NEWTON_DB ? 15 : 9;   // five iterates (Newton-DB) or S and two B_k (Clenshaw), three planes each
     if (m == DASH_COUPLED_NEWTON) return 9;
     return m == DASH_NEWTON_DB ? 5 : 3;
 }
@@ -412,24 +412,34 @@ dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], bf16_t** lb, bf16_t** lb2,
 // copy of B_{k+1} in half precision, fp32 accumulation) ----------------------------------------
 dash_status clenshaw_chunk_bf16(dash_ctx* c, float* fb[2], bf16_t* hb[3], const float* A, float* X, int64_t n, int B,
                                 int d, const double* cf, double ca, double cb, float eps, const float* inv_s,
-                                const float* unscale, int32_t* nonfinite) {
+                                const float* unscale, int32_t* nonfinite, bf16_t** hm = nullptr, bf16_t** hl = nullptr) {
+    // hm, hl != null: three-plane mode -- the operand copies of S, B_{k+1}, B_{k+2} are carried as three bf16
+    // planes each (hb the high, hm the middle, hl the lowest planes) and every product has six segments
     hipStream_t st = c->stream;
-    bf16_t* Sh = hb[0];
-    float* b1 = fb[0]; bf16_t* h1 = hb[1];   // B_{k+1}: fp32 master and bf16 operand copy
-    float* b2 = fb[1]; bf16_t* h2 = hb[2];   // B_{k+2}
+    int i1 = 1, i2 = 2;                       // plane sets of B_{k+1} and B_{k+2} (set 0 is S)
+    float* b1 = fb[0];                        // B_{k+1}: fp32 master next to its operand copy
+    float* b2 = fb[1];                        // B_{k+2}
+    auto mid = [&](int i) -> bf16_t* { return hm ? hm[i] : nullptr; };
+    auto low = [&](int i) -> bf16_t* { return hl ? hl[i] : nullptr; };
+    // S B_{k+1} (operand copies) with D, fp32 result Cf and operand copy of the result in plane set ic (-1: none)
+    auto prod = [&](const float* D, float* Cf, int ic, const float* mult, float alpha, float beta, float gamma) {
+        GemmProblem p = problem_h(hb[0], hb[i1], D, Cf, ic >= 0 ? hb[ic] : nullptr, mult, alpha, beta, gamma);
+        p.A2 = mid(0); p.B2 = mid(i1); p.Cl = ic >= 0 ? mid(ic) : nullptr;
+        p.A3 = low(0); p.B3 = low(i1); p.Cl2 = ic >= 0 ? low(ic) : nullptr;
+        return p;
+    };
     const float m1 = (float)(2.0 / (cb - ca)), m0 = (float)(-(ca + cb) / (cb - ca));
     HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, m1, m0, nullptr, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
-                                  Sh, h1, nullptr, st, c->half_kind));
+                                  hb[0], hb[i1], nullptr, st, c->half_kind, mid(0), mid(i1), low(0), low(i1)));
     if (d == 2)
-        return gemm1(c, problem_h(Sh, h1, nullptr, X, nullptr, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B,
-                     nonfinite, 1, true);
-    DASH_TRY(gemm1(c, problem_h(Sh, h1, nullptr, b2, h2, nullptr, 2.f, 0.f, (float)(cf[d - 2] - cf[d])), n, B, nullptr, 1, true));
-    { float* t = b1; b1 = b2; b2 = t; bf16_t* u = h1; h1 = h2; h2 = u; }
+        return gemm1(c, prod(nullptr, X, -1, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B, nonfinite, 1, true);
+    DASH_TRY(gemm1(c, prod(nullptr, b2, i2, nullptr, 2.f, 0.f, (float)(cf[d - 2] - cf[d])), n, B, nullptr, 1, true));
+    { float* t = b1; b1 = b2; b2 = t; int u = i1; i1 = i2; i2 = u; }
     for (int k = d - 3; k >= 1; --k) {
-        DASH_TRY(gemm1(c, problem_h(Sh, h1, b2, b2, h2, nullptr, 2.f, -1.f, (float)cf[k]), n, B, nullptr, 1, true));
-        float* t = b1; b1 = b2; b2 = t; bf16_t* u = h1; h1 = h2; h2 = u;
+        DASH_TRY(gemm1(c, prod(b2, b2, i2, nullptr, 2.f, -1.f, (float)cf[k]), n, B, nullptr, 1, true));
+        float* t = b1; b1 = b2; b2 = t; int u = i1; i1 = i2; i2 = u;
     }
-    return gemm1(c, problem_h(Sh, h1, b2, X, nullptr, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite, 1, true);
+    return gemm1(c, prod(b2, X, -1, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite, 1, true);
 }
 
 // ---- Coupled-Newton on one chunk (paper Section 3.2) ----------------------------------------
@@ -922,8 +932,8 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32 && precision != DASH_BF16X3 &&
         precision != DASH_BF16X6)
         return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
-    if ((precision == DASH_BF16X3 || precision == DASH_BF16X6) && method != DASH_NEWTON_DB)
-        return fail(c, DASH_ERR_UNSUPPORTED, "split-operand bf16 is built for Newton-DB only");
+    if ((precision == DASH_BF16X3 && method != DASH_NEWTON_DB) || (precision == DASH_BF16X6 && method == DASH_COUPLED_NEWTON))
+        return fail(c, DASH_ERR_UNSUPPORTED, "split-operand bf16: two planes are built for Newton-DB, three for Newton-DB and Chebyshev");
     c->half_kind = precision == DASH_FP16_ACC32 ? HALF_FP16 : HALF_BF16;
     if (method == DASH_NEWTON_DB && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Newton-DB needs iters >= 1");
     if (method == DASH_CHEBYSHEV) {
@@ -990,7 +1000,9 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
                 DASH_TRY(ndb_call_bf16(c, hbuf, lows, lows2, buf[0], idx, nb, B, iters, false, false, nullptr, 0.f, nullptr, Xc, unscale, nf, &idx2));
             }
         } else if (lowp) {
-            DASH_TRY(clenshaw_chunk_bf16(c, buf, hbuf, Ac, Xc, nb, B, iters, cheb_coeffs, cheb_a, cheb_b, eps, inv_s, unscale, nf));
+            const bool planes3 = precision == DASH_BF16X6;
+            DASH_TRY(clenshaw_chunk_bf16(c, buf, hbuf, Ac, Xc, nb, B, iters, cheb_coeffs, cheb_a, cheb_b, eps, inv_s, unscale, nf,
+                                         planes3 ? hbuf + 3 : nullptr, planes3 ? hbuf + 6 : nullptr));
         } else if (method == DASH_NEWTON_DB) {
             int idx = -1;
             if (p == 2) {

@@ -82,11 +82,33 @@ def test_reaches_the_fp32_floor(dash, B, lo, k):
     assert e["bf16x6"] < e["bf16x3"] / 3
 
 
+@pytest.mark.parametrize("p", [2, 4])
+@pytest.mark.parametrize("B,d", [(128, 2), (128, 3), (128, 16), (256, 32), (1024, 24)])
+def test_chebyshev_matches_float64_clenshaw(dash, p, B, d):
+    """The Clenshaw recurrence with three-plane operands (B_k kept in fp32, as in Appendix A.3) against the float64
+    recurrence with the same coefficients: the bar of the fp32 path."""
+    from oracle import chebyshev as ocheb
+    from paper_2602_02016_amd import chebyshev_fit
+    N = 3
+    A32, Q, lam = workloads.spd_stack(N, B, -1.0, 0.0, seed=147, share_q=B >= 512)
+    A = A32.astype(np.float64)
+    s = np.sqrt((A ** 2).sum(axis=(1, 2)))
+    a, b = float((lam.min(axis=1) / s).min()) * 0.99, 1.0
+    coef = chebyshev_fit(p, d, a, b)
+    kw = dict(method="chebyshev", p=p, iters=d, cheb_coeffs=coef, cheb_a=a, cheb_b=b)
+    X6 = dash.inverse_root(_to_gpu(A32), precision="bf16x6", **kw).cpu().numpy()
+    X32 = dash.inverse_root(_to_gpu(A32), **kw).cpu().numpy()
+    X_same = ocheb.inverse_root_chebyshev(A, p, np.array(coef), a, b)
+    e6, e32 = rel_frobenius_error(X6, X_same).max(), rel_frobenius_error(X32, X_same).max()
+    print(f"cheb bf16x6 p={p} B={B} d={d}: vs f64 Clenshaw {e6:.2e} (fp32 path {e32:.2e})", flush=True)
+    assert e6 < 1e-5 and e6 < 3 * e32 + 1e-6
+
+
 def test_unsupported_methods(dash):
     from paper_2602_02016_amd import DashError, chebyshev_fit
     A32, _, _ = workloads.spd_stack(2, 64, -1.0, 0.0, seed=145)
     with pytest.raises(DashError):
         dash.inverse_root(_to_gpu(A32), method="coupled_newton", p=2, iters=4, precision="bf16x6")
     with pytest.raises(DashError):
-        dash.inverse_root(_to_gpu(A32), method="chebyshev", p=2, iters=8, precision="bf16x6",
+        dash.inverse_root(_to_gpu(A32), method="chebyshev", p=2, iters=8, precision="bf16x3",
                           cheb_coeffs=chebyshev_fit(2, 8, 0.1, 1.0), cheb_a=0.1, cheb_b=1.0)
