@@ -396,17 +396,26 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
                 }
                 if (Cb) *reinterpret_cast<v4f*>(Cb + off) = v;
                 if (Hb || Lb) {
-                    v4s h, lo, lo2;
+                    v4s h;
 #pragma unroll
-                    for (int m = 0; m < 4; ++m) {
-                        h[m] = H::from_float(v[m]);
-                        const float rest = v[m] - H::to_float(h[m]);
-                        lo[m] = H::from_float(rest);
-                        lo2[m] = H::from_float(rest - H::to_float(lo[m]));
-                    }
+                    for (int m = 0; m < 4; ++m) h[m] = H::from_float(v[m]);
                     if (Hb) *reinterpret_cast<v4s*>(Hb + off) = h;
-                    if (Lb) *reinterpret_cast<v4s*>(Lb + off) = lo;
-                    if (L2b) *reinterpret_cast<v4s*>(L2b + off) = lo2;
+                    if (Lb) {                     // split modes only: the plain product pays nothing for them
+                        v4s lo;
+                        float rest[4];
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) {
+                            rest[m] = v[m] - H::to_float(h[m]);
+                            lo[m] = H::from_float(rest[m]);
+                        }
+                        *reinterpret_cast<v4s*>(Lb + off) = lo;
+                        if (L2b) {
+                            v4s lo2;
+#pragma unroll
+                            for (int m = 0; m < 4; ++m) lo2[m] = H::from_float(rest[m] - H::to_float(lo[m]));
+                            *reinterpret_cast<v4s*>(L2b + off) = lo2;
+                        }
+                    }
                 }
                 if (H2b) {
                     v4s h2;
@@ -434,17 +443,26 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
                 const size_t moff = (size_t)col * B + row;
                 if (Cb) *reinterpret_cast<v4f*>(Cb + moff) = v;
                 if (Hb || Lb) {
-                    v4s h, lo, lo2;
+                    v4s h;
 #pragma unroll
-                    for (int m = 0; m < 4; ++m) {
-                        h[m] = H::from_float(v[m]);
-                        const float rest = v[m] - H::to_float(h[m]);
-                        lo[m] = H::from_float(rest);
-                        lo2[m] = H::from_float(rest - H::to_float(lo[m]));
-                    }
+                    for (int m = 0; m < 4; ++m) h[m] = H::from_float(v[m]);
                     if (Hb) *reinterpret_cast<v4s*>(Hb + moff) = h;
-                    if (Lb) *reinterpret_cast<v4s*>(Lb + moff) = lo;
-                    if (L2b) *reinterpret_cast<v4s*>(L2b + moff) = lo2;
+                    if (Lb) {                     // split modes only: the plain product pays nothing for them
+                        v4s lo;
+                        float rest[4];
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) {
+                            rest[m] = v[m] - H::to_float(h[m]);
+                            lo[m] = H::from_float(rest[m]);
+                        }
+                        *reinterpret_cast<v4s*>(Lb + moff) = lo;
+                        if (L2b) {
+                            v4s lo2;
+#pragma unroll
+                            for (int m = 0; m < 4; ++m) lo2[m] = H::from_float(rest[m] - H::to_float(lo[m]));
+                            *reinterpret_cast<v4s*>(L2b + moff) = lo2;
+                        }
+                    }
                 }
                 if (H2b) {
                     v4s h2;
