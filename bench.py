@@ -351,7 +351,20 @@ def main():
                       "ndb_iters": k, "ms": x6_ms, "blocks_per_s": 2 * N / (x6_ms * 1e-3),
                       "speedup_over_fp32_roots": root_ms / x6_ms, "rel_diff_to_headline_roots": d6,
                       "residual_fp32": residual(X[0], S[0]), "residual_bf16x6": residual(X6[0], S[0])}
-        del X6
+        # and the whole step with these roots (accumulation and update stay on the fp32 MFMA path)
+        U6 = torch.empty_like(U)
+        dash.step(grads[0], S, X6, U6, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf, precision="bf16x6")
+        torch.cuda.synchronize()
+        t4 = time.perf_counter()
+        for i in range(reps):
+            dash.step(grads[(i + 1) % len(grads)], S, X6, U6, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf,
+                      precision="bf16x6")
+        torch.cuda.synchronize()
+        x6_step_ms = (time.perf_counter() - t4) * 1e3 / reps
+        x6_variant["step_ms"] = x6_step_ms
+        x6_variant["step_blocks_per_s"] = 2 * N / (x6_step_ms * 1e-3)
+        assert int(nf.sum().item()) == 0, "non-finite root with bf16x6 operands"
+        del X6, U6
 
     ms_per_step = dt * 1e3 / args.steps
     blocks_per_s = 2 * N * args.steps / dt
