@@ -94,6 +94,7 @@ def sweep(dash, only_16bit=False):
         if cfg == "cfg5":
             cases += [("newton_db", 4, 10, "bf16"), ("newton_db", 4, 10, "fp16"), ("newton_db", 4, 10, "bf16x3"),
                       ("newton_db", 4, 10, "bf16x6"), ("chebyshev", 4, 16, "bf16x6"),
+                      ("coupled_newton", 4, 10, "bf16x6"),
                       ("coupled_newton", 4, 10, "fp16"), ("chebyshev", 4, 16, "fp16")]
         if only_16bit:
             cases = [c for c in cases if c[3] != "fp32"]

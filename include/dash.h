@@ -57,7 +57,7 @@ typedef enum { DASH_SCALE_FROBENIUS = 0, DASH_SCALE_TRACE = 1, DASH_SCALE_NONE =
  * operand is carried as two bf16 planes, x ~ hi + lo with hi = bf16(x), lo = bf16(x - hi), and a
  * product is A_lo B_hi + A_hi B_lo + A_hi B_hi accumulated in fp32 -- about 16 significand bits
  * per operand at three bf16 MFMA products, which keeps Newton-DB stable where plain bf16 is not.
- * DASH_BF16X6 (Newton-DB and Chebyshev): three planes, x ~ hi + mid + lo (24 significand bits: a float is
+ * DASH_BF16X6 (every method): three planes, x ~ hi + mid + lo (24 significand bits: a float is
  * represented exactly), and the six plane products of weight 2^-16 and above,
  * A_lo B_hi + A_hi B_lo + A_mid B_mid + A_mid B_hi + A_hi B_mid + A_hi B_hi -- fp32 accuracy from six
  * bf16 MFMA products, which cost less matrix-core time than one fp32 MFMA product. */

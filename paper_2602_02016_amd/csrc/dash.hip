@@ -106,7 +106,8 @@ int f32_buffers(dash_method m, dash_precision prec) {
 int bf16_buffers(dash_method m, dash_precision prec) {
     if (prec == DASH_FP32) return 0;
     if (prec == DASH_BF16X3) return 10;            // Newton-DB only: five iterates, a high and a low plane each
-    if (prec == DASH_BF16X6) return m == DASH_NEWTON_DB ? 15 : 9;   // five iterates (Newton-DB) or S and two B_k (Clenshaw), three planes each
+    if (prec == DASH_BF16X6)                        // three planes per iterate: five iterates (Newton-DB), nine
+        return m == DASH_NEWTON_DB ? 15 : m == DASH_COUPLED_NEWTON ? 27 : 9;      // (Coupled-Newton), S and two B_k (Clenshaw)
     if (m == DASH_COUPLED_NEWTON) return 9;
     return m == DASH_NEWTON_DB ? 5 : 3;
 }
@@ -166,7 +167,7 @@ dash_status collect_events(dash_ctx* c) {
 GemmProblem problem(const float* A, const float* B, const float* D, float* C, const float* mult, float alpha,
                     float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.C2 = nullptr; p.C2h = nullptr; p.A2 = nullptr; p.B2 = nullptr; p.Cl = nullptr; p.A3 = nullptr; p.B3 = nullptr; p.Cl2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
+    p.A = A; p.B = B; p.D = D; p.C = C; p.Ch = nullptr; p.C2 = nullptr; p.C2h = nullptr; p.A2 = nullptr; p.B2 = nullptr; p.Cl = nullptr; p.A3 = nullptr; p.B3 = nullptr; p.Cl2 = nullptr; p.C2l = nullptr; p.C2l2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
@@ -175,7 +176,7 @@ GemmProblem problem(const float* A, const float* B, const float* D, float* C, co
 GemmProblem problem_h(const bf16_t* Ah, const bf16_t* Bh, const float* D, float* C, bf16_t* Ch, const float* mult,
                       float alpha, float beta, float gamma, int ta = 0, int tb = 0) {
     GemmProblem p;
-    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.C2 = nullptr; p.C2h = nullptr; p.A2 = nullptr; p.B2 = nullptr; p.Cl = nullptr; p.A3 = nullptr; p.B3 = nullptr; p.Cl2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
+    p.A = Ah; p.B = Bh; p.D = D; p.C = C; p.Ch = Ch; p.C2 = nullptr; p.C2h = nullptr; p.A2 = nullptr; p.B2 = nullptr; p.Cl = nullptr; p.A3 = nullptr; p.B3 = nullptr; p.Cl2 = nullptr; p.C2l = nullptr; p.C2l2 = nullptr; p.a2 = 0.f; p.g2 = 0.f; p.mult = mult;
     p.alpha = alpha; p.beta = beta; p.gamma = gamma; p.transA = ta; p.transB = tb;
     return p;
 }
@@ -500,14 +501,23 @@ dash_status cn_chunk(dash_ctx* c, float* buf[9], const float* A, float* X, int64
 // accumulator of the M product before rounding), so all nine buffers hold 16-bit values; accumulation,
 // the epilogue arithmetic and the result X are fp32.
 dash_status cn_chunk_half(dash_ctx* c, bf16_t* hb[9], const float* A, float* X, int64_t n, int B, int p, int iters,
-                          float eps, const float* inv_s, const float* unscale, int32_t* nonfinite, float* tmp_f32) {
+                          float eps, const float* inv_s, const float* unscale, int32_t* nonfinite, float* tmp_f32,
+                          bf16_t** hm = nullptr, bf16_t** hl = nullptr) {
+    // hm, hl != null: three-plane mode -- every iterate is carried as three bf16 planes (hb the high, hm the
+    // middle, hl the lowest planes of the same nine iterates) and every product has six segments
     hipStream_t st = c->stream;
     const float a = 1.f + 1.f / p, ip = 1.f / p;
     const float inv_c = (float)std::pow(1.0 + p, 1.0 / p);
-    bf16_t* Xb[2] = {hb[0], hb[1]};
-    bf16_t* Mb[2] = {hb[2], hb[3]};
-    bf16_t* Cb[3] = {hb[4], hb[5], hb[6]};
-    bf16_t *P2 = hb[7], *P4 = hb[8];
+    // iterate indices: X ping-pong 0, 1; M ping-pong 2, 3; three C 4, 5, 6; C^2 7; C^4 8
+    auto mid = [&](int i) -> bf16_t* { return hm && i >= 0 ? hm[i] : nullptr; };
+    auto low = [&](int i) -> bf16_t* { return hl && i >= 0 ? hl[i] : nullptr; };
+    // iterate ia times iterate ib -> iterate ic (-1: none) and/or fp32 Cf
+    auto prod = [&](int ia, int ib, float* Cf, int ic, const float* mult, float alpha) {
+        GemmProblem q = problem_h(hb[ia], hb[ib], nullptr, Cf, ic >= 0 ? hb[ic] : nullptr, mult, alpha, 0.f, 0.f);
+        q.A2 = mid(ia); q.B2 = mid(ib); q.Cl = mid(ic);
+        q.A3 = low(ia); q.B3 = low(ib); q.Cl2 = low(ic);
+        return q;
+    };
     if (iters == 1) {   // X = s^(-1/p) (1/c) C_0 in fp32, no product: C_0 via the fp32 temporary X itself
         HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, X, nullptr, nullptr,
                                       nullptr, st, c->half_kind));
@@ -516,29 +526,29 @@ dash_status cn_chunk_half(dash_ctx* c, bf16_t* hb[9], const float* A, float* X, 
         (void)tmp_f32;
         return DASH_OK;
     }
-    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, nullptr, Mb[0], Cb[0],
-                                  nullptr, st, c->half_kind));
-    const bf16_t* Xcur = Cb[0];
+    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, nullptr, hb[2], hb[4],
+                                  nullptr, st, c->half_kind, mid(2), mid(4), low(2), low(4)));
+    int xcur = 4;                                   // X_1 = (1/c) C_0: the first update needs no product
     for (int k = 0; k + 1 < iters; ++k) {
-        bf16_t* Ck = Cb[k % 3];
-        DASH_TRY(gemm1(c, problem_h(Ck, Ck, nullptr, nullptr, P2, nullptr, 1.f, 0.f, 0.f), n, B, nullptr, 1));
-        const bf16_t* Pp = P2;
+        const int ck = 4 + k % 3;
+        DASH_TRY(gemm1(c, prod(ck, ck, nullptr, 7, nullptr, 1.f), n, B, nullptr, 1));
+        int pp = 7;
         if (p == 4) {
-            DASH_TRY(gemm1(c, problem_h(P2, P2, nullptr, nullptr, P4, nullptr, 1.f, 0.f, 0.f), n, B, nullptr, 1));
-            Pp = P4;
+            DASH_TRY(gemm1(c, prod(7, 7, nullptr, 8, nullptr, 1.f), n, B, nullptr, 1));
+            pp = 8;
         }
-        GemmProblem pm = problem_h(Pp, Mb[k % 2], nullptr, nullptr, Mb[(k + 1) % 2], nullptr, 1.f, 0.f, 0.f);
-        pm.C2h = Cb[(k + 1) % 3]; pm.a2 = -ip; pm.g2 = a;
+        const int cn = 4 + (k + 1) % 3;
+        GemmProblem pm = prod(pp, 2 + k % 2, nullptr, 2 + (k + 1) % 2, nullptr, 1.f);
+        pm.C2h = hb[cn]; pm.C2l = mid(cn); pm.C2l2 = low(cn); pm.a2 = -ip; pm.g2 = a;
         if (k == 0) {
             DASH_TRY(gemm1(c, pm, n, B, nullptr, 1));
         } else {
-            bf16_t* Xn = Xb[k % 2];
-            DASH_TRY(gemm2(c, pm, problem_h(Xcur, Ck, nullptr, nullptr, Xn, nullptr, 1.f, 0.f, 0.f), n, B, 1));
-            Xcur = Xn;
+            const int xn = k % 2;
+            DASH_TRY(gemm2(c, pm, prod(xcur, ck, nullptr, xn, nullptr, 1.f), n, B, 1));
+            xcur = xn;
         }
     }
-    return gemm1(c, problem_h(Xcur, Cb[(iters - 1) % 3], nullptr, X, nullptr, unscale, inv_c, 0.f, 0.f), n, B,
-                 nonfinite, 1);
+    return gemm1(c, prod(xcur, 4 + (iters - 1) % 3, X, -1, unscale, inv_c), n, B, nonfinite, 1);
 }
 
 // ---- Clenshaw on one chunk (paper Appendix A.2, reduced form, d-1 products) --------------
@@ -932,8 +942,8 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32 && precision != DASH_BF16X3 &&
         precision != DASH_BF16X6)
         return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
-    if ((precision == DASH_BF16X3 && method != DASH_NEWTON_DB) || (precision == DASH_BF16X6 && method == DASH_COUPLED_NEWTON))
-        return fail(c, DASH_ERR_UNSUPPORTED, "split-operand bf16: two planes are built for Newton-DB, three for Newton-DB and Chebyshev");
+    if (precision == DASH_BF16X3 && method != DASH_NEWTON_DB)
+        return fail(c, DASH_ERR_UNSUPPORTED, "two-plane split bf16 is built for Newton-DB only (three planes: every method)");
     c->half_kind = precision == DASH_FP16_ACC32 ? HALF_FP16 : HALF_BF16;
     if (method == DASH_NEWTON_DB && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Newton-DB needs iters >= 1");
     if (method == DASH_CHEBYSHEV) {
@@ -968,8 +978,8 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         float* inv_s = sc.inv_s;
         float* unscale = sc.unscale;
         float* buf[9] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-        bf16_t* hbuf[15] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
-                            nullptr, nullptr, nullptr, nullptr, nullptr};
+        bf16_t* hbuf[27];
+        for (int i = 0; i < 27; ++i) hbuf[i] = nullptr;
         for (int i = 0; i < nbuf; ++i) buf[i] = (float*)cv.take((size_t)nb * mat * sizeof(float));
         for (int i = 0; i < nhbuf; ++i) hbuf[i] = (bf16_t*)cv.take((size_t)nb * mat * sizeof(bf16_t));
         if (!sc_ok || (nbuf && !buf[nbuf - 1]) || (nhbuf && !hbuf[nhbuf - 1]))
@@ -984,7 +994,9 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         DASH_TRY(compute_scales(c, Ac, nb, B, eps, scaling, p, sc, scale_out ? scale_out + b0 : sc.s));
 
         if (method == DASH_COUPLED_NEWTON && lowp) {
-            DASH_TRY(cn_chunk_half(c, hbuf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf, nullptr));
+            const bool planes3 = precision == DASH_BF16X6;
+            DASH_TRY(cn_chunk_half(c, hbuf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf, nullptr,
+                                   planes3 ? hbuf + 9 : nullptr, planes3 ? hbuf + 18 : nullptr));
         } else if (method == DASH_COUPLED_NEWTON) {
             DASH_TRY(cn_chunk(c, buf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf));
         } else if (lowp && method == DASH_NEWTON_DB) {

@@ -343,6 +343,8 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     float* __restrict__ Cb = P.C ? P.C + boff : nullptr;
     u16* __restrict__ Hb = P.Ch ? static_cast<u16*>(P.Ch) + boff : nullptr;
     u16* __restrict__ H2b = P.C2h ? static_cast<u16*>(P.C2h) + boff : nullptr;
+    u16* __restrict__ H2lb = P.C2l ? static_cast<u16*>(P.C2l) + boff : nullptr;     // planes of the second output
+    u16* __restrict__ H2l2b = P.C2l2 ? static_cast<u16*>(P.C2l2) + boff : nullptr;  // (both or neither)
     u16* __restrict__ Lb = P.Cl ? static_cast<u16*>(P.Cl) + boff : nullptr;    // low plane of the result
     u16* __restrict__ L2b = P.Cl2 ? static_cast<u16*>(P.Cl2) + boff : nullptr; // third plane (with Lb only)
     const float a2 = P.a2, g2 = P.g2;
@@ -419,9 +421,24 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
                 }
                 if (H2b) {
                     v4s h2;
+                    float w[4];
 #pragma unroll
-                    for (int m = 0; m < 4; ++m) h2[m] = H::from_float(a2 * v[m] + (diag && row == col + m ? g2 : 0.f));
+                    for (int m = 0; m < 4; ++m) {
+                        w[m] = a2 * v[m] + (diag && row == col + m ? g2 : 0.f);
+                        h2[m] = H::from_float(w[m]);
+                    }
                     *reinterpret_cast<v4s*>(H2b + off) = h2;
+                    if (H2lb) {
+                        v4s lo, lo2;
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) {
+                            const float rest = w[m] - H::to_float(h2[m]);
+                            lo[m] = H::from_float(rest);
+                            lo2[m] = H::from_float(rest - H::to_float(lo[m]));
+                        }
+                        *reinterpret_cast<v4s*>(H2lb + off) = lo;
+                        *reinterpret_cast<v4s*>(H2l2b + off) = lo2;
+                    }
                 }
                 if (mirror) *reinterpret_cast<v4f*>(sp) = v;       // final values for phase C
             }
@@ -469,6 +486,17 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
 #pragma unroll
                     for (int m = 0; m < 4; ++m) h2[m] = H::from_float(a2 * v[m]);
                     *reinterpret_cast<v4s*>(H2b + moff) = h2;
+                    if (H2lb) {
+                        v4s lo, lo2;
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) {
+                            const float rest = a2 * v[m] - H::to_float(h2[m]);
+                            lo[m] = H::from_float(rest);
+                            lo2[m] = H::from_float(rest - H::to_float(lo[m]));
+                        }
+                        *reinterpret_cast<v4s*>(H2lb + moff) = lo;
+                        *reinterpret_cast<v4s*>(H2l2b + moff) = lo2;
+                    }
                 }
             }
             __builtin_amdgcn_wave_barrier();

@@ -35,6 +35,8 @@ struct GemmProblem {
     const void* A3;
     const void* B3;
     void* Cl2;
+    void* C2l;             // middle and lowest plane of the second output (three-plane mode, with C2h)
+    void* C2l2;
     float a2, g2;
     const float* mult;
     float alpha, beta, gamma;

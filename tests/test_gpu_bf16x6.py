@@ -104,11 +104,41 @@ def test_chebyshev_matches_float64_clenshaw(dash, p, B, d):
     assert e6 < 1e-5 and e6 < 3 * e32 + 1e-6
 
 
+@pytest.mark.parametrize("p", [2, 4])
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_coupled_newton_few_iterations_match_emulation(dash, p, k):
+    N, B = 3, 128
+    A32, _, _ = workloads.spd_stack(N, B, -1.0, 0.0, seed=149)
+    X = dash.inverse_root(_to_gpu(A32), method="coupled_newton", p=p, iters=k, eps=1e-6, precision="bf16x6").cpu().numpy()
+    X_emu = lowprec.inverse_root_cn_lowprec(A32, p, k, eps=1e-6, fmt="bf16x6")
+    e = rel_frobenius_error(X, X_emu).max()
+    print(f"cn bf16x6 p={p} k={k}: vs emulation {e:.2e}", flush=True)
+    assert e < 5e-6
+
+
+@pytest.mark.parametrize("p", [2, 4])
+@pytest.mark.parametrize("B", [256, 1024])
+def test_coupled_newton_reaches_the_fp32_floor(dash, p, B):
+    N, k = 3, 25
+    A32, _, _ = workloads.spd_stack(N, B, -1.0, 0.0, seed=151, share_q=B >= 512)
+    X_evd = inverse_root_evd(A32.astype(np.float64), p, eps=1e-6)
+    e = {}
+    for prec in ("fp32", "bf16x6", "fp16"):
+        nf = _to_gpu(np.zeros(N, dtype=np.int32))
+        X = dash.inverse_root(_to_gpu(A32), method="coupled_newton", p=p, iters=k, eps=1e-6, precision=prec,
+                              nonfinite_out=nf).cpu().numpy()
+        assert int(nf.sum().item()) == 0
+        e[prec] = rel_frobenius_error(X, X_evd).max()
+    print(f"cn p={p} B={B} k={k}: vs EVD fp32 {e['fp32']:.2e}  bf16x6 {e['bf16x6']:.2e}  fp16 {e['fp16']:.2e}", flush=True)
+    assert e["bf16x6"] < 3 * e["fp32"] + 1e-6 and e["bf16x6"] < e["fp16"] / 10
+
+
 def test_unsupported_methods(dash):
+    """Two planes are built for Newton-DB only."""
     from paper_2602_02016_amd import DashError, chebyshev_fit
     A32, _, _ = workloads.spd_stack(2, 64, -1.0, 0.0, seed=145)
     with pytest.raises(DashError):
-        dash.inverse_root(_to_gpu(A32), method="coupled_newton", p=2, iters=4, precision="bf16x6")
+        dash.inverse_root(_to_gpu(A32), method="coupled_newton", p=2, iters=4, precision="bf16x3")
     with pytest.raises(DashError):
         dash.inverse_root(_to_gpu(A32), method="chebyshev", p=2, iters=8, precision="bf16x3",
                           cheb_coeffs=chebyshev_fit(2, 8, 0.1, 1.0), cheb_a=0.1, cheb_b=1.0)
