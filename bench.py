@@ -202,8 +202,8 @@ def main():
                          "1 GiB stack (table on stderr, one JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards over blocks; see DESIGN.md); "
-              "--gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (blocks are independent, so the path would shard over "
+              "them, but no multi-GPU code is built); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
