@@ -7,7 +7,7 @@
 // pool only widens the skinny product W = A V.  The pool vectors are kept pool-major
 // ([32][B] per block: a column of V is contiguous) so that every operand of the sweep is
 // read 16 bytes per lane.  Kernels:
-//   pi_init    V_b = start vectors with unit columns (pool padded with zero columns to 32)
+//   pi_init    V_0 = start vectors with unit columns (pool padded with zero columns to 32); pi_spread copies it to every block
 //   pi_sweep   W_b = A_b V_b + eps V_b with v_mfma_f32_32x32x2_f32, computed as W^T = V^T A (the
 //              blocks are symmetric).  A workgroup owns 128 columns of A; its four wavefronts split
 //              K (16-wide half-chunks, round robin), each streams its rows of the 128 columns
@@ -34,28 +34,38 @@ namespace {
 constexpr int POOL = 32;     // columns of V (pool members beyond the requested count are zero)
 constexpr int PNT = 256;
 
-// grid = nblocks; V0: [B][m] row-major (shared by all blocks); V: [nblocks][32][B]
+// The start vectors are the same for every block: one workgroup per pool column writes the column, scaled to unit
+// length, into block 0 of V (pool-major, [32][B]; columns beyond the requested m are zero), then every other block
+// copies block 0.  grid = 32; V0: [B][m] row-major
 __global__ __launch_bounds__(PNT) void pi_init_kernel(const float* __restrict__ V0, int m, int B,
                                                      float* __restrict__ V) {
-    __shared__ float part[PNT / POOL][POOL];
-    __shared__ float inv_norm[POOL];
-    const int j = threadIdx.x % POOL, rg = threadIdx.x / POOL;
+    __shared__ float sh[PNT / 64];
+    __shared__ float inv;
+    const int c = blockIdx.x;
     float acc = 0.f;
-    if (j < m)
-        for (int i = rg; i < B; i += PNT / POOL) { const float x = V0[(size_t)i * m + j]; acc += x * x; }
-    part[rg][j] = acc;
+    if (c < m)
+        for (int i = threadIdx.x; i < B; i += PNT) { const float x = V0[(size_t)i * m + c]; acc += x * x; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
     __syncthreads();
-    if (rg == 0) {
+    if (threadIdx.x == 0) {
         float t = 0.f;
-        for (int r = 0; r < PNT / POOL; ++r) t += part[r][j];
-        inv_norm[j] = t > 0.f ? 1.f / sqrtf(t) : 0.f;
+        for (int w = 0; w < PNT / 64; ++w) t += sh[w];
+        inv = t > 0.f ? 1.f / sqrtf(t) : 0.f;
     }
     __syncthreads();
-    float* __restrict__ Vb = V + (size_t)blockIdx.x * B * POOL;
-    for (int idx = threadIdx.x; idx < POOL * B; idx += PNT) {
-        const int c = idx / B, i = idx % B;
-        Vb[idx] = c < m ? V0[(size_t)i * m + c] * inv_norm[c] : 0.f;
-    }
+    const float sc = inv;
+    for (int i = threadIdx.x; i < B; i += PNT) V[(size_t)c * B + i] = c < m ? V0[(size_t)i * m + c] * sc : 0.f;
+}
+
+// grid = (32 B / 4 / PNT, nblocks - 1): V_b = V_0 for b = 1 .. nblocks - 1
+__global__ __launch_bounds__(PNT) void pi_spread_kernel(float* __restrict__ V, int B) {
+    const size_t per = (size_t)B * POOL;
+    const size_t f = (size_t)blockIdx.x * PNT + threadIdx.x;
+    if (4 * f >= per) return;
+    const v4f x = *reinterpret_cast<const v4f*>(V + 4 * f);
+    *reinterpret_cast<v4f*>(V + ((size_t)blockIdx.y + 1) * per + 4 * f) = x;
 }
 
 // per-block scalars: q[32], then per workgroup of the sweep (128 columns each) the partial sums
@@ -355,7 +365,10 @@ hipError_t launch_power_iteration(const float* A, int64_t nblocks, int B, float 
         float* dst = W + ov;
         float* qa = q0 + b0 * QF;
         float* qb = q1 + b0 * QF;
-        hipLaunchKernelGGL(pi_init_kernel, dim3(nb), dim3(PNT), 0, stream, V0, pool, B, src);
+        hipLaunchKernelGGL(pi_init_kernel, dim3(POOL), dim3(PNT), 0, stream, V0, pool, B, src);
+        if (nb > 1)
+            hipLaunchKernelGGL(pi_spread_kernel, dim3((unsigned)(((size_t)B * POOL / 4 + PNT - 1) / PNT), nb - 1), dim3(PNT), 0,
+                               stream, src, B);
         hipLaunchKernelGGL(pi_unit_norms_kernel, dim3(nb), dim3(256), 0, stream, qa, B);
         for (int t = 1; t <= sweeps; ++t) {
             const bool big = (size_t)nblocks * B * B * sizeof(float) >= ((size_t)256 << 20);
