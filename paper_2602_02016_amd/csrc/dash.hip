@@ -750,8 +750,9 @@ dash_status dash_accumulate_factors(dash_ctx* c, const float* G, float* L, float
     HIP_TRY(c, hipSetDevice(c->device));
     // L = beta L + alpha G G^T ; R = beta R + alpha G^T G  (EMA fused in the epilogue)
     // G G^T and G^T G are symmetric bit for bit (same products, same summation order for (i,j) and (j,i))
-    DASH_TRY(gemm1(c, problem(G, G, L, L, nullptr, alpha, beta, 0.f, 0, 1), N, B, nullptr, 0, true));
-    DASH_TRY(gemm1(c, problem(G, G, R, R, nullptr, alpha, beta, 0.f, 1, 0), N, B, nullptr, 0, true));
+    // (one launch for both: the two products of a block use different memory orders of G)
+    DASH_TRY(gemm2(c, problem(G, G, L, L, nullptr, alpha, beta, 0.f, 0, 1), problem(G, G, R, R, nullptr, alpha, beta, 0.f, 1, 0),
+                   N, B, 0, true));
     return DASH_OK;
 }
 

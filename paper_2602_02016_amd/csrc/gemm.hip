@@ -365,6 +365,39 @@ __global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void 
     }
 }
 
+// The factor accumulation: product 0 of every block is A B^T (G G^T), product 1 is A^T B (G^T G) -- two memory
+// orders, two instances of the tile function, one launch, so that the 2 x 36 tiles of a block fill the chip
+// together (each product alone is half a round of workgroups on the benchmark's 16 gradient blocks).
+template <int TILE>
+__device__ __forceinline__ void gemm_f32_pair_tile(const GemmLaunch& g, int64_t lid, int64_t blk_first, float* lds) {
+    const int tiles = g.B / TILE;
+    const int T = g.sym ? tiles * (tiles + 1) / 2 : tiles * tiles;
+    const int pi = (int)(lid % ((int64_t)2 * T)) / T;         // as the tile function will find it
+    if (pi == 0) gemm_f32_tile<TILE, false, true, false>(g, lid, blk_first, lds);
+    else gemm_f32_tile<TILE, true, false, false>(g, lid, blk_first, lds);
+}
+
+template <int TILE>
+__global__ __launch_bounds__(Cfg<TILE>::NT, DASH_MIN_WG) void gemm_f32_pair_kernel(GemmLaunch g) {
+    __shared__ __attribute__((aligned(1024))) float lds[LdsNeed<TILE>::FLOATS];
+    const int64_t bid = blockIdx.x;
+    if (TILE == 128) {
+        if (bid >= g.w_main) {
+            gemm_f32_pair_tile<64>(g, xcd_remap(bid - g.w_main, (int64_t)gridDim.x - g.w_main), g.blk0 + g.n_main, lds);
+            return;
+        }
+        gemm_f32_pair_tile<TILE>(g, xcd_remap(bid, g.w_main), g.blk0, lds);
+    } else {
+        gemm_f32_pair_tile<TILE>(g, xcd_remap(bid, gridDim.x), g.blk0, lds);
+    }
+}
+
+// the one two-product launch with different memory orders: (A B^T, A^T B) on square fp32 blocks
+static bool gemm_is_pair(const GemmLaunch& g) {
+    return g.nprob == 2 && g.half == HALF_NONE && !g.M && !g.N && !g.K && !g.prob[0].transA && g.prob[0].transB &&
+           g.prob[1].transA && !g.prob[1].transB;
+}
+
 // workgroups of nblocks blocks computed with TILE tiles
 template <int TILE>
 static int64_t tile_count(const GemmLaunch& g, int64_t nblocks) {
@@ -381,9 +414,13 @@ static hipError_t launch_tile(const GemmLaunch& g0, int64_t n_main, hipStream_t 
     const int64_t W = g.w_main + (n_main < g.nblocks ? tile_count<64>(g, g.nblocks - n_main) : 0);
     if (W <= 0) return hipSuccess;
     if (W > 0x7fffffffLL) return hipErrorInvalidValue;
-    // both products of a launch must use the same transpose flags (one kernel instance)
     const int ta = g.prob[0].transA, tb = g.prob[0].transB;
     dim3 grid((unsigned)W), block(Cfg<TILE>::NT);
+    if (gemm_is_pair(g)) {
+        hipLaunchKernelGGL((gemm_f32_pair_kernel<TILE>), grid, block, 0, stream, g);
+        return hipGetLastError();
+    }
+    // otherwise both products of a launch use the same transpose flags (one kernel instance)
     if (g.M || g.N || g.K) {
         if (!ta && !tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, false, true>), grid, block, 0, stream, g);
         else if (!ta && tb) hipLaunchKernelGGL((gemm_f32_kernel<TILE, false, true, true>), grid, block, 0, stream, g);
@@ -404,7 +441,8 @@ hipError_t launch_gemm(const GemmLaunch& g, hipStream_t stream) {
     const bool rect = g.M || g.N || g.K;
     if (rect && g.half != HALF_NONE) return hipErrorInvalidValue;              // rectangular: fp32 only
     if (g.sym && (g.M ? g.M : g.B) != (g.N ? g.N : g.B)) return hipErrorInvalidValue;   // mirroring needs a square output
-    if (g.nprob == 2 && (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
+    if (g.nprob == 2 && !gemm_is_pair(g) &&
+        (g.prob[0].transA != g.prob[1].transA || g.prob[0].transB != g.prob[1].transB))
         return hipErrorInvalidValue;
     if (g.half != HALF_NONE) return launch_gemm_half(g, stream);
     if (gemm_tile_edge(g) != 128) return launch_tile<64>(g, g.nblocks, stream);
