@@ -38,8 +38,9 @@ def _oracle_step(grads, state, beta, eps, refresh):
     return out, new
 
 
+@pytest.mark.parametrize("precision", ["fp32", "bf16x6"])
 @pytest.mark.parametrize("ws_cap", [None, 3 << 20])
-def test_model_step_matches_per_layer_oracle(dash, ws_cap):
+def test_model_step_matches_per_layer_oracle(dash, ws_cap, precision):
     import torch
     from paper_2602_02016_amd import DashModel
     model = DashModel(dash, LAYERS, B, p=4, p_vec=2)
@@ -58,7 +59,7 @@ def test_model_step_matches_per_layer_oracle(dash, ws_cap):
         ups = [torch.full_like(g, 7.0) for g in grads]
         dash.reset_stats()
         model.step(grads, ups, beta=beta, eps=eps, method="newton_db", iters=k, refresh=refresh, nonfinite_out=nf,
-                   workspace_max_bytes=ws_cap)
+                   workspace_max_bytes=ws_cap, precision=precision)
         st = dash.get_stats()
         ref, state = _oracle_step(g_np, state, beta, eps, refresh)
         errs = [rel_frobenius_error(u.cpu().numpy().reshape(1, -1, 1) if u.dim() == 1 else u.cpu().numpy()[None],
