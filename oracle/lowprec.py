@@ -66,6 +66,19 @@ def split_bf16(x):
     return hi, lo
 
 
+FP16_LO_SCALE = np.float32(2048.0)   # 2^11: the low fp16 plane is stored times this, so that it does not go subnormal
+
+
+def split_fp16(x):
+    """x ~ hi + lo with hi = fp16(x) and lo = fp16((x - hi) 2^11) 2^-11 (as float32 values): 22 significand bits.
+    The low plane is rounded after scaling by 2^11 -- it is 2^-11 of x or less, and unscaled it would fall into
+    fp16's subnormal range for |x| < 0.125."""
+    hi = round_fp16(x)
+    with np.errstate(invalid="ignore", over="ignore"):
+        lo = round_fp16((_f32(x) - hi) * FP16_LO_SCALE) / FP16_LO_SCALE
+    return hi, _f32(lo)
+
+
 def split3_bf16(x):
     """x ~ hi + mid + lo, three bf16 planes: hi = bf16(x), mid = bf16(x - hi), lo = bf16(x - hi - mid)
     (as float32 values; the differences are exact in float32)."""
@@ -79,12 +92,18 @@ def matmul_lowprec(A, B, fmt: str = "bf16") -> np.ndarray:
     """float32( half(A) @ half(B) ) with the product summed in float64.  fmt = 'bf16x3': both operands
     split into two bf16 planes, product = A_lo B_hi + A_hi B_lo + A_hi B_hi (lo*lo dropped).  fmt = 'bf16x6':
     three planes each, the six plane products of weight 2^-16 and above:
-    A_lo B_hi + A_hi B_lo + A_mid B_mid + A_mid B_hi + A_hi B_mid + A_hi B_hi."""
+    A_lo B_hi + A_hi B_lo + A_mid B_mid + A_mid B_hi + A_hi B_mid + A_hi B_hi.  fmt = 'fp16x3': two fp16 planes
+    (split_fp16: 22 significand bits), the same three products as 'bf16x3'."""
     if fmt == "bf16x6":
         ah, am, al = (t.astype(np.float64) for t in split3_bf16(A))
         bh, bm, bl = (t.astype(np.float64) for t in split3_bf16(B))
         with np.errstate(over="ignore", invalid="ignore"):
             return _f32(al @ bh + ah @ bl + am @ bm + am @ bh + ah @ bm + ah @ bh)
+    if fmt == "fp16x3":
+        ah, al = (t.astype(np.float64) for t in split_fp16(A))
+        bh, bl = (t.astype(np.float64) for t in split_fp16(B))
+        with np.errstate(over="ignore", invalid="ignore"):
+            return _f32((al @ bh + ah @ bl) + ah @ bh)
     if fmt == "bf16x3":
         ah, al = (t.astype(np.float64) for t in split_bf16(A))
         bh, bl = (t.astype(np.float64) for t in split_bf16(B))

@@ -171,3 +171,40 @@ def test_ndb_with_six_term_products_matches_the_float32_floor():
     e3 = rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32, 4, 14, rounding="bf16x3"), X).max()
     print(f"NDB p=4 k=14 kappa=1e3: no rounding {e32:.2e}, bf16x6 {e6:.2e}, bf16x3 {e3:.2e}")
     assert e6 < 3 * e32 + 1e-6 and e3 > 3 * e6
+
+
+def test_split_fp16_planes():
+    # two fp16 planes carry 22 significand bits down to where the high plane goes subnormal (6e-5); below that the
+    # error is absolute: half a subnormal step of the high plane's format at most
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal(40000) * 10.0 ** rng.uniform(-4, 0.5, 40000)).astype(np.float32)
+    hi, lo = lowprec.split_fp16(x)
+    assert np.array_equal(hi, lowprec.round_fp16(x))
+    err = np.abs((hi.astype(np.float64) + lo) - x)
+    assert np.all(err <= np.maximum(np.abs(x) * 2.0 ** -22, 2.0 ** -36))
+    big = np.abs(x) > 1e-3
+    assert (err[big] / np.abs(x[big])).max() > 2.0 ** -26          # and it is not better than that: a real bound
+    # unscaled, the low plane is subnormal for values well inside the range of the iterates and loses its bits
+    small = (np.abs(x) > 1e-3) & (np.abs(x) < 1e-2)
+    naive = lowprec.round_fp16(x - hi)
+    assert np.abs((hi.astype(np.float64) + naive) - x)[small].max() > 5 * err[small].max()
+
+
+def test_fp16x3_product_is_close_to_the_float32_product():
+    rng = np.random.default_rng(8)
+    A = rng.standard_normal((96, 96)).astype(np.float32)
+    B = rng.standard_normal((96, 96)).astype(np.float32)
+    exact = A.astype(np.float64) @ B.astype(np.float64)
+    e = {f: rel_frobenius_error(lowprec.matmul_lowprec(A, B, f), exact)[0] for f in ("fp16x3", "bf16x3", "bf16x6", "fp16")}
+    e32 = rel_frobenius_error((A @ B).astype(np.float32), exact)[0]
+    print(e, e32)
+    assert e["fp16x3"] < 6e-7 and e["fp16x3"] < e["bf16x3"] / 20 and e["fp16x3"] < e["fp16"] / 500
+
+
+def test_ndb_with_fp16x3_products_is_near_the_float32_floor():
+    A32, _, _ = workloads.spd_stack(2, 64, -3.0, 0.0, seed=17)
+    X = inverse_root_evd(A32.astype(np.float64), 4)
+    e = {f: rel_frobenius_error(lowprec.inverse_root_ndb_lowprec(A32, 4, 14, rounding=f), X).max()
+         for f in ("none", "fp16x3", "bf16x3", "fp16")}
+    print("NDB p=4 k=14 kappa=1e3:", e)
+    assert e["fp16x3"] < 10 * e["none"] and e["fp16x3"] < e["bf16x3"] / 5
