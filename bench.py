@@ -95,6 +95,7 @@ def sweep(dash, only_16bit=False):
             cases += [("newton_db", 4, 10, "bf16"), ("newton_db", 4, 10, "fp16"), ("newton_db", 4, 10, "bf16x3"),
                       ("newton_db", 4, 10, "bf16x6"), ("chebyshev", 4, 16, "bf16x6"),
                       ("coupled_newton", 4, 10, "bf16x6"),
+                      ("newton_db", 4, 10, "fp16x3"), ("coupled_newton", 4, 10, "fp16x3"), ("chebyshev", 4, 16, "fp16x3"),
                       ("coupled_newton", 4, 10, "fp16"), ("chebyshev", 4, 16, "fp16")]
         if only_16bit:
             cases = [c for c in cases if c[3] != "fp32"]
@@ -328,44 +329,51 @@ def main():
                       "rel_diff_to_headline_roots": diff}
         del Xp
 
-    # the same roots with three-plane split bf16 operands (DASH_BF16X6: six bf16 MFMA products per matmul, fp32
-    # accuracy; context, not the headline): time, difference to the fp32 roots, and the residual
-    # ||X^4 (A + eps I) - I||_F / sqrt(B) of both, formed in float64 on one block
-    x6_variant = None
+    # the same roots with split 16-bit operands (context, not the headline): three bf16 planes and six plane
+    # products (DASH_BF16X6), two fp16 planes with a scaled low plane and three products (DASH_FP16X3); fp32
+    # accumulation in both.  Time, difference to the fp32 roots, the residual ||X^4 (A + eps I) - I||_F / sqrt(B)
+    # formed in float64 on one block, and the whole step with these roots (accumulation and update stay on the
+    # fp32 MFMA path).
+    split_variants = {}
     if reps > 0:
-        X6 = torch.empty_like(S)
-        dash.inverse_root(S, X6, p=p, iters=k, eps=eps, precision="bf16x6", nonfinite_out=nf)
-        torch.cuda.synchronize()
-        t3 = time.perf_counter()
-        for _ in range(reps):
-            dash.inverse_root(S, X6, p=p, iters=k, eps=eps, precision="bf16x6", nonfinite_out=nf)
-        torch.cuda.synchronize()
-        x6_ms = (time.perf_counter() - t3) * 1e3 / reps
-
         def residual(Xb, Ab):
             X64 = Xb.double()
             X2 = X64 @ X64
             R = X2 @ X2 @ (Ab.double() + eps * torch.eye(B, device=dev, dtype=torch.float64)) - torch.eye(B, device=dev, dtype=torch.float64)
             return float(R.norm() / B ** 0.5)
-        d6 = float(((X6[:2] - X[:2]).double().flatten(1).norm(dim=1) / X[:2].double().flatten(1).norm(dim=1)).max())
-        x6_variant = {"precision": "bf16x6 (operands as three bf16 planes, six plane products, fp32 accumulation)",
-                      "ndb_iters": k, "ms": x6_ms, "blocks_per_s": 2 * N / (x6_ms * 1e-3),
-                      "speedup_over_fp32_roots": root_ms / x6_ms, "rel_diff_to_headline_roots": d6,
-                      "residual_fp32": residual(X[0], S[0]), "residual_bf16x6": residual(X6[0], S[0])}
-        # and the whole step with these roots (accumulation and update stay on the fp32 MFMA path)
-        U6 = torch.empty_like(U)
-        dash.step(grads[0], S, X6, U6, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf, precision="bf16x6")
-        torch.cuda.synchronize()
-        t4 = time.perf_counter()
-        for i in range(reps):
-            dash.step(grads[(i + 1) % len(grads)], S, X6, U6, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf,
-                      precision="bf16x6")
-        torch.cuda.synchronize()
-        x6_step_ms = (time.perf_counter() - t4) * 1e3 / reps
-        x6_variant["step_ms"] = x6_step_ms
-        x6_variant["step_blocks_per_s"] = 2 * N / (x6_step_ms * 1e-3)
-        assert int(nf.sum().item()) == 0, "non-finite root with bf16x6 operands"
-        del X6, U6
+        S_keep = S.clone()                  # the steps below move the factors on: every variant starts from the same
+        res32 = residual(X[0], S[0])
+        notes = {"bf16x6": "operands as three bf16 planes, six plane products, fp32 accumulation",
+                 "fp16x3": "operands as two fp16 planes (low plane scaled by 2^11), three plane products, fp32 accumulation"}
+        for prec in ("bf16x6", "fp16x3"):
+            S.copy_(S_keep)
+            Xs = torch.empty_like(S)
+            dash.inverse_root(S, Xs, p=p, iters=k, eps=eps, precision=prec, nonfinite_out=nf)
+            torch.cuda.synchronize()
+            t3 = time.perf_counter()
+            for _ in range(reps):
+                dash.inverse_root(S, Xs, p=p, iters=k, eps=eps, precision=prec, nonfinite_out=nf)
+            torch.cuda.synchronize()
+            v_ms = (time.perf_counter() - t3) * 1e3 / reps
+            dv = float(((Xs[:2] - X[:2]).double().flatten(1).norm(dim=1) / X[:2].double().flatten(1).norm(dim=1)).max())
+            rec = {"precision": prec + " (" + notes[prec] + ")", "ndb_iters": k, "ms": v_ms,
+                   "blocks_per_s": 2 * N / (v_ms * 1e-3), "speedup_over_fp32_roots": root_ms / v_ms,
+                   "rel_diff_to_headline_roots": dv, "residual_fp32": res32, "residual": residual(Xs[0], S[0])}
+            Us = torch.empty_like(U)
+            dash.step(grads[0], S, Xs, Us, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf, precision=prec)
+            torch.cuda.synchronize()
+            t4 = time.perf_counter()
+            for i in range(reps):
+                dash.step(grads[(i + 1) % len(grads)], S, Xs, Us, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf,
+                          precision=prec)
+            torch.cuda.synchronize()
+            rec["step_ms"] = (time.perf_counter() - t4) * 1e3 / reps
+            rec["step_blocks_per_s"] = 2 * N / (rec["step_ms"] * 1e-3)
+            assert int(nf.sum().item()) == 0, "non-finite root with " + prec + " operands"
+            split_variants[prec] = rec
+            del Xs, Us
+        S.copy_(S_keep)
+        del S_keep
 
     ms_per_step = dt * 1e3 / args.steps
     blocks_per_s = 2 * N * args.steps / dt
@@ -429,7 +437,8 @@ def main():
                                       "it is a throughput figure, not a utilisation"},
     }
     out["inverse_root_power_iteration_scaling"] = pi_variant
-    out["inverse_root_bf16x6"] = x6_variant
+    out["inverse_root_bf16x6"] = split_variants.get("bf16x6")
+    out["inverse_root_fp16x3"] = split_variants.get("fp16x3")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(min(args.cpu_sample_blocks, N), B, beta, eps, p, args.cpu_repeats)
     log(f"step {ms_per_step:.2f} ms, {blocks_per_s:.0f} factor blocks/s, matmul kernel {achieved_tflops:.1f} TFLOP/s "

@@ -53,15 +53,21 @@ typedef enum { DASH_SCALE_FROBENIUS = 0, DASH_SCALE_TRACE = 1, DASH_SCALE_NONE =
 /* DASH_FP32: fp32 MFMA operands.  DASH_FP16_ACC32 / DASH_BF16_ACC32: the recipe of
  * Appendix A.3 -- iterates kept in fp32, every matmul operand rounded to fp16 / bf16 (round to
  * nearest even), fp32 accumulation -- applied to Clenshaw (as in the paper) and to Newton-DB
- * (which the paper reports unstable in half precision).  DASH_BF16X3 (Newton-DB only): every
+ * (which the paper reports unstable in half precision).  DASH_BF16X3: every
  * operand is carried as two bf16 planes, x ~ hi + lo with hi = bf16(x), lo = bf16(x - hi), and a
  * product is A_lo B_hi + A_hi B_lo + A_hi B_hi accumulated in fp32 -- about 16 significand bits
  * per operand at three bf16 MFMA products, which keeps Newton-DB stable where plain bf16 is not.
- * DASH_BF16X6 (every method): three planes, x ~ hi + mid + lo (24 significand bits: a float is
+ * DASH_BF16X6: three planes, x ~ hi + mid + lo (24 significand bits: a float is
  * represented exactly), and the six plane products of weight 2^-16 and above,
  * A_lo B_hi + A_hi B_lo + A_mid B_mid + A_mid B_hi + A_hi B_mid + A_hi B_hi -- fp32 accuracy from six
- * bf16 MFMA products, which cost less matrix-core time than one fp32 MFMA product. */
-typedef enum { DASH_FP32 = 0, DASH_BF16_ACC32 = 1, DASH_FP16_ACC32 = 2, DASH_BF16X3 = 3, DASH_BF16X6 = 4 } dash_precision;
+ * bf16 MFMA products, which cost less matrix-core time than one fp32 MFMA product.
+ * DASH_FP16X3: two fp16 planes, hi = fp16(x), lo = fp16((x - hi) 2^11) kept scaled (unscaled it would be
+ * subnormal), the same three products as DASH_BF16X3 with the two low-plane terms scaled back by 2^-11 in the
+ * accumulator: 22 significand bits per operand -- close to fp32 accuracy from three fp16 MFMA products; fp16's
+ * exponent range applies to the iterates (entries above 65504 overflow and are flagged).
+ * The split modes serve every method. */
+typedef enum { DASH_FP32 = 0, DASH_BF16_ACC32 = 1, DASH_FP16_ACC32 = 2, DASH_BF16X3 = 3, DASH_BF16X6 = 4,
+               DASH_FP16X3 = 5 } dash_precision;
 
 /* ---- context ------------------------------------------------------------------- */
 

@@ -18,13 +18,13 @@ LIB_PATH = os.path.join(HERE, "libdash.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 NEWTON_DB, CHEBYSHEV, COUPLED_NEWTON = 0, 1, 2
 SCALE_FROBENIUS, SCALE_TRACE, SCALE_NONE, SCALE_POWER_ITERATION = 0, 1, 2, 3
-FP32, BF16_ACC32, FP16_ACC32, BF16X3, BF16X6 = 0, 1, 2, 3, 4
+FP32, BF16_ACC32, FP16_ACC32, BF16X3, BF16X6, FP16X3 = 0, 1, 2, 3, 4, 5
 
 _METHODS = {"newton_db": NEWTON_DB, "ndb": NEWTON_DB, "chebyshev": CHEBYSHEV, "cheb": CHEBYSHEV,
             "coupled_newton": COUPLED_NEWTON, "cn": COUPLED_NEWTON}
 _SCALINGS = {"frobenius": SCALE_FROBENIUS, "trace": SCALE_TRACE, "none": SCALE_NONE,
              "power_iteration": SCALE_POWER_ITERATION, "pi": SCALE_POWER_ITERATION}
-_PRECISIONS = {"fp32": FP32, "bf16": BF16_ACC32, "fp16": FP16_ACC32, "bf16x3": BF16X3, "bf16x6": BF16X6}
+_PRECISIONS = {"fp32": FP32, "bf16": BF16_ACC32, "fp16": FP16_ACC32, "bf16x3": BF16X3, "bf16x6": BF16X6, "fp16x3": FP16X3}
 
 
 class DashError(RuntimeError):

@@ -105,11 +105,10 @@ int f32_buffers(dash_method m, dash_precision prec) {
 }
 int bf16_buffers(dash_method m, dash_precision prec) {
     if (prec == DASH_FP32) return 0;
-    if (prec == DASH_BF16X3) return 10;            // Newton-DB only: five iterates, a high and a low plane each
-    if (prec == DASH_BF16X6)                        // three planes per iterate: five iterates (Newton-DB), nine
-        return m == DASH_NEWTON_DB ? 15 : m == DASH_COUPLED_NEWTON ? 27 : 9;      // (Coupled-Newton), S and two B_k (Clenshaw)
-    if (m == DASH_COUPLED_NEWTON) return 9;
-    return m == DASH_NEWTON_DB ? 5 : 3;
+    // 16-bit iterates: five (Newton-DB), nine (Coupled-Newton), S and two B_k (Clenshaw); one, two or three planes each
+    const int iterates = m == DASH_NEWTON_DB ? 5 : m == DASH_COUPLED_NEWTON ? 9 : 3;
+    const int planes = prec == DASH_BF16X6 ? 3 : (prec == DASH_BF16X3 || prec == DASH_FP16X3) ? 2 : 1;
+    return iterates * planes;
 }
 
 size_t per_block_bytes(int B, dash_method m, dash_precision prec) {
@@ -701,11 +700,11 @@ dash_status dash_gemm_batched(dash_ctx* c, int transA, int transB, const float* 
     if (!A || !Bm || !C) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
     if (!D && beta != 0.f) return fail(c, DASH_ERR_INVALID_ARG, "beta != 0 needs D");
     if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32 && precision != DASH_BF16X3 &&
-        precision != DASH_BF16X6)
+        precision != DASH_BF16X6 && precision != DASH_FP16X3)
         return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
-    c->half_kind = precision == DASH_FP16_ACC32 ? HALF_FP16 : HALF_BF16;
+    c->half_kind = (precision == DASH_FP16_ACC32 || precision == DASH_FP16X3) ? HALF_FP16 : HALF_BF16;
     const bool planes3 = precision == DASH_BF16X6;
-    const bool split = precision == DASH_BF16X3 || planes3;
+    const bool split = precision == DASH_BF16X3 || precision == DASH_FP16X3 || planes3;
     const size_t bytes = (size_t)N * B * B * sizeof(float);
     if (overlap(C, A, bytes) || overlap(C, Bm, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "C overlaps an operand");
     if (D && D != C && overlap(C, D, bytes)) return fail(c, DASH_ERR_INVALID_ARG, "D must equal C or be disjoint from it");
@@ -941,11 +940,9 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     if (method == DASH_COUPLED_NEWTON && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Coupled-Newton needs iters >= 1");
     if ((int)scaling < 0 || (int)scaling > 3) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
     if (precision != DASH_FP32 && precision != DASH_BF16_ACC32 && precision != DASH_FP16_ACC32 && precision != DASH_BF16X3 &&
-        precision != DASH_BF16X6)
+        precision != DASH_BF16X6 && precision != DASH_FP16X3)
         return fail(c, DASH_ERR_INVALID_ARG, "bad precision");
-    if (precision == DASH_BF16X3 && method != DASH_NEWTON_DB)
-        return fail(c, DASH_ERR_UNSUPPORTED, "two-plane split bf16 is built for Newton-DB only (three planes: every method)");
-    c->half_kind = precision == DASH_FP16_ACC32 ? HALF_FP16 : HALF_BF16;
+    c->half_kind = (precision == DASH_FP16_ACC32 || precision == DASH_FP16X3) ? HALF_FP16 : HALF_BF16;
     if (method == DASH_NEWTON_DB && iters < 1) return fail(c, DASH_ERR_INVALID_ARG, "Newton-DB needs iters >= 1");
     if (method == DASH_CHEBYSHEV) {
         if (iters < 2) return fail(c, DASH_ERR_INVALID_ARG, "Chebyshev needs degree >= 2");
@@ -969,6 +966,7 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
     const int P = norm_slabs(B);
     const int nbuf = f32_buffers(method, precision), nhbuf = bf16_buffers(method, precision);
     const bool lowp = precision != DASH_FP32;
+    const int planes = precision == DASH_BF16X6 ? 3 : (precision == DASH_BF16X3 || precision == DASH_FP16X3) ? 2 : 1;
     hipStream_t st = c->stream;
 
     for (int64_t b0 = 0; b0 < N; b0 += chunk) {
@@ -995,16 +993,14 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         DASH_TRY(compute_scales(c, Ac, nb, B, eps, scaling, p, sc, scale_out ? scale_out + b0 : sc.s));
 
         if (method == DASH_COUPLED_NEWTON && lowp) {
-            const bool planes3 = precision == DASH_BF16X6;
             DASH_TRY(cn_chunk_half(c, hbuf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf, nullptr,
-                                   planes3 ? hbuf + 9 : nullptr, planes3 ? hbuf + 18 : nullptr));
+                                   planes >= 2 ? hbuf + 9 : nullptr, planes == 3 ? hbuf + 18 : nullptr));
         } else if (method == DASH_COUPLED_NEWTON) {
             DASH_TRY(cn_chunk(c, buf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf));
         } else if (lowp && method == DASH_NEWTON_DB) {
             int idx = -1;
-            const bool planes3 = precision == DASH_BF16X6;
-            bf16_t** lows = precision == DASH_BF16X3 || planes3 ? hbuf + 5 : nullptr;     // low (middle) planes of the split modes
-            bf16_t** lows2 = planes3 ? hbuf + 10 : nullptr;                                // lowest planes of the three-plane mode
+            bf16_t** lows = planes >= 2 ? hbuf + 5 : nullptr;      // low (middle) planes of the split modes
+            bf16_t** lows2 = planes == 3 ? hbuf + 10 : nullptr;    // lowest planes of the three-plane mode
             if (p == 2) {
                 DASH_TRY(ndb_call_bf16(c, hbuf, lows, lows2, buf[0], -1, nb, B, iters, false, true, Ac, eps, inv_s, Xc, unscale, nf, &idx));
             } else {
@@ -1013,9 +1009,8 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
                 DASH_TRY(ndb_call_bf16(c, hbuf, lows, lows2, buf[0], idx, nb, B, iters, false, false, nullptr, 0.f, nullptr, Xc, unscale, nf, &idx2));
             }
         } else if (lowp) {
-            const bool planes3 = precision == DASH_BF16X6;
             DASH_TRY(clenshaw_chunk_bf16(c, buf, hbuf, Ac, Xc, nb, B, iters, cheb_coeffs, cheb_a, cheb_b, eps, inv_s, unscale, nf,
-                                         planes3 ? hbuf + 3 : nullptr, planes3 ? hbuf + 6 : nullptr));
+                                         planes >= 2 ? hbuf + 3 : nullptr, planes == 3 ? hbuf + 6 : nullptr));
         } else if (method == DASH_NEWTON_DB) {
             int idx = -1;
             if (p == 2) {

@@ -155,17 +155,19 @@ __global__ __launch_bounds__(NT) void scale_shift_kernel(const float* __restrict
         for (int i = 0; i < 4; ++i) t[i] = to_half(o2[i], half);
         *reinterpret_cast<v4s*>(h2 + off) = t;
     }
-    // low planes of the split representation x ~ hi + lo, lo = round(x - hi)
+    // low planes of the split representation x ~ hi + lo, lo = round(x - hi); with two fp16 planes the low plane is
+    // stored times 2^11 (it would go subnormal otherwise; the matmul kernel scales the sum of its segments back)
+    const float ls1 = (half == HALF_FP16 && !ll1) ? 2048.f : 1.f, ls2 = (half == HALF_FP16 && !ll2) ? 2048.f : 1.f;
     if (l1) {
         v4s t;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] = to_half(o1[i] - from_half(to_half(o1[i], half), half), half);
+        for (int i = 0; i < 4; ++i) t[i] = to_half((o1[i] - from_half(to_half(o1[i], half), half)) * ls1, half);
         *reinterpret_cast<v4s*>(l1 + off) = t;
     }
     if (l2) {
         v4s t;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] = to_half(o2[i] - from_half(to_half(o2[i], half), half), half);
+        for (int i = 0; i < 4; ++i) t[i] = to_half((o2[i] - from_half(to_half(o2[i], half), half)) * ls2, half);
         *reinterpret_cast<v4s*>(l2 + off) = t;
     }
     // third planes, x ~ hi + mid + lo: lo = round(x - hi - mid)

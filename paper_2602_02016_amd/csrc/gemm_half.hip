@@ -51,6 +51,7 @@ typedef u16 v4s __attribute__((ext_vector_type(4)));
 
 // the two 16-bit operand formats: conversion from fp32 (round to nearest even) and the MFMA
 struct Bf16 {
+    static constexpr float LO_SCALE = 1.f;      // bf16 has the exponent range of fp32: low planes need no scaling
     typedef __bf16 v8 __attribute__((ext_vector_type(8)));
     static __device__ __forceinline__ u16 from_float(float v) {
         union { __bf16 h; u16 u; } x; x.h = (__bf16)v; return x.u;
@@ -64,6 +65,9 @@ struct Bf16 {
     }
 };
 struct Fp16 {
+    // two-plane mode: the low plane is 2^-11 of the value or less and would go subnormal in fp16 for |x| < 0.125;
+    // it is stored times 2^11, and the sum of the two segments that read a low plane is scaled back once
+    static constexpr float LO_SCALE = 2048.f;
     typedef _Float16 v8 __attribute__((ext_vector_type(8)));
     static __device__ __forceinline__ u16 from_float(float v) {
         union { _Float16 h; u16 u; } x; x.h = (_Float16)v; return x.u;
@@ -245,6 +249,7 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
 
     const int KS = B / HBK;             // slabs per segment
     const int KT = nseg * KS;           // slabs in all
+    const int scale_at = nseg == 3 ? 2 * KS : -1;     // first slab of the high-high segment of a two-plane product
     unsigned offa[NV], offb[NV];
     hdma_offsets<TILE, A_KC>(B, row0, wave, lane, offa);
     hdma_offsets<TILE, B_KC>(B, col0, wave, lane, offb);
@@ -313,6 +318,14 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
             constexpr int sg = decltype(S)::value;
             const int h = h0 + sg;
             if (h < KT) {
+                if (H::LO_SCALE != 1.f && h == scale_at) {       // the two low-plane segments are done: undo their scale
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+#pragma unroll
+                        for (int j = 0; j < MT; ++j)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) acc[i][j][r] *= 1.f / H::LO_SCALE;
+                }
                 const char* cur = stage(S);
                 static_for<STEPS - 1>([&](auto ST) {
                     frags(cur, std::integral_constant<int, decltype(ST)::value + 1>{});
@@ -344,9 +357,10 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
     u16* __restrict__ Hb = P.Ch ? static_cast<u16*>(P.Ch) + boff : nullptr;
     u16* __restrict__ H2b = P.C2h ? static_cast<u16*>(P.C2h) + boff : nullptr;
     u16* __restrict__ H2lb = P.C2l ? static_cast<u16*>(P.C2l) + boff : nullptr;     // planes of the second output
-    u16* __restrict__ H2l2b = P.C2l2 ? static_cast<u16*>(P.C2l2) + boff : nullptr;  // (both or neither)
+    u16* __restrict__ H2l2b = P.C2l2 ? static_cast<u16*>(P.C2l2) + boff : nullptr;  // (with Cl2, as for the first output)
     u16* __restrict__ Lb = P.Cl ? static_cast<u16*>(P.Cl) + boff : nullptr;    // low plane of the result
     u16* __restrict__ L2b = P.Cl2 ? static_cast<u16*>(P.Cl2) + boff : nullptr; // third plane (with Lb only)
+    const float lo_scale = P.Cl2 ? 1.f : H::LO_SCALE;     // two-plane results: the low plane is stored scaled
     const float a2 = P.a2, g2 = P.g2;
     // symmetric mode: an off-diagonal tile is also written transposed
     const bool mirror = g.sym && ti != tj;
@@ -408,7 +422,7 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
 #pragma unroll
                         for (int m = 0; m < 4; ++m) {
                             rest[m] = v[m] - H::to_float(h[m]);
-                            lo[m] = H::from_float(rest[m]);
+                            lo[m] = H::from_float(rest[m] * lo_scale);
                         }
                         *reinterpret_cast<v4s*>(Lb + off) = lo;
                         if (L2b) {
@@ -433,11 +447,11 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
 #pragma unroll
                         for (int m = 0; m < 4; ++m) {
                             const float rest = w[m] - H::to_float(h2[m]);
-                            lo[m] = H::from_float(rest);
-                            lo2[m] = H::from_float(rest - H::to_float(lo[m]));
+                            lo[m] = H::from_float(rest * lo_scale);
+                            lo2[m] = H::from_float(rest - H::to_float(lo[m]));    // (three planes: lo_scale is 1)
                         }
                         *reinterpret_cast<v4s*>(H2lb + off) = lo;
-                        *reinterpret_cast<v4s*>(H2l2b + off) = lo2;
+                        if (H2l2b) *reinterpret_cast<v4s*>(H2l2b + off) = lo2;
                     }
                 }
                 if (mirror) *reinterpret_cast<v4f*>(sp) = v;       // final values for phase C
@@ -470,7 +484,7 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
 #pragma unroll
                         for (int m = 0; m < 4; ++m) {
                             rest[m] = v[m] - H::to_float(h[m]);
-                            lo[m] = H::from_float(rest[m]);
+                            lo[m] = H::from_float(rest[m] * lo_scale);
                         }
                         *reinterpret_cast<v4s*>(Lb + moff) = lo;
                         if (L2b) {
@@ -491,11 +505,11 @@ __global__ __launch_bounds__(HCfg<TILE>::NT, HCfg<TILE>::OCC) void gemm_half_ker
 #pragma unroll
                         for (int m = 0; m < 4; ++m) {
                             const float rest = a2 * v[m] - H::to_float(h2[m]);
-                            lo[m] = H::from_float(rest);
-                            lo2[m] = H::from_float(rest - H::to_float(lo[m]));
+                            lo[m] = H::from_float(rest * lo_scale);
+                            lo2[m] = H::from_float(rest - H::to_float(lo[m]));    // (three planes: lo_scale is 1)
                         }
                         *reinterpret_cast<v4s*>(H2lb + moff) = lo;
-                        *reinterpret_cast<v4s*>(H2l2b + moff) = lo2;
+                        if (H2l2b) *reinterpret_cast<v4s*>(H2l2b + moff) = lo2;
                     }
                 }
             }

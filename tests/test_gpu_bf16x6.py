@@ -131,14 +131,3 @@ def test_coupled_newton_reaches_the_fp32_floor(dash, p, B):
         e[prec] = rel_frobenius_error(X, X_evd).max()
     print(f"cn p={p} B={B} k={k}: vs EVD fp32 {e['fp32']:.2e}  bf16x6 {e['bf16x6']:.2e}  fp16 {e['fp16']:.2e}", flush=True)
     assert e["bf16x6"] < 3 * e["fp32"] + 1e-6 and e["bf16x6"] < e["fp16"] / 10
-
-
-def test_unsupported_methods(dash):
-    """Two planes are built for Newton-DB only."""
-    from paper_2602_02016_amd import DashError, chebyshev_fit
-    A32, _, _ = workloads.spd_stack(2, 64, -1.0, 0.0, seed=145)
-    with pytest.raises(DashError):
-        dash.inverse_root(_to_gpu(A32), method="coupled_newton", p=2, iters=4, precision="bf16x3")
-    with pytest.raises(DashError):
-        dash.inverse_root(_to_gpu(A32), method="chebyshev", p=2, iters=8, precision="bf16x3",
-                          cheb_coeffs=chebyshev_fit(2, 8, 0.1, 1.0), cheb_a=0.1, cheb_b=1.0)
