@@ -38,7 +38,7 @@ def _oracle_step(grads, state, beta, eps, refresh):
     return out, new
 
 
-@pytest.mark.parametrize("precision", ["fp32", "bf16x6"])
+@pytest.mark.parametrize("precision", ["fp32", "bf16x6", "fp16x3"])
 @pytest.mark.parametrize("ws_cap", [None, 3 << 20])
 def test_model_step_matches_per_layer_oracle(dash, ws_cap, precision):
     import torch

@@ -23,7 +23,7 @@ def _to_gpu(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.mark.parametrize("precision", ["fp32", "bf16x6"])
+@pytest.mark.parametrize("precision", ["fp32", "bf16x6", "fp16x3"])
 @pytest.mark.parametrize("N,B,warm", [(4, 128, 6), (3, 256, 4), (2, 512, 3)])
 def test_step_against_oracle(dash, N, B, warm, precision):
     """Factors are EMAs of seeded N(0, 1e-2^2) gradients (Wishart-like, well conditioned once
