@@ -67,7 +67,7 @@ def sweep(dash, only_16bit=False):
     precision.  Timing does not depend on the values, so the stacks are well-conditioned random SPD
     blocks; accuracy on the configurations' own spectra is the business of tests/test_gpu_configs.py.
     Returns a list of records; `mfma_frac` prices the executed flops against the peak of the operand type.
-    `only_16bit` keeps the five 16-bit cases on the cfg5 shape (short enough to run under a kernel trace)."""
+    `only_16bit` keeps the 16-bit cases on the cfg5 shape (short enough to run under a kernel trace)."""
     import torch
     from paper_2602_02016_amd import chebyshev_fit
     rows = []
@@ -91,6 +91,8 @@ def sweep(dash, only_16bit=False):
             for d in (8, 16, 32):
                 cases.append(("chebyshev", pp, d, "fp32"))
             cases.append(("coupled_newton", pp, 10, "fp32"))
+        if cfg != "cfg5":          # the fastest fp32-accurate mode on the smaller shapes as well
+            cases += [("newton_db", 4, 10, "fp16x3"), ("coupled_newton", 4, 10, "fp16x3")]
         if cfg == "cfg5":
             cases += [("newton_db", 4, 10, "bf16"), ("newton_db", 4, 10, "fp16"), ("newton_db", 4, 10, "bf16x3"),
                       ("newton_db", 4, 10, "bf16x6"), ("chebyshev", 4, 16, "bf16x6"),
