@@ -106,3 +106,22 @@ def test_chebyshev_two_planes(dash, prec, p):
     e = rel_frobenius_error(X, ocheb.inverse_root_chebyshev(A, p, np.array(coef), a, b)).max()
     print(f"cheb {prec} p={p}: vs f64 Clenshaw {e:.2e}", flush=True)
     assert e < (1e-5 if prec == "fp16x3" else 3e-4)
+
+
+def test_overflow_is_flagged_not_hidden(dash):
+    """fp16's exponent range applies to the iterates: a block whose inverse square root has entries beyond 65504
+    (kappa = 1e12, no damping) overflows; the per-block flag says so for exactly the blocks whose result is not
+    finite, and a well-conditioned block in the same stack is untouched by its neighbour."""
+    N, B, p = 3, 128, 4
+    bad, _, _ = workloads.spd_stack(2, B, -12.0, 0.0, seed=167)
+    good, _, _ = workloads.spd_stack(1, B, -1.0, 0.0, seed=168)
+    A32 = np.concatenate([bad[:1], good, bad[1:]])
+    nf = _to_gpu(np.zeros(N, dtype=np.int32))
+    X = dash.inverse_root(_to_gpu(A32), p=p, iters=30, eps=0.0, precision="fp16x3", nonfinite_out=nf).cpu().numpy()
+    flags = nf.cpu().numpy()
+    for i in range(N):
+        assert bool(flags[i]) == (not np.isfinite(X[i]).all()), (i, flags)
+    assert flags[1] == 0
+    e = rel_frobenius_error(X[1:2], inverse_root_evd(good.astype(np.float64), p))[0]
+    print(f"fp16x3 overflow: flags {flags.tolist()}, good block vs EVD {e:.2e}", flush=True)
+    assert e < 1e-5
