@@ -125,3 +125,26 @@ def test_overflow_is_flagged_not_hidden(dash):
     e = rel_frobenius_error(X[1:2], inverse_root_evd(good.astype(np.float64), p))[0]
     print(f"fp16x3 overflow: flags {flags.tolist()}, good block vs EVD {e:.2e}", flush=True)
     assert e < 1e-5
+
+
+@pytest.mark.parametrize("B", [64, 192, 320, 448, 768])
+@pytest.mark.parametrize("N", [1, 5])
+def test_split_modes_agree_with_fp32_on_odd_block_edges(dash, N, B):
+    """Block edges that are multiples of 64 only (64-wide tiles, odd tile counts) and of 256 times an odd number:
+    every split mode, every method, against the fp32 path on the same well-conditioned blocks."""
+    from paper_2602_02016_amd import chebyshev_fit
+    A32, _, lam = workloads.spd_stack(N, B, -1.0, 0.0, seed=170 + B)
+    A = _to_gpu(A32)
+    s = np.sqrt((A32.astype(np.float64) ** 2).sum(axis=(1, 2)))
+    a = float((lam.min(axis=1) / s).min()) * 0.99
+    cases = {"newton_db": dict(iters=14), "coupled_newton": dict(iters=20),
+             "chebyshev": dict(iters=24, cheb_coeffs=chebyshev_fit(4, 24, a, 1.0), cheb_a=a, cheb_b=1.0)}
+    for method, kw in cases.items():
+        X32 = dash.inverse_root(A, method=method, p=4, eps=1e-6, **kw).cpu().numpy()
+        for prec in ("fp16x3", "bf16x6", "bf16x3"):
+            nf = _to_gpu(np.zeros(N, dtype=np.int32))
+            X = dash.inverse_root(A, method=method, p=4, eps=1e-6, precision=prec, nonfinite_out=nf, **kw).cpu().numpy()
+            e = rel_frobenius_error(X, X32.astype(np.float64)).max()
+            assert int(nf.sum().item()) == 0
+            assert e < (2e-4 if prec == "bf16x3" else 2e-5), (method, prec, B, N, e)
+    print(f"split modes vs fp32 ok N={N} B={B}", flush=True)
