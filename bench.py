@@ -329,6 +329,18 @@ def main():
         pi_variant = {"scaling": "2*lambda_PI, 4 sweeps, pool 16", "ndb_iters": 5, "ms": pi_ms,
                       "blocks_per_s": 2 * N / (pi_ms * 1e-3),
                       "rel_diff_to_headline_roots": diff}
+        # and both together: that scaling with two-plane split fp16 operands (DASH_FP16X3)
+        dash.inverse_root(S, Xp, p=p, iters=5, eps=eps, scaling="pi", precision="fp16x3", nonfinite_out=nf)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(reps):
+            dash.inverse_root(S, Xp, p=p, iters=5, eps=eps, scaling="pi", precision="fp16x3", nonfinite_out=nf)
+        torch.cuda.synchronize()
+        pi3_ms = (time.perf_counter() - t2) * 1e3 / reps
+        X5 = Xp[:2].cpu().numpy().astype(np.float64)
+        diff3 = float(max(np.linalg.norm(X5[i] - X10[i]) / np.linalg.norm(X10[i]) for i in range(2)))
+        pi_variant["with_fp16x3_operands"] = {"ms": pi3_ms, "blocks_per_s": 2 * N / (pi3_ms * 1e-3),
+                                              "rel_diff_to_headline_roots": diff3}
         del Xp
 
     # the same roots with split 16-bit operands (context, not the headline): three bf16 planes and six plane
