@@ -11,7 +11,8 @@ import workloads
 pytestmark = pytest.mark.gpu
 
 
-def test_captured_inverse_root_and_step_replay_bit_identical():
+@pytest.mark.parametrize("precision", ["fp32", "fp16x3"])
+def test_captured_inverse_root_and_step_replay_bit_identical(precision):
     import torch
     from paper_2602_02016_amd import Dash
     d = Dash(0)
@@ -22,14 +23,14 @@ def test_captured_inverse_root_and_step_replay_bit_identical():
     X = torch.empty_like(A)
     G = torch.zeros(N, B, B, device="cuda")
     S = torch.zeros(2 * N, B, B, device="cuda"); XS = torch.zeros_like(S); U = torch.zeros_like(G)
-    d.ensure_workspace(2 * N, B, "newton_db", 4)          # sized before capture: nothing allocates inside
+    d.ensure_workspace(2 * N, B, "newton_db", 4, precision)          # sized before capture: nothing allocates inside
     torch.cuda.synchronize()
     d.set_stream(s)
     g_root, g_step = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
     with torch.cuda.graph(g_root, stream=s):
-        d.inverse_root(A, X, method="newton_db", p=4, iters=10, eps=1e-6)
+        d.inverse_root(A, X, method="newton_db", p=4, iters=10, eps=1e-6, precision=precision)
     with torch.cuda.graph(g_step, stream=s):
-        d.step(G, S, XS, U, beta=0.95, eps=1e-6, method="newton_db", p=4, iters=10)
+        d.step(G, S, XS, U, beta=0.95, eps=1e-6, method="newton_db", p=4, iters=10, precision=precision)
     torch.cuda.synchronize()
     d.set_stream(torch.cuda.current_stream())
     S_eager = torch.zeros_like(S); XS_eager = torch.zeros_like(S); U_eager = torch.zeros_like(G)
@@ -43,8 +44,8 @@ def test_captured_inverse_root_and_step_replay_bit_identical():
         g_step.replay()
         torch.cuda.synchronize()
         X_replay, U_replay, S_replay = X.clone(), U.clone(), S.clone()
-        X_e = d.inverse_root(A, method="newton_db", p=4, iters=10, eps=1e-6)
-        d.step(G, S_eager, XS_eager, U_eager, beta=0.95, eps=1e-6, method="newton_db", p=4, iters=10)
+        X_e = d.inverse_root(A, method="newton_db", p=4, iters=10, eps=1e-6, precision=precision)
+        d.step(G, S_eager, XS_eager, U_eager, beta=0.95, eps=1e-6, method="newton_db", p=4, iters=10, precision=precision)
         torch.cuda.synchronize()
         assert torch.equal(X_replay, X_e), rep
         assert torch.equal(S_replay, S_eager) and torch.equal(U_replay, U_eager), rep
@@ -57,7 +58,7 @@ def test_captured_inverse_root_and_step_replay_bit_identical():
             fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / n * 1e6
-    t_eager = timed(lambda: d.inverse_root(A, X, method="newton_db", p=4, iters=10, eps=1e-6))
+    t_eager = timed(lambda: d.inverse_root(A, X, method="newton_db", p=4, iters=10, eps=1e-6, precision=precision))
     t_graph = timed(g_root.replay)
-    print(f"cfg1 inverse root (N={N}, B={B}, p=4, k=10): eager {t_eager:.0f} us, graph replay {t_graph:.0f} us", flush=True)
+    print(f"cfg1 inverse root (N={N}, B={B}, p=4, k=10, {precision}): eager {t_eager:.0f} us, graph replay {t_graph:.0f} us", flush=True)
     d.close()
