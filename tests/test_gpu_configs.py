@@ -72,6 +72,19 @@ def test_config2_full_step(dash):
     assert max(eXL, eXR) < 1e-4
     assert eU < 1e-4
     assert int(nf.sum().item()) == 0
+    # the same roots with split 16-bit operands, to the same bar
+    for prec in ("fp16x3", "bf16x6"):
+        X2 = torch.empty_like(S)
+        dash.inverse_root(S, X2, p=c["p"], iters=c["ndb_iters"], eps=c["eps"], precision=prec, nonfinite_out=nf)
+        U2 = torch.empty_like(U)
+        dash.precondition(X2[:N], _to_gpu(G), X2[N:], U2)
+        torch.cuda.synchronize()
+        eX = max(rel_frobenius_error(X2[:N][idx].cpu().numpy(), ref["X_L"]).max(),
+                 rel_frobenius_error(X2[N:][idx].cpu().numpy(), ref["X_R"]).max())
+        eU2 = rel_frobenius_error(U2[idx].cpu().numpy(), ref["U"]).max()
+        print(f"cfg2 with {prec} operands: roots {eX:.2e} update {eU2:.2e}", flush=True)
+        assert eX < 1e-4 and eU2 < 1e-4 and int(nf.sum().item()) == 0
+        del X2, U2
     # properties that hold for every block, sampled or not: symmetric roots, finite update
     Xs = X.cpu().numpy()
     asym = np.sqrt(((Xs - np.swapaxes(Xs, 1, 2)) ** 2).sum(axis=(1, 2))) / np.sqrt((Xs ** 2).sum(axis=(1, 2)))
