@@ -29,6 +29,9 @@
 #include <type_traits>
 #include <utility>
 
+#ifndef DASH_HALF_SPLIT_COND
+#define DASH_HALF_SPLIT_COND
+#endif
 namespace dash {
 
 // compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  The accumulator
@@ -547,8 +550,33 @@ int gemm_half_tile_edge(const GemmLaunch& g) {
     return gemm_tile_edge(g);
 }
 
+static hipError_t launch_half_edge(const GemmLaunch& g, int edge, hipStream_t stream);
+
 hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream) {
     const int edge = gemm_half_tile_edge(g);
+#ifndef DASH_NO_HALF_SPLIT
+    // A 256 tile fills a CU, so a launch runs in rounds of 256 workgroups.  A symmetric launch whose last round would
+    // be at most half full (the residual on 32 blocks: 320 workgroups) computes the blocks of the whole rounds with
+    // 256 tiles and the remaining blocks with 128 tiles in a second launch.
+    if (edge == 256 && g.sym && g.prob[0].A2 DASH_HALF_SPLIT_COND) {
+        const int64_t t = g.B / 256, per_block = g.nprob * t * (t + 1) / 2, W = g.nblocks * per_block;
+        const int64_t rem = W % 256;
+        const int64_t n_main = (W - rem) / per_block;
+        if (W > 256 && rem > 0 && rem <= 128 && n_main >= 1 && n_main < g.nblocks) {
+            GemmLaunch a = g, b = g;
+            a.nblocks = n_main;
+            b.blk0 = g.blk0 + n_main;
+            b.nblocks = g.nblocks - n_main;
+            hipError_t e = launch_half_edge(a, 256, stream);
+            if (e != hipSuccess) return e;
+            return launch_half_edge(b, 128, stream);
+        }
+    }
+#endif
+    return launch_half_edge(g, edge, stream);
+}
+
+static hipError_t launch_half_edge(const GemmLaunch& g, int edge, hipStream_t stream) {
     if (g.half == HALF_BF16)
         return edge == 256 ? hlaunch_tile<Bf16, 256>(g, stream)
                            : edge == 128 ? hlaunch_tile<Bf16, 128>(g, stream) : hlaunch_tile<Bf16, 64>(g, stream);
