@@ -92,7 +92,7 @@ def sweep(dash, only_16bit=False):
                 cases.append(("chebyshev", pp, d, "fp32"))
             cases.append(("coupled_newton", pp, 10, "fp32"))
         if cfg != "cfg5":          # the fastest fp32-accurate mode on the smaller shapes as well
-            cases += [("newton_db", 4, 10, "fp16x3"), ("coupled_newton", 4, 10, "fp16x3")]
+            cases += [("newton_db", 4, 10, "fp16x3"), ("coupled_newton", 4, 10, "fp16x3"), ("chebyshev", 4, 16, "fp16x3")]
         if cfg == "cfg5":
             cases += [("newton_db", 4, 10, "bf16"), ("newton_db", 4, 10, "fp16"), ("newton_db", 4, 10, "bf16x3"),
                       ("newton_db", 4, 10, "bf16x6"), ("chebyshev", 4, 16, "bf16x6"),
