@@ -29,6 +29,9 @@
 #include <type_traits>
 #include <utility>
 
+#ifndef DASH_H256_MIN
+#define DASH_H256_MIN 128      // workgroups a launch must have for the 256 tile (measured: 96 and 64 lose, 160 and 256 lose)
+#endif
 #ifndef DASH_HALF_SPLIT_COND
 #define DASH_HALF_SPLIT_COND
 #endif
@@ -539,13 +542,14 @@ hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
 
 }  // namespace
 
-// tile edge of a 16-bit launch: 256 when the block edge allows it and the launch still gives every CU a
-// workgroup, else as the fp32 kernel.  (A 256 tile of four wavefronts with 128 x 128 each, accumulators in
+// tile edge of a 16-bit launch: 256 when the block edge allows it and the launch still gives half the CUs a
+// workgroup (a 256 tile on half the chip beats 128 tiles on all of it: 4 x 2048 Clenshaw 3.36 -> 3.00 ms,
+// Newton-DB on 16 to 24 blocks of 1024 4 % faster), else as the fp32 kernel.  (A 256 tile of four wavefronts with 128 x 128 each, accumulators in
 // AGPRs, was also built: one wavefront per SIMD cannot hide its own latencies, 500-560 TFLOP/s.)
 int gemm_half_tile_edge(const GemmLaunch& g) {
 #ifndef DASH_NO_TILE256
     const int64_t t = g.B / 256;
-    if (g.B % 256 == 0 && g.nblocks * g.nprob * (g.sym ? t * (t + 1) / 2 : t * t) >= 256) return 256;
+    if (g.B % 256 == 0 && g.nblocks * g.nprob * (g.sym ? t * (t + 1) / 2 : t * t) >= DASH_H256_MIN) return 256;
 #endif
     return gemm_tile_edge(g);
 }
