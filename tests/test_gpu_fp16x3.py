@@ -148,3 +148,21 @@ def test_split_modes_agree_with_fp32_on_odd_block_edges(dash, N, B):
             assert int(nf.sum().item()) == 0
             assert e < (2e-4 if prec == "bf16x3" else 2e-5), (method, prec, B, N, e)
     print(f"split modes vs fp32 ok N={N} B={B}", flush=True)
+
+
+@pytest.mark.parametrize("method,k", [("newton_db", 20), ("coupled_newton", 30)])
+@pytest.mark.parametrize("B", [256, 512])
+def test_illconditioned_blocks_kappa_1e4(dash, method, k, B):
+    """Spectra log-uniform in [1e-4, 1], no damping (the shape of the block-size sweep): at the floor of the fp32
+    path or below it."""
+    N, p = 3, 4
+    A32, _, _ = workloads.spd_stack(N, B, -4.0, 0.0, seed=500 + B, share_q=True)
+    X_evd = inverse_root_evd(A32.astype(np.float64), p)
+    e = {}
+    for prec in ("fp32", "fp16x3", "bf16x6"):
+        nf = _to_gpu(np.zeros(N, dtype=np.int32))
+        X = dash.inverse_root(_to_gpu(A32), method=method, p=p, iters=k, precision=prec, nonfinite_out=nf).cpu().numpy()
+        assert int(nf.sum().item()) == 0
+        e[prec] = rel_frobenius_error(X, X_evd).max()
+    print(f"{method} B={B} kappa=1e4 k={k}: vs EVD fp32 {e['fp32']:.2e}  fp16x3 {e['fp16x3']:.2e}  bf16x6 {e['bf16x6']:.2e}", flush=True)
+    assert e["fp16x3"] < 2 * e["fp32"] + 1e-5 and e["bf16x6"] < 2 * e["fp32"] + 1e-5
