@@ -559,11 +559,12 @@ static hipError_t launch_half_edge(const GemmLaunch& g, int edge, hipStream_t st
 hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream) {
     const int edge = gemm_half_tile_edge(g);
 #ifndef DASH_NO_HALF_SPLIT
-    // A 256 tile fills a CU, so a launch runs in rounds of 256 workgroups.  A symmetric launch whose last round would
-    // be at most half full (the residual on 32 blocks: 320 workgroups) computes the blocks of the whole rounds with
-    // 256 tiles and the remaining blocks with 128 tiles in a second launch.
-    if (edge == 256 && g.sym && g.prob[0].A2 DASH_HALF_SPLIT_COND) {
-        const int64_t t = g.B / 256, per_block = g.nprob * t * (t + 1) / 2, W = g.nblocks * per_block;
+    // A 256 tile fills a CU, so a launch runs in rounds of 256 workgroups.  A launch of a split mode (several K
+    // segments per product: long enough to pay for a second launch) whose last round would be at most half full
+    // (the symmetric residual on 32 blocks: 320 workgroups) computes the blocks of the whole rounds with 256 tiles
+    // and the remaining blocks with 128 tiles in a second launch.
+    if (edge == 256 && g.prob[0].A2 DASH_HALF_SPLIT_COND) {
+        const int64_t t = g.B / 256, per_block = g.nprob * (g.sym ? t * (t + 1) / 2 : t * t), W = g.nblocks * per_block;
         const int64_t rem = W % 256;
         const int64_t n_main = (W - rem) / per_block;
         if (W > 256 && rem > 0 && rem <= 128 && n_main >= 1 && n_main < g.nblocks) {
