@@ -369,10 +369,25 @@ def main():
                 dash.inverse_root(S, Xs, p=p, iters=k, eps=eps, precision=prec, nonfinite_out=nf)
             torch.cuda.synchronize()
             v_ms = (time.perf_counter() - t3) * 1e3 / reps
+            # the 16-bit kernel's own roofline on these calls: HIP events around each of its launches (a second,
+            # instrumented pass; the library counts one product per multi-segment product, hence the factor)
+            segs = 6 if prec == "bf16x6" else 3
+            dash.reset_stats(); dash.set_timing(True)
+            for _ in range(max(1, reps // 2)):
+                dash.inverse_root(S, Xs, p=p, iters=k, eps=eps, precision=prec, nonfinite_out=nf)
+            torch.cuda.synchronize()
+            sv = dash.get_stats(); dash.set_timing(False)
+            half_tflops = segs * sv["variant_flops"][0] / (sv["variant_ms"][0] * 1e-3) / 1e12
             dv = float(((Xs[:2] - X[:2]).double().flatten(1).norm(dim=1) / X[:2].double().flatten(1).norm(dim=1)).max())
             rec = {"precision": prec + " (" + notes[prec] + ")", "ndb_iters": k, "ms": v_ms,
                    "blocks_per_s": 2 * N / (v_ms * 1e-3), "speedup_over_fp32_roots": root_ms / v_ms,
-                   "rel_diff_to_headline_roots": dv, "residual_fp32": res32, "residual": residual(Xs[0], S[0])}
+                   "rel_diff_to_headline_roots": dv, "residual_fp32": res32, "residual": residual(Xs[0], S[0]),
+                   "roofline": {"bound": "mfma", "kernel": "dash::gemm_half_kernel<dash::%s, 256, false, false>"
+                                                            % ("Bf16" if prec == "bf16x6" else "Fp16"),
+                                "achieved": half_tflops, "peak": 2500.0, "unit": "TFLOP/s", "frac": half_tflops / 2500.0,
+                                "launches_per_call": sv["variant_launches"][0] / max(1, reps // 2),
+                                "mean_launch_ms": sv["variant_ms"][0] / max(sv["variant_launches"][0], 1),
+                                "note": "MFMA work of the K segments executed (symmetric launches: computed tiles only)"}}
             Us = torch.empty_like(U)
             dash.step(grads[0], S, Xs, Us, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf, precision=prec)
             torch.cuda.synchronize()
