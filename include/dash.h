@@ -218,6 +218,18 @@ dash_status dash_precondition_vector(dash_ctx* ctx, const float* Linv, const flo
 dash_status dash_block_norms(dash_ctx* ctx, const float* A, int64_t N, int B, float eps,
                              dash_scaling scaling, float* s_out);
 
+/* dash_block_norms for callers that cannot allocate and have no workspace to hand over: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit for bit
+ * the same s_out as dash_block_norms, but the slab partial sums go to a 2 MiB array that is part of the
+ * library's device image (one copy per GPU, held until the process ends) instead of the context's workspace:
+ * no workspace is needed and the call allocates nothing.  Limits: N <= 16384 blocks (DASH_ERR_INVALID_ARG
+ * beyond that); scaling Frobenius, trace or none (DASH_ERR_UNSUPPORTED for power iteration, whose pool
+ * vectors need a workspace).  Every call on one GPU, from any context, uses that GPU's one array: calls that
+ * overlap in time on one GPU (different streams or contexts) race; calls on one stream are ordered.  Nothing
+ * has to be cleared between calls (each call writes every partial sum before it reads it). */
+dash_status dash_block_norms_static(dash_ctx* ctx, const float* A, int64_t N, int B, float eps,
+                                    dash_scaling scaling, float* s_out);
+
 /* ---- inverse roots (Section 3.3 Newton-DB; Appendix A Chebyshev) ----------------- */
 
 /* X_i <- approximately (A_i + eps I)^(-1/p), p in {2, 4}.

@@ -130,6 +130,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_model_set_arena.argtypes = [vp, vp, C.c_size_t]
     lib.dash_model_step.argtypes = [vp, C.POINTER(_ModelStepArgs)]
     lib.dash_block_norms.argtypes = [vp, vp, i64, i32, f32, i32, vp]
+    lib.dash_block_norms_static.argtypes = [vp, vp, i64, i32, f32, i32, vp]
     lib.dash_inverse_root.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, f32, i32, i32,
                                       C.POINTER(f64), f64, f64, vp, vp]
     lib.dash_chebyshev_fit.argtypes = [i32, i32, f64, f64, i32, C.POINTER(f64)]
@@ -145,6 +146,7 @@ def load_library(path: str = LIB_PATH):
                  "dash_model_step",
                  "dash_precondition_rect", "dash_accumulate_vector", "dash_precondition_vector",
                  "dash_get_stats", "dash_gemm_batched", "dash_accumulate_factors", "dash_block_norms",
+                 "dash_block_norms_static",
                  "dash_inverse_root", "dash_chebyshev_fit", "dash_precondition", "dash_graft_update", "dash_step"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -381,6 +383,14 @@ class Dash:
         self.ensure_workspace(max(n, 1), b, "chebyshev")
         self._check(self.lib.dash_block_norms(self.h, self._stack(A, "A"), n, b, eps, _enum(_SCALINGS, scaling),
                                               self._vec(out, "s_out", n, torch.float32)))
+        return out
+
+    def block_norms_static(self, A, out, eps: float = 0.0, scaling="frobenius"):
+        """dash_block_norms_static: as block_norms, on the library's static scratch; `out` is the caller's
+        [N] float32 device tensor (nothing is allocated here either)."""
+        n, b = A.shape[0], A.shape[1]
+        self._check(self.lib.dash_block_norms_static(self.h, self._stack(A, "A"), n, b, eps, _enum(_SCALINGS, scaling),
+                                                     self._vec(out, "s_out", n, self._torch.float32)))
         return out
 
     def inverse_root(self, A, X=None, method="newton_db", p: int = 4, iters: int = 10, eps: float = 0.0,

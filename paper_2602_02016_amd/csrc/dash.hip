@@ -41,7 +41,16 @@ struct dash_ctx {
     // multi-Power-Iteration scaling: pool size, sweeps, start vectors [pi_rows][pi_pool] on the device
     int pi_pool = 0, pi_sweeps = 0, pi_rows = 0;
     const float* pi_v0 = nullptr;
+    // this device's copy of the file-scope scratch array (its device address, resolved in dash_create)
+    float* static_scratch = nullptr;
 };
+
+// Scratch of dash_block_norms_static: the slab partial sums of up to DASH_STATIC_MAX_BLOCKS blocks (32 per
+// block), 2 MiB, held by every GPU the library runs on until the process ends.  In host code this name is
+// only a handle for hipGetSymbolAddress; kernels and host calls use the address resolved per device.
+constexpr int64_t STATIC_MAX_BLOCKS = 16384;
+constexpr int STATIC_SLABS = 32;
+static __device__ __align__(256) float scratch[STATIC_MAX_BLOCKS * STATIC_SLABS];
 
 namespace {
 
@@ -608,6 +617,13 @@ dash_status dash_create(dash_ctx** out, int device, void* hip_stream) {
     if (!c) return DASH_ERR_HIP;
     c->device = device;
     c->stream = (hipStream_t)hip_stream;
+    // device address of this GPU's copy of the static scratch array (the device is current here)
+    void* sp = nullptr;
+    if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp) {
+        delete c;
+        return DASH_ERR_HIP;
+    }
+    c->static_scratch = static_cast<float*>(sp);
     *out = c;
     return DASH_OK;
 }
@@ -905,6 +921,28 @@ dash_status dash_block_norms(dash_ctx* c, const float* A, int64_t N, int B, floa
         if (!sc.carve(cv, nb, B)) return fail(c, DASH_ERR_WORKSPACE, "internal: workspace carve failed");
         DASH_TRY(compute_scales(c, A + (size_t)b0 * B * B, nb, B, eps, scaling, 2, sc, s_out + b0));
     }
+    return DASH_OK;
+}
+
+dash_status dash_block_norms_static(dash_ctx* c, const float* A, int64_t N, int B, float eps, dash_scaling scaling,
+                                    float* s_out) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    if (N < 0 || !valid_B(B)) return fail(c, DASH_ERR_INVALID_ARG, "N must be >= 0 and B a multiple of 64");
+    if (scaling == DASH_SCALE_POWER_ITERATION)
+        return fail(c, DASH_ERR_UNSUPPORTED, "dash_block_norms_static: power-iteration scaling needs the pool vectors of "
+                                             "a workspace; use dash_block_norms");
+    if ((int)scaling < 0 || (int)scaling > 2) return fail(c, DASH_ERR_INVALID_ARG, "bad scaling");
+    if (N > STATIC_MAX_BLOCKS)
+        return fail(c, DASH_ERR_INVALID_ARG, "dash_block_norms_static: %lld blocks exceed the static scratch of %lld blocks; "
+                                             "use dash_block_norms with a workspace", (long long)N, (long long)STATIC_MAX_BLOCKS);
+    if (N == 0) return DASH_OK;
+    if (!A || !s_out) return fail(c, DASH_ERR_INVALID_ARG, "null operand");
+    if (!c->static_scratch) return fail(c, DASH_ERR_HIP, "static scratch address was not resolved");
+    HIP_TRY(c, hipSetDevice(c->device));
+    static_assert(STATIC_SLABS >= 32, "norm_slabs(B) is at most 32");
+    float* partial = c->static_scratch;        // every partial a finalize reads is written by this call first
+    if (scaling != DASH_SCALE_NONE) HIP_TRY(c, launch_norm_partials(A, N, B, eps, (int)scaling, partial, c->stream));
+    HIP_TRY(c, launch_finalize_scale(partial, N, norm_slabs(B), (int)scaling, 2, s_out, nullptr, nullptr, c->stream));
     return DASH_OK;
 }
 
