@@ -8,6 +8,7 @@ import workloads
 from oracle import chebyshev as ocheb
 from oracle import newton_db as ondb
 from oracle.evd import inverse_root_evd, rel_frobenius_error
+from tolerances import fp32_floor, max_abs_bar, rel_max_abs_error
 
 pytestmark = pytest.mark.gpu
 
@@ -18,16 +19,6 @@ def dash():
     d = Dash(0)
     yield d
     d.close()
-
-
-def fp32_floor(kappa: float, p: int, B: int = 256) -> float:
-    """Rounding floor of the fp32 coupled iteration relative to the same iteration in
-    float64.  Newton-DB amplifies a relative perturbation of the iterates by about the
-    condition number of the scaled block, and each perturbation is the rounding error of fp32
-    dot products of length B (growing like sqrt(B)); measured floors are ~0.1*kappa*2^-24 at
-    B = 256 for p=4 and ~2.5x that for p=2.  A factor 4 of margin is applied on top."""
-    base = max(1e-6, 0.1 * kappa * 2.0 ** -24) * max(1.0, (B / 256.0) ** 0.5)
-    return 4.0 * base * (2.5 if p == 2 else 1.0)
 
 
 def _to_gpu(a):
@@ -69,8 +60,12 @@ def test_ndb_config1(dash, p, k):
     e_model = rel_frobenius_error(X_same, X_evd)
     print(f"cfg1 p={p} k={k}: vs f64 same-k max {e_same.max():.2e}; vs EVD max {e_evd.max():.2e} "
           f"(f64 model {e_model.max():.2e})", flush=True)
-    floor = fp32_floor(1e3, p, c["B"])
+    floor = fp32_floor(1e3, p, c["B"])          # derived on the CPU: tests/test_fp32_floor.py
     assert e_same.max() < floor
+    # element by element, scaled by the largest entry of the reference block: the same bar
+    m_same = rel_max_abs_error(X, X_same)
+    print(f"   largest element-wise deviation / max|X_ref|: {m_same.max():.2e} (bar {max_abs_bar(floor):.2e})", flush=True)
+    assert m_same.max() < max_abs_bar(floor)
     # distance to the true root = truncation error of the method, up to the fp32 floor
     assert np.all(np.abs(e_evd - e_model) <= 0.1 * e_model + floor)
     # the closed form known by construction (no eigensolver): same statement
@@ -88,8 +83,10 @@ def test_ndb_well_conditioned_meets_1e4(dash, N, B, p):
     X = dash.inverse_root(_to_gpu(A32), p=p, iters=10, eps=1e-6, nonfinite_out=nf).cpu().numpy()
     X_evd = inverse_root_evd(A32.astype(np.float64), p, eps=1e-6)
     e = rel_frobenius_error(X, X_evd)
-    print(f"   max rel err vs EVD {e.max():.2e}", flush=True)
+    m = rel_max_abs_error(X, X_evd)
+    print(f"   max rel err vs EVD {e.max():.2e}, largest element-wise deviation / max|X_ref| {m.max():.2e}", flush=True)
     assert e.max() < 1e-4
+    assert m.max() < max_abs_bar(1e-4)
     assert np.all(nf.cpu().numpy() == 0)
     # defining identity X^p (A + eps I) = I, computed in float64 from the GPU result
     Xd = X.astype(np.float64)
@@ -109,6 +106,7 @@ def test_ndb_few_iterations_match_float64_iteration(dash, p, k):
     X = dash.inverse_root(_to_gpu(A32), p=p, iters=k, eps=1e-4).cpu().numpy()
     X_same = ondb.inverse_root_ndb(A32.astype(np.float64), p, k, eps=1e-4)
     assert rel_frobenius_error(X, X_same).max() < 1e-5
+    assert rel_max_abs_error(X, X_same).max() < max_abs_bar(1e-5)
 
 
 @pytest.mark.parametrize("scaling", ["trace", "none"])
@@ -121,6 +119,7 @@ def test_ndb_other_scalings(dash, scaling):
     X = dash.inverse_root(_to_gpu(A32), p=p, iters=k, scaling=scaling, scale_out=s_out).cpu().numpy()
     X_same = ondb.inverse_root_ndb(A32.astype(np.float64), p, k, scaling=scaling)
     assert rel_frobenius_error(X, X_same).max() < 1e-5
+    assert rel_max_abs_error(X, X_same).max() < max_abs_bar(1e-5)
     s_ref = [ondb.block_scale(A32[i].astype(np.float64), scaling) for i in range(N)]
     assert np.allclose(s_out.cpu().numpy(), s_ref, rtol=2e-6)
 
@@ -218,6 +217,7 @@ def test_chebyshev_matches_float64_clenshaw(dash, p, d):
     print(f"cheb p={p} d={d}: vs f64 Clenshaw {e_same.max():.2e}; vs EVD {e_evd.max():.2e} (model {e_model.max():.2e})",
           flush=True)
     assert e_same.max() < 1e-5
+    assert rel_max_abs_error(X, X_same).max() < max_abs_bar(1e-5)
     assert np.all(np.abs(e_evd - e_model) <= 0.1 * e_model + 1e-5)
 
 
@@ -233,11 +233,13 @@ def test_chebyshev_config1_and_paper_interval(dash):
     X = dash.inverse_root(_to_gpu(A32), method="chebyshev", p=p, iters=d, cheb_coeffs=coef, cheb_a=0.0, cheb_b=1.0)
     X_same = ocheb.inverse_root_chebyshev(A, p, np.array(coef), 0.0, 1.0)
     assert rel_frobenius_error(X.cpu().numpy(), X_same).max() < 1e-5
+    assert rel_max_abs_error(X.cpu().numpy(), X_same).max() < max_abs_bar(1e-5)
     s = np.sqrt((A ** 2).sum(axis=(1, 2)))
     a = float((lam.min(axis=1) / s).min())
     coef2 = chebyshev_fit(p, d, a, 1.0)
     X2 = dash.inverse_root(_to_gpu(A32), method="chebyshev", p=p, iters=d, cheb_coeffs=coef2, cheb_a=a, cheb_b=1.0)
     X2_same = ocheb.inverse_root_chebyshev(A, p, np.array(coef2), a, 1.0)
     assert rel_frobenius_error(X2.cpu().numpy(), X2_same).max() < 1e-5
+    assert rel_max_abs_error(X2.cpu().numpy(), X2_same).max() < max_abs_bar(1e-5)
     e2 = rel_frobenius_error(X2.cpu().numpy(), inverse_root_evd(A, p)).max()
     print(f"cfg1 chebyshev d=16: err vs EVD with [lmin/s,1] = {e2:.2e}", flush=True)

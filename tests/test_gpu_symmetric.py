@@ -12,6 +12,8 @@ from oracle import chebyshev as ocheb
 from oracle import shampoo as oshampoo
 from oracle.evd import inverse_root_evd, rel_frobenius_error
 
+from tolerances import fp32_floor, max_abs_bar, rel_max_abs_error
+
 pytestmark = pytest.mark.gpu
 
 
@@ -95,10 +97,14 @@ def test_ndb_both_modes_meet_the_same_bar(dashes, N, B, lo, p):
     assert ss["matmul_flops"] == pytest.approx(expect, rel=1e-12)                                   # ... fewer tiles
     sample = [0, N - 1]
     X_same = ondb.inverse_root_ndb(A32[sample].astype(np.float64), p, k, eps=1e-6)
-    floor = 4.0 * max(1e-6, 0.1 * 10 ** (-lo) * 2.0 ** -24) * max(1.0, (B / 256.0) ** 0.5) * (2.5 if p == 2 else 1.0)
+    # each mode against its own bar (derived on the CPU: tests/test_fp32_floor.py)
+    floor_s, floor_f = fp32_floor(10 ** (-lo), p, B, symmetric=True), fp32_floor(10 ** (-lo), p, B, symmetric=False)
     es, ef = rel_frobenius_error(Xs[sample], X_same).max(), rel_frobenius_error(Xf[sample], X_same).max()
-    print(f"ndb sym/full N={N} B={B} p={p}: vs float64 same-k  sym {es:.2e}  full {ef:.2e}", flush=True)
-    assert es < floor and ef < floor
+    ms, mf = rel_max_abs_error(Xs[sample], X_same).max(), rel_max_abs_error(Xf[sample], X_same).max()
+    print(f"ndb sym/full N={N} B={B} p={p}: vs float64 same-k  sym {es:.2e} (element-wise {ms:.2e}, bar {floor_s:.2e})  "
+          f"full {ef:.2e} (element-wise {mf:.2e}, bar {floor_f:.2e})", flush=True)
+    assert es < floor_s and ef < floor_f
+    assert ms < max_abs_bar(floor_s) and mf < max_abs_bar(floor_f)
 
 
 @pytest.mark.parametrize("p", [2, 4])
@@ -108,12 +114,12 @@ def test_ndb_symmetric_mode_stays_stable_after_convergence(dashes, p):
     N, B = 4, 256
     A32, _, _ = workloads.spd_stack(N, B, -4.0, 0.0, seed=89, share_q=True)
     X_evd = inverse_root_evd(A32.astype(np.float64), p)
-    floor = 4.0 * 0.1 * 1e4 * 2.0 ** -24 * (2.5 if p == 2 else 1.0)
+    floor_s, floor_f = fp32_floor(1e4, p, B, symmetric=True), fp32_floor(1e4, p, B, symmetric=False)
     for k in (20, 40):
         es = rel_frobenius_error(sym.inverse_root(_to_gpu(A32), p=p, iters=k).cpu().numpy(), X_evd).max()
         ef = rel_frobenius_error(full.inverse_root(_to_gpu(A32), p=p, iters=k).cpu().numpy(), X_evd).max()
         print(f"ndb stability p={p} k={k}: sym {es:.2e} full {ef:.2e}", flush=True)
-        assert es < floor and ef < floor
+        assert es < floor_s and ef < floor_f
 
 
 def test_chebyshev_and_step_both_modes(dashes):
