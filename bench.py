@@ -9,9 +9,12 @@ Workload = one 4096 x 4096 linear layer with B = 1024: 16 gradient blocks, 32 st
 Newton-DB updates per call, factors warmed with 20 seeded gradients.
 
 Prints ONE JSON line.  `value` is factor blocks brought through the whole step per second
-(inputs resident in HBM).  `roofline` is for the batched matmul kernel, from HIP events
-recorded around each of its launches on the library's stream during the timed steps.
-`cpu_baseline` times the float64 oracle step on a bounded sample on the host cores.
+(inputs resident in HBM; nothing but the step's launches inside the timed region).  `roofline`
+is for the batched matmul kernel, from HIP events recorded around each of its launches on the
+library's stream in a separate instrumented pass after the timed steps.  `other_product_mode`
+is the same workload with symmetric mode switched the other way, `configs` carries the other
+four workload configurations (cfg1, cfg3, cfg4, cfg5), each with its own sampled float64-oracle
+baseline, and `cpu_baseline` times the oracle step of the headline workload on the host cores.
 """
 from __future__ import annotations
 
@@ -26,14 +29,54 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
-# HBM bytes the matmul kernel moves per block product on this workload, from two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size
-# (profiles/gemm_f32_cfg2_hbm_traffic.txt); the algorithmic figure is 12*B^2 = 12.58e6.
-MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT = 14.0e6
+PEAK_16BIT_MFMA_TFLOPS = 2500.0    # dense bf16 / fp16 matrix peak
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemm_f32_cfg2_hbm_traffic.txt")
+
+
+def measured_traffic_per_block_product():
+    """HBM bytes the fp32 matmul kernel moves per block product on the headline stack, as the committed rocprofv3
+    summary states it (two --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size; the
+    algorithmic figure is 12 B^2 = 12.58e6).  Read from the summary, not typed here; None when it is missing."""
+    import re
+    try:
+        m = re.search(r"=\s*([0-9.]+)e6 bytes per block product", open(TRAFFIC_PROFILE).read())
+        return float(m.group(1)) * 1e6 if m else None
+    except OSError:
+        return None
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def blas_threads() -> int:
+    import numpy  # noqa: F401  (loads the BLAS whose pool is counted)
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([i.get("num_threads", 1) for i in threadpool_info()] or [1]))
+    except Exception:
+        return os.cpu_count() or 1
+
+
+def cpu_root_baseline(N: int, B: int, p: int, seconds: float, what: str, of_total: int):
+    """The float64 oracle root (eigendecomposition, oracle/evd.py) on well-conditioned seeded SPD blocks of edge B,
+    repeated over `N` blocks until about `seconds` have passed (at least one pass).  Timing does not depend on the
+    spectrum.  Returns blocks/s on the host threads the BLAS uses."""
+    import numpy as np
+    from oracle.evd import inverse_root_evd
+    rng = np.random.default_rng(B + N)
+    G = rng.standard_normal((N, B, B))
+    A = np.matmul(G, np.swapaxes(G, 1, 2)) / B + 0.1 * np.eye(B)
+    done, t0 = 0, time.perf_counter()
+    while True:
+        inverse_root_evd(A, p, eps=1e-6)
+        done += N
+        if time.perf_counter() - t0 >= seconds:
+            break
+    dt = time.perf_counter() - t0
+    return dict(value=done / dt, unit="blocks/s", cores=blas_threads(), kind="oracle",
+                sample=f"float64 eigendecomposition roots (p={p}) of {N} of the {of_total} {B}x{B} blocks of {what}, "
+                       f"{done // N} pass(es), {dt:.1f} s")
 
 
 def cpu_baseline(sample_blocks: int, B: int, beta: float, eps: float, p: int, repeats: int = 3):
@@ -41,11 +84,7 @@ def cpu_baseline(sample_blocks: int, B: int, beta: float, eps: float, p: int, re
     import numpy as np
     import workloads
     from oracle import shampoo as oshampoo
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-    except Exception:
-        threads = os.cpu_count() or 1
+    threads = blas_threads()
     L = np.zeros((sample_blocks, B, B))
     R = np.zeros((sample_blocks, B, B))
     for t in range(2):
@@ -177,6 +216,194 @@ def hbm_kernels(dash):
     return rows
 
 
+
+def _timed(fn, reps):
+    """Mean wall time of fn() in ms over `reps` back-to-back calls, device idle before and after."""
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / reps
+
+
+def _root_record(dash, A, X, reps, peak, **kw):
+    """One inverse-root configuration on the resident stack A: ms per call, blocks/s, and the flops of the tiles the
+    launches computed (library statistics) against `peak`."""
+    dash.inverse_root(A, X, **kw)                      # warm-up, sizes the workspace
+    dash.reset_stats()
+    ms = _timed(lambda: dash.inverse_root(A, X, **kw), reps)
+    fl = dash.get_stats()["matmul_flops"] / reps
+    tf = fl / (ms * 1e-3) / 1e12
+    return dict(ms=ms, blocks_per_s=A.shape[0] / (ms * 1e-3), executed_tflops=tf, mfma_frac=tf / peak)
+
+
+def _spd_stack_on_device(N, B, seed):
+    """Well-conditioned random SPD blocks built on the device (timing does not depend on the values; accuracy on the
+    configurations' own spectra is what tests/test_gpu_configs.py checks)."""
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    A = torch.empty(N, B, B, device="cuda")
+    chunk = max(1, min(N, (1 << 28) // (B * B)))
+    for i in range(0, N, chunk):
+        Gm = torch.randn(min(chunk, N - i), B, B, device="cuda", generator=gen)
+        A[i:i + chunk] = Gm @ Gm.transpose(1, 2) / B
+    A += 0.1 * torch.eye(B, device="cuda")
+    return A
+
+
+def other_configs(dash, cpu: bool):
+    """Driver-visible numbers of the workload configurations other than the headline one.  Inputs are resident in HBM
+    before any timed call; each record carries its own sampled float64-oracle baseline (host threads stated)."""
+    import torch
+    import workloads
+    from paper_2602_02016_amd import chebyshev_fit
+    out = {}
+    coef16 = chebyshev_fit(4, 16, 0.05, 1.0)
+    cheb = dict(method="chebyshev", p=4, iters=16, eps=1e-6, cheb_coeffs=coef16, cheb_a=0.05, cheb_b=1.0)
+    ndb = dict(method="newton_db", p=4, iters=10, eps=1e-6)
+
+    # cfg1: 16 blocks of 128 -- bound by launch latency, reported as time per stack
+    c1 = workloads.CFG1
+    A = _spd_stack_on_device(c1["N"], c1["B"], 11)
+    X = torch.empty_like(A)
+    r_ndb = _root_record(dash, A, X, 50, PEAK_FP32_MFMA_TFLOPS, **ndb)
+    r_ch = _root_record(dash, A, X, 50, PEAK_FP32_MFMA_TFLOPS, **cheb)
+    out["cfg1"] = {"workload": "cfg1: inverse 4th root of 16 fp32 SPD blocks, B=128",
+                   "newton_db_k10": dict(us_per_stack=r_ndb["ms"] * 1e3, **r_ndb),
+                   "chebyshev_d16": dict(us_per_stack=r_ch["ms"] * 1e3, **r_ch),
+                   "note": "latency-bound: dependent launches of a few microseconds each; not a roofline point"}
+    if cpu:
+        out["cfg1"]["cpu_baseline"] = cpu_root_baseline(c1["N"], c1["B"], 4, 1.0, "cfg1", c1["N"])
+    del A, X
+
+    # cfg4: 64 MiB stacks of three block sizes
+    out["cfg4"] = {"workload": "cfg4: N*B^2 = 2^24 stacks, Newton-DB k=10 and Chebyshev d=16, p=4", "shapes": []}
+    for B, N in workloads.CFG4["shapes"]:
+        A = _spd_stack_on_device(N, B, 40 + B)
+        X = torch.empty_like(A)
+        rec = {"B": B, "N": N, "newton_db_k10": _root_record(dash, A, X, 10, PEAK_FP32_MFMA_TFLOPS, **ndb),
+               "chebyshev_d16": _root_record(dash, A, X, 10, PEAK_FP32_MFMA_TFLOPS, **cheb)}
+        if cpu:
+            n_cpu = max(1, min(N, (1 << 22) // (B * B) * 4))          # 64 / 16 / 4 blocks
+            rec["cpu_baseline"] = cpu_root_baseline(n_cpu, B, 4, 2.0, "cfg4", N)
+        out["cfg4"]["shapes"].append(rec)
+        del A, X
+
+    # cfg5: 1024 blocks of 1024, fp32 and bf16 operands (the latter priced against the 16-bit peak)
+    c5 = workloads.CFG5
+    A = _spd_stack_on_device(c5["N"], c5["B"], 55)
+    X = torch.empty_like(A)
+    out["cfg5"] = {"workload": "cfg5 shape: 1024 blocks of 1024x1024, Newton-DB p=4 k=10 (timing; the ill-conditioned "
+                               "spectra and the error-vs-k table are in tests/test_gpu_configs.py)",
+                   "fp32": _root_record(dash, A, X, 3, PEAK_FP32_MFMA_TFLOPS, **ndb),
+                   "bf16_operands": _root_record(dash, A, X, 5, PEAK_16BIT_MFMA_TFLOPS, precision="bf16", **ndb),
+                   "fp16x3_operands": _root_record(dash, A, X, 3, PEAK_16BIT_MFMA_TFLOPS, precision="fp16x3", **ndb)}
+    out["cfg5"]["fp16x3_operands"]["note"] = ("two fp16 planes, three plane products per product: executed_tflops counts "
+                                              "one product per multi-segment product; MFMA work is three times that")
+    if cpu:
+        out["cfg5"]["cpu_baseline"] = cpu_root_baseline(8, c5["B"], 4, 3.0, "cfg5", c5["N"])
+    del A, X
+
+    # cfg3: the whole 24-layer stack, one step (accumulate, 3072 roots in chunks of 512, 1536 updates)
+    c3 = workloads.CFG3
+    N, B = workloads.cfg3_num_gradient_blocks(), c3["B"]
+    S = torch.zeros(2 * N, B, B, device="cuda")
+    X = torch.empty_like(S)
+    G = torch.empty(N, B, B, device="cuda")
+    U = torch.empty_like(G)
+    nf = torch.zeros(2 * N, dtype=torch.int32, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(c3["seed_base"])
+    ws = dash.workspace_bytes(512, B)
+    for t in range(3):                                   # two warm-up gradients, then the gradient of the timed step
+        torch.randn(G.shape, device="cuda", generator=gen, out=G)
+        G.mul_(c3["grad_std"])
+        if t < 2:
+            dash.accumulate_factors(G, S[:N], S[N:], c3["beta"])
+    step = lambda: dash.step(G, S, X, U, beta=c3["beta"], eps=c3["eps"], p=c3["p"], iters=c3["ndb_iters"],
+                             nonfinite_out=nf, workspace_max_bytes=ws)
+    step()                                               # warm-up step
+    dash.reset_stats()
+    ms = _timed(step, 2)
+    fl = dash.get_stats()["matmul_flops"] / 2
+    assert int(nf.sum().item()) == 0, "non-finite root in cfg3"
+    out["cfg3"] = {"workload": "cfg3: 24-layer decoder (d=2048, FFN 8192), B=1024: 1536 gradient blocks, 3072 factor blocks "
+                               "(12 GiB), one step = accumulate + 3072 inverse 4th roots (chunks of 512) + 1536 updates",
+                   "step_s": ms * 1e-3, "blocks_per_s": 2 * N / (ms * 1e-3),
+                   "executed_tflops": fl / (ms * 1e-3) / 1e12,
+                   "mfma_frac_executed": fl / (ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
+    del S, X, G, U
+    if cpu:
+        b = cpu_baseline(8, B, c3["beta"], c3["eps"], c3["p"], repeats=1)
+        b["sample"] = b["sample"].replace("of the 16 gradient blocks", f"of the {N} gradient blocks")
+        out["cfg3"]["cpu_baseline"] = b
+    torch.cuda.empty_cache()
+    return out
+
+
+def headline(dash, args, symmetric: bool, grads, S, X, U, nf, c):
+    """W untimed warm-up steps, then exactly K timed steps of the cfg2 workload with the library's event timing OFF
+    (nothing but the step's own launches inside the timed region); after that a second, instrumented pass of a few
+    steps with HIP events around every matmul launch for the roofline figure.  Returns (ms_per_step, stats of the
+    instrumented pass, its number of steps)."""
+    import torch
+    B, beta, eps, p, k = c["B"], c["beta"], c["eps"], c["p"], c["ndb_iters"]
+    dash.set_symmetric(symmetric)
+
+    def one_step(i):
+        dash.step(grads[i % len(grads)], S, X, U, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf)
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert int(nf.sum().item()) == 0, "non-finite root in the benchmark workload"
+    # instrumented pass: per-launch HIP events on the library's stream (not part of ms_per_step)
+    n_inst = max(2, min(args.steps, 5))
+    dash.reset_stats()
+    dash.set_timing(True)
+    for i in range(n_inst):
+        one_step(i)
+    st = dash.get_stats()
+    dash.set_timing(False)
+    return dt * 1e3 / args.steps, st, n_inst
+
+
+def roofline_of(st, n_inst, B, ms_per_step):
+    """Roofline object of the dominant kernel (the non-transposed fp32 matmul instance: every Newton-DB and
+    precondition product) from the instrumented pass."""
+    flop_per_product = 2.0 * B ** 3
+    mm_ms = st["variant_ms"][0]
+    launches = st["variant_launches"][0]
+    # flops of the output tiles the launches really computed (symmetric products compute the tiles on and above the
+    # diagonal only), never the full-product count
+    achieved = st["variant_flops"][0] / (mm_ms * 1e-3) / 1e12 if mm_ms > 0 else 0.0
+    tile_fraction = st["variant_flops"][0] / (flop_per_product * st["variant_block_products"][0])
+    per_product = measured_traffic_per_block_product()
+    return dict(bound="mfma", kernel="dash::gemm_f32_kernel<128, false, false, false>",
+                achieved=achieved, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s", frac=achieved / PEAK_FP32_MFMA_TFLOPS,
+                computed_tile_fraction=tile_fraction,
+                full_product_equivalent_tflops=achieved / tile_fraction,
+                traffic=None if per_product is None else per_product * st["variant_block_products"][0] / max(launches, 1),
+                traffic_note="HBM bytes per mean launch = bytes per block product stated in "
+                             "profiles/gemm_f32_cfg2_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs, "
+                             "scaled by a copy kernel of known size; collected offline on full-product launches) x "
+                             "block products per launch of this run",
+                algorithmic_bytes=12.0 * B * B * st["variant_block_products"][0] / max(launches, 1),
+                launches_per_step=launches / n_inst,
+                mean_launch_ms=mm_ms / max(launches, 1),
+                timing_note="HIP events around each launch on the library's stream, in a separate instrumented pass of "
+                            f"{n_inst} steps after the timed steps (the timed steps run with event timing off)",
+                instrumented_matmul_ms_per_step=mm_ms / n_inst)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -188,13 +415,22 @@ def main():
     ap.add_argument("--root-only-reps", type=int, default=-1,
                     help="extra timed calls of the inverse root alone (default steps/2; 0 = none)")
     ap.add_argument("--full-products", action="store_true",
-                    help="switch the library's symmetric mode off (every product computed in full)")
+                    help="headline with the library's symmetric mode off (every product computed in full); the default "
+                         "run reports that variant beside the headline anyway")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the records of the other configurations and of the variants (short run, e.g. under a profiler)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc: one device copy of known size, then three launches of the "
                          "matmul kernel on the workload's 32-block stack; prints nothing else")
     ap.add_argument("--pmc-probe-16bit", action="store_true",
                     help="as --pmc-probe with the 16-bit kernel: a device copy of known size, then three launches "
                          "of the bf16-operand matmul on 256 blocks (fp32 result)")
+    ap.add_argument("--pmc-probe-step", action="store_true",
+                    help="for rocprofv3 --pmc: the headline workload's factors, then two whole steps (every launch of "
+                         "the step under the counters); prints the host-side flop count of those two steps")
+    ap.add_argument("--pmc-probe-ndb16", action="store_true",
+                    help="for rocprofv3 --pmc: one bf16-operand Newton-DB call (p=4, k=10) on 256 blocks of 1024; "
+                         "prints the host-side flop count")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline step: inverse-root throughput on the shapes of the other "
                          "configurations, all methods and precisions (table on stderr, one JSON line)")
@@ -248,6 +484,21 @@ def main():
         print(json.dumps({"pmc_probe_16bit": "copy of %d bytes then 3 bf16 matmul launches on %d blocks" % (32 * B * B * 4, nb)}))
         return
 
+    if args.pmc_probe_ndb16:
+        A = _spd_stack_on_device(256, B, 55)
+        Xo = torch.empty_like(A)
+        kw = dict(p=4, iters=10, eps=1e-6, precision="bf16")
+        dash.inverse_root(A[:8], Xo[:8], **kw)
+        dash.ensure_workspace(256, B, "newton_db", 4, "bf16")
+        torch.cuda.synchronize()
+        dash.reset_stats()
+        dash.inverse_root(A, Xo, **kw)
+        torch.cuda.synchronize()
+        st = dash.get_stats()
+        print(json.dumps({"pmc_probe_ndb16": "one bf16-operand Newton-DB call, p=4 k=10, 256 blocks of 1024",
+                          "host_side_matmul_flops": st["matmul_flops"], "matmul_launches": st["matmul_launches"]}))
+        return
+
     if args.pmc_probe:
         gen = torch.Generator(device=dev)
         gen.manual_seed(1)
@@ -280,33 +531,52 @@ def main():
     total = args.warmup + args.steps
     grads = [torch.randn(N, B, B, device=dev, generator=gen) * c["grad_std"] for _ in range(min(total, 8))]
 
-    def one_step(i):
-        dash.step(grads[i % len(grads)], S, X, U, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf)
+    if args.pmc_probe_step:
+        dash.step(grads[0], S, X, U, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf)     # sizes the workspace
+        torch.cuda.synchronize()
+        dash.reset_stats()
+        for i in range(2):
+            dash.step(grads[i + 1], S, X, U, beta=beta, eps=eps, p=p, iters=k, nonfinite_out=nf)
+        torch.cuda.synchronize()
+        st = dash.get_stats()
+        print(json.dumps({"pmc_probe_step": "20 accumulations, one untimed step, then two whole cfg2 steps",
+                          "host_side_matmul_flops_of_the_two_steps": st["matmul_flops"],
+                          "matmul_launches_of_the_two_steps": st["matmul_launches"],
+                          "symmetric_products": not args.full_products}))
+        return
 
-    for i in range(args.warmup):
-        one_step(i)
-    torch.cuda.synchronize()
-
-    dash.reset_stats()
-    dash.set_timing(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_step(args.warmup + i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    st = dash.get_stats()
-    dash.set_timing(False)
-    assert int(nf.sum().item()) == 0, "non-finite root in the benchmark workload"
+    S_warm = S.clone()
+    symmetric = not args.full_products
+    ms_per_step, st, n_inst = headline(dash, args, symmetric, grads, S, X, U, nf, c)
+    blocks_per_s = 2 * N / (ms_per_step * 1e-3)
+    roofline = roofline_of(st, n_inst, B, ms_per_step)
+    flop_per_product = 2.0 * B ** 3
+    achieved_tflops = roofline["achieved"]
 
     # the inverse roots alone (same stack, same call the step makes), timed the same way
     reps = args.root_only_reps if args.root_only_reps >= 0 else max(1, args.steps // 2)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(reps):
-        dash.inverse_root(S, X, p=p, iters=k, eps=eps, nonfinite_out=nf)
-    torch.cuda.synchronize()
-    root_ms = (time.perf_counter() - t1) * 1e3 / max(reps, 1)
+    if args.headline_only:
+        reps = 0
+    root_ms = _timed(lambda: dash.inverse_root(S, X, p=p, iters=k, eps=eps, nonfinite_out=nf), reps) if reps > 0 else 0.0
+
+    # the same workload with the other setting of symmetric mode (a reading of the paper, not its product set: with it
+    # on, the residual Z Y of Section 3.3 is computed on its upper triangle of tiles and mirrored)
+    other_mode = None
+    if not args.headline_only:
+        S_now = S.clone()
+        S.copy_(S_warm)
+        ms2, st2, n2 = headline(dash, args, not symmetric, grads, S, X, U, nf, c)
+        r2 = roofline_of(st2, n2, B, ms2)
+        other_mode = {"symmetric_products": not symmetric, "ms_per_step": ms2, "value": 2 * N / (ms2 * 1e-3),
+                      "unit": "blocks/s", "steps": args.steps, "warmup": args.warmup,
+                      "roofline": {kk: r2[kk] for kk in ("achieved", "peak", "unit", "frac", "computed_tile_fraction",
+                                                         "launches_per_step", "mean_launch_ms")},
+                      "step_mfma_frac_executed": st2["matmul_flops"] / n2 / (ms2 * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
+        dash.set_symmetric(symmetric)
+        S.copy_(S_now)
+        dash.inverse_root(S, X, p=p, iters=k, eps=eps, nonfinite_out=nf)      # X of the headline mode again
+        del S_now
+    del S_warm
 
     # the same stack with the paper's multi-Power-Iteration scaling (Sections 3.4, 3.5), which converges in
     # half the updates on these factors: 5 per call against the headline's 10 (context, not the headline)
@@ -404,34 +674,6 @@ def main():
         S.copy_(S_keep)
         del S_keep
 
-    ms_per_step = dt * 1e3 / args.steps
-    blocks_per_s = 2 * N * args.steps / dt
-
-    # matmul kernel: algorithmic flops per launch / mean launch duration
-    flop_per_product = 2.0 * B ** 3
-    # dominant kernel = the non-transposed instance (all Newton-DB and precondition products)
-    mm_ms = st["variant_ms"][0]
-    launches = st["variant_launches"][0]
-    # flops of the output tiles the launches really computed (symmetric products compute the tiles on and
-    # above the diagonal only), never the full-product count
-    achieved_tflops = st["variant_flops"][0] / (mm_ms * 1e-3) / 1e12 if mm_ms > 0 else 0.0
-    tile_fraction = st["variant_flops"][0] / (flop_per_product * st["variant_block_products"][0])
-    roofline = dict(bound="mfma", kernel="dash::gemm_f32_kernel<128, false, false, false>",
-                    achieved=achieved_tflops, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
-                    frac=achieved_tflops / PEAK_FP32_MFMA_TFLOPS,
-                    computed_tile_fraction=tile_fraction,
-                    full_product_equivalent_tflops=achieved_tflops / tile_fraction,
-                    traffic=MEASURED_TRAFFIC_BYTES_PER_BLOCK_PRODUCT * st["variant_block_products"][0] / max(launches, 1),
-                    traffic_note="HBM bytes per mean launch = rocprofv3 FETCH_SIZE+WRITE_SIZE per block product "
-                                 "(measured offline, scaled by a copy kernel) x block products per launch of this run",
-                    algorithmic_bytes=12.0 * B * B * st["variant_block_products"][0] / max(launches, 1),
-                    launches_per_step=launches / args.steps,
-                    mean_launch_ms=mm_ms / max(launches, 1),
-                    launch_note="a launch whose last round of 128-tile workgroups would be under half full (the "
-                                "36-tile symmetric residual on 32 blocks) computes the blocks that fill whole rounds "
-                                "with 128 tiles and the remaining blocks with 64 tiles, in the same kernel launch",
-                    matmul_share_of_step=mm_ms / (dt * 1e3))
-
     # the paper's own matmul count for the root (3k-2 per call, two calls) prices the
     # inverse root alone: what the headline "blocks/s at B=1024" would be without the
     # accumulate and precondition products of the step
@@ -452,22 +694,31 @@ def main():
         "data": "synthetic",
         "config": {"workload": "cfg2: one Shampoo step of a 4096x4096 layer, B=1024, 16 gradient blocks / 32 factor "
                                "blocks, Newton-DB p=4 with 10 updates per call, Frobenius scaling, beta=0.95, "
-                               "eps=1e-6, factors warmed with 20 seeded gradients",
+                               "eps=1e-6, factors warmed with 20 seeded gradients; symmetric mode "
+                               + ("on: the residual product Z Y of Newton-DB and G G^T, G^T G compute their upper "
+                                  "triangle of tiles and mirror it -- a reading of the paper, whose Section 3.3 computes "
+                                  "Z Y in full (the full-products twin of this number is in other_product_mode)"
+                                  if symmetric else "off: every product computed in full, the paper's product set"),
                    "N_gradient_blocks": N, "N_factor_blocks": 2 * N, "B": B, "p": p, "ndb_iters": k,
-                   "symmetric_products": not args.full_products},
+                   "symmetric_products": symmetric},
         "roofline": roofline,
         "step_mfma_frac_paper_count": (2 * N * paper_products_root + 4 * N) * flop_per_product
                                       / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
-        "step_mfma_frac_executed": st["matmul_flops"] / args.steps / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+        "step_mfma_frac_executed": st["matmul_flops"] / n_inst / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
         "inverse_root_only": None if reps == 0 else {"blocks_per_s": 2 * N / (root_ms * 1e-3), "ms": root_ms,
                               "mfma_frac_paper_count": 2 * N * paper_products_root * flop_per_product
                               / (root_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
                               "note": "mfma_frac_paper_count prices every product of the paper's count in full; "
                                       "it is a throughput figure, not a utilisation"},
     }
+    out["other_product_mode"] = other_mode
     out["inverse_root_power_iteration_scaling"] = pi_variant
     out["inverse_root_bf16x6"] = split_variants.get("bf16x6")
     out["inverse_root_fp16x3"] = split_variants.get("fp16x3")
+    if not args.headline_only:
+        del X, U
+        torch.cuda.empty_cache()
+        out["configs"] = other_configs(dash, cpu=not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(min(args.cpu_sample_blocks, N), B, beta, eps, p, args.cpu_repeats)
     log(f"step {ms_per_step:.2f} ms, {blocks_per_s:.0f} factor blocks/s, matmul kernel {achieved_tflops:.1f} TFLOP/s "

@@ -25,23 +25,20 @@ from .newton_db import MatmulCounter, block_scale
 
 def chebyshev_fit(p: int, degree: int, a: float, b: float, n_points: int = 10000,
                   f=None) -> np.ndarray:
-    """Coefficients c_0..c_d of sum_k c_k T_k(t) ~ f(x(t)) on [a, b], f(x) = x^(-1/p).
+    """Coefficients c_0..c_d of sum_k c_k T_k(t) ~ f(x(t)) on [a, b], f(x) = x^(-1/p) (Appendix A.1).
 
-    Cosine-series fit at the n_points Chebyshev nodes theta_v = (2v+1) pi / (2N):
-    c_k = (2/N) sum_v f(x_v) cos(k theta_v), and c_0 is halved."""
+    Discrete orthogonality of the Chebyshev polynomials at the N roots t_v = cos(theta_v) of T_N,
+    theta_v = (v + 1/2) pi / N:  c = w * (T f) with the (d+1) x N matrix T[k, v] = T_k(t_v) = cos(k theta_v),
+    f[v] = f(x(t_v)) and weights w_0 = 1/N, w_k = 2/N."""
     if f is None:
         def f(x):
             return np.power(x, -1.0 / p)
-    v = np.arange(n_points, dtype=np.float64)
-    theta = (2.0 * v + 1.0) * np.pi / (2.0 * n_points)
-    t = np.cos(theta)
-    x = 0.5 * (b - a) * t + 0.5 * (b + a)
-    fx = f(x)
-    c = np.zeros(degree + 1)
-    for k in range(degree + 1):
-        c[k] = (2.0 / n_points) * np.dot(fx, np.cos(k * theta))
-    c[0] *= 0.5
-    return c
+    theta = (np.arange(n_points, dtype=np.float64) + 0.5) * (np.pi / n_points)
+    x = a + 0.5 * (b - a) * (1.0 + np.cos(theta))          # [-1, 1] -> [a, b]
+    T = np.cos(np.outer(np.arange(degree + 1, dtype=np.float64), theta))
+    w = np.full(degree + 1, 2.0 / n_points)
+    w[0] = 1.0 / n_points
+    return w * (T @ f(x))
 
 
 def to_unit_interval(x, a: float, b: float):

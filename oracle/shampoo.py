@@ -41,6 +41,8 @@ def adam_graft(G, U, Acc, beta_g: float, eps_g: float):
     Acc <- beta_g Acc + (1-beta_g) G*G (elementwise); P = G / (eps_g + sqrt(Acc));
     s_i = ||P_i||_F / ||U_i||_F per block.  Returns (Acc_new, s) with s of shape (N,).
     The parameter update is then theta <- theta - eta * s_i * U_i.
+    Section 2.3 is silent on a block whose update U_i is all zero (a block that saw no gradient):
+    reading s_i = 0 there -- the update is zero whatever s_i is, and 0/0 would poison theta.
     """
     G = np.asarray(G, dtype=np.float64)
     U = np.asarray(U, dtype=np.float64)
@@ -49,7 +51,8 @@ def adam_graft(G, U, Acc, beta_g: float, eps_g: float):
     P = G / (eps_g + np.sqrt(Acc_new))
     nP = np.sqrt((P * P).sum(axis=(-1, -2)))
     nU = np.sqrt((U * U).sum(axis=(-1, -2)))
-    return Acc_new, nP / nU
+    s = np.divide(nP, nU, out=np.zeros_like(nP), where=nU > 0.0)
+    return Acc_new, s
 
 
 def step(G, L, R, beta: float, eps: float, p: int = 4, alpha: float | None = None,

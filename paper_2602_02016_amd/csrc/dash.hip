@@ -949,20 +949,25 @@ dash_status dash_block_norms_static(dash_ctx* c, const float* A, int64_t N, int 
 dash_status dash_chebyshev_fit(int p, int degree, double a, double b, int n_points, double* coeffs_out) {
     if ((p != 2 && p != 4) || degree < 0 || n_points < degree + 1 || !(b > a) || !(a > 0.0) || !coeffs_out)
         return DASH_ERR_INVALID_ARG;
-    // cosine-series fit at the Chebyshev nodes theta_v = (2v+1) pi / (2N)  (Appendix A.1)
+    // Appendix A.1: c_k = (w_k / N) sum_v f(x_v) T_k(t_v) over the N roots t_v of T_N, w_0 = 1, w_k = 2.
+    // One pass over the nodes; at each node all T_k(t_v) come from the three-term recurrence
+    // T_{k+1} = 2 t T_k - T_{k-1} (no cosine per coefficient), and node v adds f(x_v) T_k(t_v) to every sum.
     const double pi = 3.14159265358979323846;
-    std::vector<double> fx(n_points), th(n_points);
+    std::vector<double> sum((size_t)degree + 1, 0.0);
     for (int v = 0; v < n_points; ++v) {
-        th[v] = (2.0 * v + 1.0) * pi / (2.0 * n_points);
-        const double x = 0.5 * (b - a) * std::cos(th[v]) + 0.5 * (b + a);
-        fx[v] = std::pow(x, -1.0 / p);
+        const double t = std::cos((v + 0.5) * pi / n_points);
+        const double fx = std::pow(a + 0.5 * (b - a) * (1.0 + t), -1.0 / p);
+        double t_prev = 1.0, t_cur = t;                      // T_0, T_1
+        sum[0] += fx;
+        if (degree >= 1) sum[1] += fx * t;
+        for (int k = 2; k <= degree; ++k) {
+            const double t_next = 2.0 * t * t_cur - t_prev;
+            sum[(size_t)k] += fx * t_next;
+            t_prev = t_cur;
+            t_cur = t_next;
+        }
     }
-    for (int k = 0; k <= degree; ++k) {
-        double acc = 0.0;
-        for (int v = 0; v < n_points; ++v) acc += fx[v] * std::cos(k * th[v]);
-        coeffs_out[k] = 2.0 / n_points * acc;
-    }
-    coeffs_out[0] *= 0.5;
+    for (int k = 0; k <= degree; ++k) coeffs_out[k] = sum[(size_t)k] * (k == 0 ? 1.0 : 2.0) / n_points;
     return DASH_OK;
 }
 

@@ -253,7 +253,8 @@ __global__ __launch_bounds__(NT) void graft_apply_kernel(const float* U, float* 
         tp += partial[(b * P + i) * 2 + 0];
         tu += partial[(b * P + i) * 2 + 1];
     }
-    const float s = sqrtf(tp) / sqrtf(tu);
+    // a block whose update is all zero (a gradient block that saw no data) has nothing to scale: s = 0, not 0/0
+    const float s = tu > 0.f ? sqrtf(tp) / sqrtf(tu) : 0.f;
     if (s_out && q == 0 && threadIdx.x == 0) s_out[b] = s;
     if (!theta && !scaled) return;
     const float k = lr * s;

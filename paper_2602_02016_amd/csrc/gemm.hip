@@ -53,10 +53,8 @@ __device__ __forceinline__ void fstatic_for(F&& f) {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-#ifndef DASH_BK
-#define DASH_BK 16
-#endif
-constexpr int BK = DASH_BK;        // K slab (16 or 32)
+constexpr int BK = 16;             // K slab (32 measured slower: 125 against 128 TFLOP/s on a 128-block launch)
+constexpr int MIN_WG = 2;          // workgroups per CU the compiler must leave room for (3 and 4 measured no better)
 // workgroup shape per tile edge: WC x WC wavefronts, each computing a WT x WT part of the tile
 //   TILE  64: 2 x 2 wavefronts of 32 x 32;  TILE 128: 2 x 2 wavefronts of 64 x 64 (256 threads);
 //   (TILE 256 = 4 x 4 wavefronts of 64 x 64, 1024 threads, one workgroup per CU, also builds from this template: half the bytes
@@ -346,10 +344,7 @@ __device__ __forceinline__ int64_t xcd_remap(int64_t bid, int64_t W) {
 // (TILE 128, square products), workgroups from g.w_main on compute 64 tiles of the remaining blocks.  They have
 // the same 256 threads and fit the same LDS, so they fill the CUs as the big tiles drain.
 template <int TILE, bool TA, bool TB, bool RECT = false>
-#ifndef DASH_MIN_WG
-#define DASH_MIN_WG 2
-#endif
-__global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : DASH_MIN_WG) void gemm_f32_kernel(GemmLaunch g) {
+__global__ __launch_bounds__(Cfg<TILE>::NT, TILE == 256 ? 1 : MIN_WG) void gemm_f32_kernel(GemmLaunch g) {
     __shared__ __attribute__((aligned(1024))) float lds[LdsNeed<TILE>::FLOATS];
     const int64_t bid = blockIdx.x;
     if (TILE == 128 && !RECT) {
@@ -378,7 +373,7 @@ __device__ __forceinline__ void gemm_f32_pair_tile(const GemmLaunch& g, int64_t 
 }
 
 template <int TILE>
-__global__ __launch_bounds__(Cfg<TILE>::NT, DASH_MIN_WG) void gemm_f32_pair_kernel(GemmLaunch g) {
+__global__ __launch_bounds__(Cfg<TILE>::NT, MIN_WG) void gemm_f32_pair_kernel(GemmLaunch g) {
     __shared__ __attribute__((aligned(1024))) float lds[LdsNeed<TILE>::FLOATS];
     const int64_t bid = blockIdx.x;
     if (TILE == 128) {
@@ -492,8 +487,14 @@ double gemm_tile_fraction(const GemmLaunch& g) {
     if (!g.sym) return 1.0;
     const int Md = g.M ? g.M : g.B;
     if (g.half != HALF_NONE) {
-        const int t = Md / gemm_half_tile_edge(g);
-        return (double)(t + 1) / (2.0 * t);
+        const int edge = gemm_half_tile_edge(g);
+        const int t = Md / edge;
+        const double f = (double)(t + 1) / (2.0 * t);
+        const int64_t na = gemm_half_split_blocks(g);      // blocks computed with the launch's own tile; the rest with 128
+        if (na == g.nblocks) return f;
+        const int t128 = Md / 128;
+        const double f128 = (double)(t128 + 1) / (2.0 * t128);
+        return (f * (double)na + f128 * (double)(g.nblocks - na)) / (double)g.nblocks;
     }
     const int t = Md / gemm_tile_edge(g);
     const double f = (double)(t + 1) / (2.0 * t);

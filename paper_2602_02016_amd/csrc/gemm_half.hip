@@ -29,13 +29,9 @@
 #include <type_traits>
 #include <utility>
 
-#ifndef DASH_H256_MIN
-#define DASH_H256_MIN 128      // workgroups a launch must have for the 256 tile (measured: 96 and 64 lose, 160 and 256 lose)
-#endif
-#ifndef DASH_HALF_SPLIT_COND
-#define DASH_HALF_SPLIT_COND
-#endif
 namespace dash {
+
+constexpr int64_t H256_MIN_WORKGROUPS = 128;   // workgroups a launch must have for the 256 tile (measured: 64, 96, 160 and 256 all lose)
 
 // compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  The accumulator
 // array must only ever be indexed by constants, or the compiler moves it to scratch memory; a pragma
@@ -102,12 +98,8 @@ struct HCfg {
     static constexpr int WC = TILE / WT;
     static constexpr int NT = 64 * WC * WC;
     static constexpr int OCC = TILE == 256 ? 1 : 2;        // workgroups per CU the kernel is built for
-#ifndef DASH_H256_BK
-#define DASH_H256_BK 64
-#define DASH_H256_NS 2
-#endif
-    static constexpr int HBK = TILE == 256 ? DASH_H256_BK : 64;
-    static constexpr int NS = TILE == 256 ? DASH_H256_NS : 2;
+    static constexpr int HBK = 64;                          // K slab (slabs of 32 in rings of 3 to 5 stages measured slower)
+    static constexpr int NS = 2;                            // stages of the ring
 };
 constexpr int HNUM_XCD = 8;
 
@@ -547,37 +539,39 @@ hipError_t hlaunch_tile(const GemmLaunch& g, hipStream_t stream) {
 // Newton-DB on 16 to 24 blocks of 1024 4 % faster), else as the fp32 kernel.  (A 256 tile of four wavefronts with 128 x 128 each, accumulators in
 // AGPRs, was also built: one wavefront per SIMD cannot hide its own latencies, 500-560 TFLOP/s.)
 int gemm_half_tile_edge(const GemmLaunch& g) {
-#ifndef DASH_NO_TILE256
     const int64_t t = g.B / 256;
-    if (g.B % 256 == 0 && g.nblocks * g.nprob * (g.sym ? t * (t + 1) / 2 : t * t) >= DASH_H256_MIN) return 256;
-#endif
+    if (g.B % 256 == 0 && g.nblocks * g.nprob * (g.sym ? t * (t + 1) / 2 : t * t) >= H256_MIN_WORKGROUPS) return 256;
     return gemm_tile_edge(g);
 }
 
 static hipError_t launch_half_edge(const GemmLaunch& g, int edge, hipStream_t stream);
 
+// A 256 tile fills a CU, so a launch runs in rounds of 256 workgroups.  A launch of a split mode (several K
+// segments per product: long enough to pay for a second launch) whose last round would be at most half full
+// (the symmetric residual on 32 blocks: 320 workgroups) computes the blocks of the whole rounds with 256 tiles
+// and the remaining blocks with 128 tiles in a second launch.  Returns the number of blocks of the first part
+// (nblocks: no split).
+int64_t gemm_half_split_blocks(const GemmLaunch& g) {
+    if (g.half == HALF_NONE || gemm_half_tile_edge(g) != 256 || !g.prob[0].A2) return g.nblocks;
+    const int64_t t = g.B / 256, per_block = g.nprob * (g.sym ? t * (t + 1) / 2 : t * t), W = g.nblocks * per_block;
+    const int64_t rem = W % 256;
+    const int64_t n_main = (W - rem) / per_block;
+    if (W > 256 && rem > 0 && rem <= 128 && n_main >= 1 && n_main < g.nblocks) return n_main;
+    return g.nblocks;
+}
+
 hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream) {
     const int edge = gemm_half_tile_edge(g);
-#ifndef DASH_NO_HALF_SPLIT
-    // A 256 tile fills a CU, so a launch runs in rounds of 256 workgroups.  A launch of a split mode (several K
-    // segments per product: long enough to pay for a second launch) whose last round would be at most half full
-    // (the symmetric residual on 32 blocks: 320 workgroups) computes the blocks of the whole rounds with 256 tiles
-    // and the remaining blocks with 128 tiles in a second launch.
-    if (edge == 256 && g.prob[0].A2 DASH_HALF_SPLIT_COND) {
-        const int64_t t = g.B / 256, per_block = g.nprob * (g.sym ? t * (t + 1) / 2 : t * t), W = g.nblocks * per_block;
-        const int64_t rem = W % 256;
-        const int64_t n_main = (W - rem) / per_block;
-        if (W > 256 && rem > 0 && rem <= 128 && n_main >= 1 && n_main < g.nblocks) {
-            GemmLaunch a = g, b = g;
-            a.nblocks = n_main;
-            b.blk0 = g.blk0 + n_main;
-            b.nblocks = g.nblocks - n_main;
-            hipError_t e = launch_half_edge(a, 256, stream);
-            if (e != hipSuccess) return e;
-            return launch_half_edge(b, 128, stream);
-        }
+    const int64_t n_main = gemm_half_split_blocks(g);
+    if (n_main < g.nblocks) {
+        GemmLaunch a = g, b = g;
+        a.nblocks = n_main;
+        b.blk0 = g.blk0 + n_main;
+        b.nblocks = g.nblocks - n_main;
+        hipError_t e = launch_half_edge(a, 256, stream);
+        if (e != hipSuccess) return e;
+        return launch_half_edge(b, 128, stream);
     }
-#endif
     return launch_half_edge(g, edge, stream);
 }
 

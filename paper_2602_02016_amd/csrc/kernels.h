@@ -66,6 +66,7 @@ int gemm_tile_edge(const GemmLaunch& g);          // tile edge launch_gemm picks
 int gemm_half_tile_edge(const GemmLaunch& g);     // tile edge of a 16-bit launch (64, 128 or 256)
 double gemm_tile_fraction(const GemmLaunch& g);   // share of output tiles actually computed
 int64_t gemm_split_blocks(const GemmLaunch& g);   // fp32: blocks a launch computes with 128 tiles; the rest (if any) with 64
+int64_t gemm_half_split_blocks(const GemmLaunch& g);   // 16-bit: blocks computed with 256 tiles when a launch is split; the rest with 128
 hipError_t launch_gemm_half(const GemmLaunch& g, hipStream_t stream);   // gemm_half.hip
 
 // partial[b*P + q] = sum over the q-th row slab of block b of (A + eps I)^2 (mode 0)

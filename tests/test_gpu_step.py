@@ -131,6 +131,31 @@ def test_graft_update_alone(dash):
     assert np.allclose(s_out.cpu().numpy(), s_ref, rtol=1e-5)
 
 
+def test_graft_block_without_gradient_stays_finite(dash):
+    """A gradient block that is all zero (rows of an embedding that saw no token) has U = 0 and P = 0: the grafting
+    scale is taken as 0 there (Section 2.3 is silent), theta of that block does not move and nothing turns NaN."""
+    import torch
+    N, B = 3, 128
+    G = workloads.gradient_stack(N, B, 3550)
+    Uh = workloads.gradient_stack(N, B, 3551, std=1.0)
+    G[1] = 0.0
+    Uh[1] = 0.0
+    theta0 = workloads.gradient_stack(N, B, 3552, std=1.0)
+    acc0 = np.zeros((N, B, B), dtype=np.float32)
+    acc, theta = _to_gpu(acc0), _to_gpu(theta0)
+    s_out = torch.full((N,), -1.0, device="cuda")
+    beta_g, eps_g, lr = float(np.float32(0.999)), float(np.float32(1e-8)), 1e-2
+    dash.graft_update(_to_gpu(G), _to_gpu(Uh), acc, theta=theta, beta_g=beta_g, eps_g=eps_g, lr=lr, s_out=s_out)
+    Acc_ref, s_ref = oshampoo.adam_graft(G, Uh, acc0, beta_g, eps_g)
+    assert s_ref[1] == 0.0 and float(s_out[1]) == 0.0
+    assert np.allclose(s_out.cpu().numpy(), s_ref, rtol=1e-5)
+    th = theta.cpu().numpy()
+    assert np.isfinite(th).all() and np.array_equal(th[1], theta0[1])
+    assert not np.array_equal(th[0], theta0[0])
+    scaled = dash.graft_scale(_to_gpu(G), _to_gpu(Uh), _to_gpu(acc0), beta_g=beta_g, eps_g=eps_g)
+    assert bool(torch.isfinite(scaled).all()) and float(scaled[1].abs().max()) == 0.0
+
+
 def test_step_chebyshev(dash):
     """The step with the Chebyshev root: compared with the oracle step that uses the float64
     Clenshaw evaluation of the same coefficients."""

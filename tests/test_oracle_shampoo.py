@@ -127,3 +127,16 @@ def test_blocking_example_shapes():
     # S_full = L_full + R_full + R_rest blocks
     assert 2 * n_m * n_n + n_n == int(vals["S_full"].split(",")[0])
     assert workloads.cfg2_num_blocks() == 16 and workloads.cfg3_num_gradient_blocks() == 1536
+
+
+def test_adam_graft_zero_block_has_zero_scale():
+    """Reading of Section 2.3 for a block whose update is all zero: s = 0 (not 0/0); other blocks unchanged."""
+    rng = np.random.default_rng(5)
+    G = rng.standard_normal((3, 8, 8))
+    U = rng.standard_normal((3, 8, 8))
+    G[1] = 0.0
+    U[1] = 0.0
+    Acc, s = shampoo.adam_graft(G, U, np.zeros((3, 8, 8)), 0.999, 1e-8)
+    assert s[1] == 0.0 and np.all(np.isfinite(s)) and s[0] > 0 and s[2] > 0
+    P0 = G[0] / (1e-8 + np.sqrt(Acc[0]))
+    assert s[0] == pytest.approx(np.linalg.norm(P0) / np.linalg.norm(U[0]), rel=1e-12)

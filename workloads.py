@@ -87,7 +87,8 @@ def gradient_stack(N: int, B: int, seed: int, std: float = 1e-2) -> np.ndarray:
 def blocks_of_layer(m: int, n: int, B: int) -> int:
     """Number of full B x B gradient blocks of an (m, n) layer (m, n divisible by B)."""
     if m % B or n % B:
-        raise ValueError("layer dims must be multiples of B (ragged blocks are not built)")
+        raise ValueError("this helper counts the full B x B blocks of a layer whose dims are multiples of B; "
+                         "ragged layers go through the library's block() (dash_block_layer)")
     return (m // B) * (n // B)
 
 
