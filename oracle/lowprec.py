@@ -167,6 +167,38 @@ def inverse_root_cn_lowprec(A, p: int, iters: int, eps: float = 0.0, scaling: st
     return X[0] if single else X
 
 
+def inverse_root_cn_lowprec_as_printed(A, p: int, iters: int, eps: float = 0.0, scaling: str = "frobenius",
+                                       fmt: str = "fp16") -> np.ndarray:
+    """Coupled-Newton exactly in the order Section 3.2 prints it, every product through matmul_lowprec:
+    X_0 = I/c, M_0 = A_s/c^p; for k = 0 .. iters-1: C_k = (1+1/p) I - M_k/p, X_{k+1} = X_k C_k,
+    M_{k+1} = C_k^p M_k -- including the product X_0 C_0 with the rounded scalar matrix I/c and the last M that
+    nobody reads.  inverse_root_cn_lowprec carries 1/c to the end instead (a reading that saves two products and
+    one rounding); this function is what pins that reading: the two must agree to the precision of the operand
+    format (tests/test_oracle_lowprec.py)."""
+    A = np.asarray(A, dtype=np.float32)
+    single = A.ndim == 2
+    if single:
+        A = A[None]
+    X = np.empty(A.shape, dtype=np.float32)
+    n = A.shape[1]
+    I = np.eye(n, dtype=np.float32)
+    c = (1.0 + p) ** (-1.0 / p)
+    for i in range(A.shape[0]):
+        Ad = _f32(A[i] + np.float32(eps) * I)
+        s = np.float32(block_scale(Ad.astype(np.float64), scaling))
+        Xk = _f32(I * np.float32(1.0 / c))
+        M = _f32((Ad * (np.float32(1.0) / s)) * np.float32(c ** -p))
+        for _ in range(iters):
+            C = _f32(np.float32(1.0 + 1.0 / p) * I - np.float32(1.0 / p) * M)
+            Xk = matmul_lowprec(Xk, C, fmt)
+            P = matmul_lowprec(C, C, fmt)
+            if p == 4:
+                P = matmul_lowprec(P, P, fmt)
+            M = matmul_lowprec(P, M, fmt)
+        X[i] = _f32(Xk * np.float32(float(s) ** (-1.0 / p)))
+    return X[0] if single else X
+
+
 def inverse_root_ndb_lowprec(A, p: int, iters: int, eps: float = 0.0, scaling: str = "frobenius",
                              rounding=True) -> np.ndarray:
     """(A + eps I)^(-1/p) by Newton-DB with half-rounded matmul operands (bf16 when rounding is

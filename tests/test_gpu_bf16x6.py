@@ -114,6 +114,9 @@ def test_coupled_newton_few_iterations_match_emulation(dash, p, k):
     e = rel_frobenius_error(X, X_emu).max()
     print(f"cn bf16x6 p={p} k={k}: vs emulation {e:.2e}", flush=True)
     assert e < 5e-6
+    # and against Coupled-Newton in the printed order of Section 3.2 (no product or rounding saved)
+    X_print = lowprec.inverse_root_cn_lowprec_as_printed(A32, p, k, eps=1e-6, fmt="bf16x6")
+    assert rel_frobenius_error(X, X_print).max() < 1e-5
 
 
 @pytest.mark.parametrize("p", [2, 4])

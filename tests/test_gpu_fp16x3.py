@@ -68,6 +68,9 @@ def test_few_iterations_match_emulation(dash, method, p, k):
     e = rel_frobenius_error(X, X_emu).max()
     print(f"fp16x3 {method} p={p} k={k}: vs emulation {e:.2e}", flush=True)
     assert e < 5e-6
+    if method != "newton_db":      # and against Coupled-Newton in the printed order of Section 3.2
+        X_print = lowprec.inverse_root_cn_lowprec_as_printed(A32, p, k, eps=1e-6, fmt="fp16x3")
+        assert rel_frobenius_error(X, X_print).max() < 1e-5
 
 
 @pytest.mark.parametrize("method,k", [("newton_db", 16), ("coupled_newton", 25)])

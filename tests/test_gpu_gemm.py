@@ -162,3 +162,36 @@ def test_gemm_large_block_edges_sampled(dash, N, B):
     Ab = At[0].bfloat16().float().cpu().numpy().astype(np.float64)
     Bb = Bt[0].bfloat16().float().cpu().numpy().astype(np.float64)
     check(C[0].cpu().numpy().astype(np.float64), Ab, Bb, 2e-5)
+
+
+@pytest.mark.parametrize("N,B", [(2048, 256), (130, 1024)])
+def test_long_launches_match_short_ones_bit_for_bit(dash, N, B):
+    """Launches of many rounds of workgroups (2048 blocks of 256, 130 of 1024): whatever tile edge and launch split the
+    library picks for a launch size, every output element is accumulated over k in the same order, so a block must come
+    out bit for bit as when it is computed alone; sampled blocks are also checked against the float64 product, and the
+    mirrored accumulation for exact symmetry."""
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(N + B)
+    A = torch.randn(N, B, B, device="cuda", generator=gen)
+    Bm = torch.randn(N, B, B, device="cuda", generator=gen)
+    D = torch.randn(N, B, B, device="cuda", generator=gen)
+    C = torch.empty_like(A)
+    dash.gemm_batched(A, Bm, C, D=D, alpha=0.5, beta=-0.25, gamma=1.5)
+    sample = [0, 1, N // 2, N - 1]
+    for i in sample:
+        Ci = torch.empty(1, B, B, device="cuda")
+        dash.gemm_batched(A[i:i + 1].contiguous(), Bm[i:i + 1].contiguous(), Ci, D=D[i:i + 1].contiguous(), alpha=0.5, beta=-0.25,
+                          gamma=1.5)
+        torch.cuda.synchronize()
+        assert torch.equal(Ci[0], C[i])
+        ref = 0.5 * (A[i].double() @ Bm[i].double()) - 0.25 * D[i].double() + 1.5 * torch.eye(B, device="cuda", dtype=torch.float64)
+        assert float((C[i].double() - ref).norm() / ref.norm()) < TOL_MM
+    # the factor accumulation's products in a long symmetric launch: G G^T through the transposed instance
+    L = torch.zeros(N, B, B, device="cuda")
+    R = torch.zeros(N, B, B, device="cuda")
+    dash.accumulate_factors(A, L, R, 0.0, alpha=1.0)
+    for i in sample:
+        ref = A[i].double() @ A[i].double().T
+        assert float((L[i].double() - ref).norm() / ref.norm()) < TOL_MM
+        assert torch.equal(L[i], L[i].T)

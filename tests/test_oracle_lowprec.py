@@ -93,6 +93,25 @@ def test_cn_emulation_without_rounding_is_the_paper_iteration(p):
         assert rel_frobenius_error(X, X64).max() < 2e-6
 
 
+@pytest.mark.parametrize("p", [2, 4])
+@pytest.mark.parametrize("fmt,unit", [("fp16", 2.0 ** -11), ("bf16", 2.0 ** -8), ("bf16x3", 2.0 ** -16),
+                                      ("fp16x3", 2.0 ** -22), ("bf16x6", 2.0 ** -24)])
+def test_cn_emulation_agrees_with_the_printed_order(p, fmt, unit):
+    """The emulation the GPU path is compared with carries 1/c to the end (no product for X_1, no last M); the
+    iteration in the order Section 3.2 prints it, with the same operand rounding, must give the same root up to a
+    few units of the operand format -- so the reading changes rounding, not the method.  Without rounding both are
+    the float64 iteration of the oracle."""
+    from oracle import coupled_newton as ocn
+    A32, _, _ = workloads.spd_stack(2, 48, -1.0, 0.0, seed=21)
+    for k in (1, 2, 4, 8):
+        X_read = lowprec.inverse_root_cn_lowprec(A32, p, k, eps=1e-6, fmt=fmt)
+        X_print = lowprec.inverse_root_cn_lowprec_as_printed(A32, p, k, eps=1e-6, fmt=fmt)
+        e = rel_frobenius_error(X_read, X_print).max()
+        assert e < 6 * k * unit + 4e-7, (fmt, p, k, e)
+    X_print = lowprec.inverse_root_cn_lowprec_as_printed(A32, p, 6, eps=1e-6, fmt="none")
+    assert rel_frobenius_error(X_print, ocn.inverse_root_cn(A32.astype(np.float64), p, 6, eps=1e-6)).max() < 2e-6
+
+
 def test_fp16_beats_bf16_on_a_well_conditioned_block():
     # Sections 2.3 / 5: Coupled-Newton works in fp16 and diverges or degrades in bf16; Newton-DB
     # plateaus higher with bf16's 8 significand bits than with fp16's 11
