@@ -14,7 +14,10 @@
  *     work it enqueued has run.  "host" pointers are ordinary host memory.
  *   - B must be a positive multiple of 64; N >= 0 (N == 0 is a no-op returning DASH_OK).
  *   - Work is enqueued on the context's HIP stream and is asynchronous with respect to
- *     the host; the caller synchronises the stream before reading results.
+ *     the host; the caller synchronises the stream before reading results.  (dash_inverse_root
+ *     may run half of a stack of small blocks on a second stream of its own, forked from and
+ *     joined back into the context's stream inside the call: see dash_set_lanes.  Stream order
+ *     as the caller sees it does not change.)
  *   - Inputs declared const are never written.  Outputs must not overlap inputs unless
  *     a call says so.
  *   - Errors in arguments or launches are reported through the return code (and the
@@ -129,6 +132,19 @@ dash_status dash_get_stats(dash_ctx* ctx, dash_stats* out /* host */);
  * product is computed in full.  The preconditioned update and dash_gemm_batched always
  * compute full products. */
 dash_status dash_set_symmetric(dash_ctx* ctx, int on);
+
+/* Lanes (default on).  Blocks are independent through the whole path (Section 4.1).  On stacks of small blocks
+ * (B <= 512, and a chunk of at least 1024 output tiles of 128 x 128 per product in fp32, 256 with 16-bit operands)
+ * the launches of the iterative methods are so short that the fixed costs of a round of workgroups weigh a tenth
+ * and more; dash_inverse_root then sends the two halves of a chunk through the
+ * same launch sequence on two streams -- the context's and one the library creates in dash_create (default priority)
+ * -- so that the two overlap.  The second stream waits for an event recorded on the context's stream when the
+ * iterative part begins, and the context's stream waits for the second one when it ends: to the caller everything
+ * still happens in the order of the context's stream, also under stream capture (the second stream joins the capture
+ * and leaves it inside the call).  With every product computed in full the results are bit for bit the same with
+ * lanes on and off; in symmetric mode the tile edge, which follows the launch size, decides which entries of a
+ * mirrored product are computed and which are copies, so the two agree to rounding.  Off: one stream only. */
+dash_status dash_set_lanes(dash_ctx* ctx, int on);
 
 /* Multi-Power-Iteration scaling (Sections 3.4, 3.5).  For every block, with A_d = A + eps I:
  *   V_0 = start vectors, columns scaled to unit length; for t = 1..sweeps: W = A_d V_{t-1},

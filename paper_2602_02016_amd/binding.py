@@ -105,6 +105,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_reset_stats.argtypes = [vp]
     lib.dash_set_timing.argtypes = [vp, i32]
     lib.dash_set_symmetric.argtypes = [vp, i32]
+    lib.dash_set_lanes.argtypes = [vp, i32]
     lib.dash_set_power_iteration.argtypes = [vp, i32, i32, vp, i32]
     lib.dash_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     lib.dash_gemm_batched.argtypes = [vp, i32, i32, vp, vp, vp, vp, i64, i32, f32, f32, f32, i32]
@@ -140,7 +141,7 @@ def load_library(path: str = LIB_PATH):
     lib.dash_graft_scale.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, vp, vp]
     lib.dash_apply_update.argtypes = [vp, vp, vp, i64, f32]
     for name in ("dash_create", "dash_destroy", "dash_set_stream", "dash_set_workspace", "dash_reset_stats", "dash_set_timing",
-                 "dash_set_symmetric", "dash_set_power_iteration", "dash_accumulate_factors_rect",
+                 "dash_set_symmetric", "dash_set_lanes", "dash_set_power_iteration", "dash_accumulate_factors_rect",
                  "dash_block_layer", "dash_unblock_layer", "dash_block_layer_padded", "dash_unblock_layer_padded", "dash_graft_scale", "dash_apply_update", "dash_model_create", "dash_model_destroy",
                  "dash_model_get_info", "dash_model_get_bucket", "dash_model_get_stack", "dash_model_set_arena",
                  "dash_model_step",
@@ -287,6 +288,10 @@ class Dash:
             raise DashError(ERR_INVALID_ARG, "start_vectors: need a contiguous float32 device tensor [rows, pool]")
         self._pi_v0 = v
         self._check(self.lib.dash_set_power_iteration(self.h, v.shape[1], sweeps, C.c_void_p(v.data_ptr()), v.shape[0]))
+
+    def set_lanes(self, on: bool):
+        """Two-stream lanes for stacks of small blocks (see dash_set_lanes in dash.h); default on."""
+        self._check(self.lib.dash_set_lanes(self.h, 1 if on else 0))
 
     def set_symmetric(self, on: bool):
         """Symmetric mode of the library (see dash_set_symmetric in dash.h); default on."""

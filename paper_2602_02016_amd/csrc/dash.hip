@@ -43,6 +43,16 @@ struct dash_ctx {
     const float* pi_v0 = nullptr;
     // this device's copy of the file-scope scratch array (its device address, resolved in dash_create)
     float* static_scratch = nullptr;
+    // Lanes.  Launches on stacks of small blocks (B <= 512) are short -- one round of workgroups or less -- so
+    // the fixed costs of a round (first operand loads, epilogue, ramp-up and tail) are a tenth and more of their
+    // time.  Blocks are independent, so the iterative part of dash_inverse_root cuts such a chunk into two halves
+    // ("lanes") that go through the same launch sequence on two streams: the context's and `aux`, a stream the
+    // library owns (default priority), forked from and joined back into the context's stream with events, so
+    // that one half's fixed costs fall into the other half's matrix-core time.  Results do not change by a bit.
+    hipStream_t aux = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int lanes = 1;                  // lanes of the chunk in progress (1: everything on the context's stream)
+    bool use_lanes = true;          // dash_set_lanes
 };
 
 // Scratch of dash_block_norms_static: the slab partial sums of up to DASH_STATIC_MAX_BLOCKS blocks (32 per
@@ -126,37 +136,75 @@ size_t per_block_bytes(int B, dash_method m, dash_precision prec) {
 }
 
 // ---- matmul launch with statistics / optional event timing ------------------------------
+// blocks [off, off + cnt) of an n-block chunk that lane `lane` of `lanes` handles, and the stream it runs on
+inline void lane_range(int64_t n, int lane, int lanes, int64_t* off, int64_t* cnt) {
+    *off = n * lane / lanes;
+    *cnt = n * (lane + 1) / lanes - *off;
+}
+inline hipStream_t lane_stream(const dash_ctx* c, int lane) { return lane == 0 ? c->stream : c->aux; }
+
 dash_status run_gemm(dash_ctx* c, const GemmLaunch& g) {
     if (g.nblocks <= 0) return DASH_OK;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
     const int variant = 2 * (g.prob[0].transA ? 1 : 0) + (g.prob[0].transB ? 1 : 0);
-    if (c->timing) {
-        if (c->ev_used + 2 > c->ev_pool.size()) {
-            for (int i = 0; i < 2; ++i) {
-                hipEvent_t e;
-                HIP_TRY(c, hipEventCreate(&e));
-                c->ev_pool.push_back(e);
+    const int lanes = g.nblocks >= 2 ? c->lanes : 1;
+    double fl = 0.0;
+    for (int lane = 0; lane < lanes; ++lane) {
+        GemmLaunch gl = g;
+        int64_t off, cnt;
+        lane_range(g.nblocks, lane, lanes, &off, &cnt);
+        gl.blk0 = g.blk0 + off;
+        gl.nblocks = cnt;
+        hipStream_t st = lane_stream(c, lane);
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (c->timing) {
+            if (c->ev_used + 2 > c->ev_pool.size()) {
+                for (int i = 0; i < 2; ++i) {
+                    hipEvent_t e;
+                    HIP_TRY(c, hipEventCreate(&e));
+                    c->ev_pool.push_back(e);
+                }
             }
+            e0 = c->ev_pool[c->ev_used];
+            e1 = c->ev_pool[c->ev_used + 1];
+            if (c->ev_variant.size() < c->ev_pool.size() / 2) c->ev_variant.resize(c->ev_pool.size() / 2);
+            c->ev_variant[c->ev_used / 2] = variant;
+            c->ev_used += 2;
+            HIP_TRY(c, hipEventRecord(e0, st));
         }
-        e0 = c->ev_pool[c->ev_used];
-        e1 = c->ev_pool[c->ev_used + 1];
-        if (c->ev_variant.size() < c->ev_pool.size() / 2) c->ev_variant.resize(c->ev_pool.size() / 2);
-        c->ev_variant[c->ev_used / 2] = variant;
-        c->ev_used += 2;
-        HIP_TRY(c, hipEventRecord(e0, c->stream));
+        HIP_TRY(c, launch_gemm(gl, st));
+        if (c->timing) HIP_TRY(c, hipEventRecord(e1, st));
+        fl += (double)gl.nprob * (double)gl.nblocks * 2.0 * (gl.M ? gl.M : gl.B) * (double)(gl.N ? gl.N : gl.B) *
+              (gl.K ? gl.K : gl.B) * gemm_tile_fraction(gl);
     }
-    HIP_TRY(c, launch_gemm(g, c->stream));
-    if (c->timing) HIP_TRY(c, hipEventRecord(e1, c->stream));
+    // statistics count the launch once, whatever the number of lanes it was cut into
     c->mm_products += g.nprob;
     c->mm_launches += 1;
     c->mm_block_products += (double)g.nprob * (double)g.nblocks;
     c->var_launches[variant] += 1;
     c->var_block_products[variant] += (double)g.nprob * (double)g.nblocks;
-    const double fl = (double)g.nprob * (double)g.nblocks * 2.0 * (g.M ? g.M : g.B) * (double)(g.N ? g.N : g.B) *
-                      (g.K ? g.K : g.B) * gemm_tile_fraction(g);
     c->mm_flops += fl;
     c->var_flops[variant] += fl;
     return DASH_OK;
+}
+
+// launch_scale_shift on every lane of the chunk (same arguments; `stream` is replaced by the lane's)
+hipError_t lane_scale_shift(dash_ctx* c, const float* in, int64_t n, int B, float eps, const float* mult, float a1, float g1,
+                            float* out1, float a2, float g2, float* out2, void* h1, void* h2, int32_t* nonfinite,
+                            hipStream_t /*stream*/, int half = HALF_BF16, void* l1 = nullptr, void* l2 = nullptr,
+                            void* ll1 = nullptr, void* ll2 = nullptr) {
+    const int lanes = n >= 2 ? c->lanes : 1;
+    for (int lane = 0; lane < lanes; ++lane) {
+        int64_t off, cnt;
+        lane_range(n, lane, lanes, &off, &cnt);
+        const size_t o = (size_t)off * B * B;
+        auto f = [&](float* q) { return q ? q + o : nullptr; };
+        auto h = [&](void* q) -> void* { return q ? static_cast<unsigned short*>(q) + o : nullptr; };
+        hipError_t e = launch_scale_shift(in + o, cnt, B, eps, mult ? mult + off : nullptr, a1, g1, f(out1), a2, g2, f(out2),
+                                          h(h1), h(h2), nonfinite ? nonfinite + off : nullptr, lane_stream(c, lane), half,
+                                          h(l1), h(l2), h(ll1), h(ll2));
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 dash_status collect_events(dash_ctx* c) {
@@ -278,11 +326,11 @@ dash_status ndb_call(dash_ctx* c, float* buf[5], int mi, int64_t n, int B, int i
     if (m_needs_init) {
         // first call: M = (A + eps I)/s -> buf[y]; E_1 = 1.5 I - 0.5 M -> buf[z]
         y = grab(); z = grab();
-        HIP_TRY(c, launch_scale_shift(A_in, n, B, eps, inv_s, 1.f, 0.f, buf[y], -0.5f, 1.5f, buf[z], nullptr, nullptr, nullptr, st));
+        HIP_TRY(c, lane_scale_shift(c, A_in, n, B, eps, inv_s, 1.f, 0.f, buf[y], -0.5f, 1.5f, buf[z], nullptr, nullptr, nullptr, st));
     } else {
         // chained call: M is buf[mi] as it stands; E_1 = 1.5 I - 0.5 M
         used[mi] = true; y = mi; z = grab();
-        HIP_TRY(c, launch_scale_shift(buf[y], n, B, 0.f, nullptr, -0.5f, 1.5f, buf[z], 0.f, 0.f, nullptr, nullptr, nullptr, nullptr, st));
+        HIP_TRY(c, lane_scale_shift(c, buf[y], n, B, 0.f, nullptr, -0.5f, 1.5f, buf[z], 0.f, 0.f, nullptr, nullptr, nullptr, nullptr, st));
     }
     if (iters == 1) {
         if (keepY) {
@@ -291,7 +339,7 @@ dash_status ndb_call(dash_ctx* c, float* buf[5], int mi, int64_t n, int B, int i
             *out_idx = y1;
         } else if (final_out) {
             // X = unscale * Z_1: no product at all
-            HIP_TRY(c, launch_scale_shift(buf[z], n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nullptr, nullptr, nonfinite, st));
+            HIP_TRY(c, lane_scale_shift(c, buf[z], n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nullptr, nullptr, nonfinite, st));
         } else {
             *out_idx = z;
         }
@@ -359,20 +407,20 @@ dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], bf16_t** lb, bf16_t** lb2,
         y = grab(); z = grab();
         // M = (A + eps I)/s -> planes of y; E_1 = 1.5 I - 0.5 M (fp32) -> planes of z; when E_1 itself is
         // the result (iters == 1, p == 2) its fp32 value goes to fy
-        HIP_TRY(c, launch_scale_shift(A_in, n, B, eps, inv_s, 1.f, 0.f, nullptr, -0.5f, 1.5f,
+        HIP_TRY(c, lane_scale_shift(c, A_in, n, B, eps, inv_s, 1.f, 0.f, nullptr, -0.5f, 1.5f,
                                       (iters == 1 && !keepY) ? fy : nullptr, hb[y], hb[z], nullptr, st, c->half_kind,
                                       lo(y), lo(z), lo2(y), lo2(z)));
     } else {
         used[mi] = true; y = mi; z = grab();
         if (iters == 1 && !keepY && final_out) {
             // X = unscale * (1.5 I - 0.5 Y): two elementwise passes, no product
-            HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, nullptr, -0.5f, 1.5f, final_out, 0.f, 0.f, nullptr, nullptr,
+            HIP_TRY(c, lane_scale_shift(c, fy, n, B, 0.f, nullptr, -0.5f, 1.5f, final_out, 0.f, 0.f, nullptr, nullptr,
                                           nullptr, nullptr, st, c->half_kind));
-            HIP_TRY(c, launch_scale_shift(final_out, n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr,
+            HIP_TRY(c, lane_scale_shift(c, final_out, n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr,
                                           nullptr, nullptr, nonfinite, st, c->half_kind));
             return DASH_OK;
         }
-        HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, nullptr, -0.5f, 1.5f, nullptr, 0.f, 0.f, nullptr, hb[z], nullptr,
+        HIP_TRY(c, lane_scale_shift(c, fy, n, B, 0.f, nullptr, -0.5f, 1.5f, nullptr, 0.f, 0.f, nullptr, hb[z], nullptr,
                                       nullptr, st, c->half_kind, lo(z), nullptr, lo2(z), nullptr));
     }
     if (iters == 1) {
@@ -381,7 +429,7 @@ dash_status ndb_call_bf16(dash_ctx* c, bf16_t* hb[5], bf16_t** lb, bf16_t** lb2,
             DASH_TRY(gemm1(c, prod(y, z, fy, y1, nullptr, 1.f, 0.f), n, B, nullptr, 1));
             *out_idx = y1;
         } else if (final_out) {
-            HIP_TRY(c, launch_scale_shift(fy, n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nullptr,
+            HIP_TRY(c, lane_scale_shift(c, fy, n, B, 0.f, unscale, 1.f, 0.f, final_out, 0.f, 0.f, nullptr, nullptr,
                                           nullptr, nonfinite, st, c->half_kind));
         } else {
             *out_idx = z;
@@ -438,7 +486,7 @@ dash_status clenshaw_chunk_bf16(dash_ctx* c, float* fb[2], bf16_t* hb[3], const 
         return p;
     };
     const float m1 = (float)(2.0 / (cb - ca)), m0 = (float)(-(ca + cb) / (cb - ca));
-    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, m1, m0, nullptr, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
+    HIP_TRY(c, lane_scale_shift(c, A, n, B, eps, inv_s, m1, m0, nullptr, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
                                   hb[0], hb[i1], nullptr, st, c->half_kind, mid(0), mid(i1), low(0), low(i1)));
     if (d == 2)
         return gemm1(c, prod(nullptr, X, -1, unscale, 1.f, 0.f, (float)(cf[0] - cf[2])), n, B, nonfinite, 1, true);
@@ -472,10 +520,10 @@ dash_status cn_chunk(dash_ctx* c, float* buf[9], const float* A, float* X, int64
     float* Cb[3] = {buf[4], buf[5], buf[6]};
     float *P2 = buf[7], *P4 = buf[8];
     // M_0 = (p+1) (A + eps I)/s ; C_0 = a I - M_0/p
-    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, Mb[0], -ip, a, Cb[0], nullptr, nullptr,
+    HIP_TRY(c, lane_scale_shift(c, A, n, B, eps, inv_s, (float)(p + 1), 0.f, Mb[0], -ip, a, Cb[0], nullptr, nullptr,
                                   nullptr, st));
     if (iters == 1) {   // X = s^(-1/p) (1/c) C_0, no product
-        HIP_TRY(c, launch_scale_shift(Cb[0], n, B, 0.f, unscale, inv_c, 0.f, X, 0.f, 0.f, nullptr, nullptr, nullptr,
+        HIP_TRY(c, lane_scale_shift(c, Cb[0], n, B, 0.f, unscale, inv_c, 0.f, X, 0.f, 0.f, nullptr, nullptr, nullptr,
                                       nonfinite, st));
         return DASH_OK;
     }
@@ -527,14 +575,14 @@ dash_status cn_chunk_half(dash_ctx* c, bf16_t* hb[9], const float* A, float* X, 
         return q;
     };
     if (iters == 1) {   // X = s^(-1/p) (1/c) C_0 in fp32, no product: C_0 via the fp32 temporary X itself
-        HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, X, nullptr, nullptr,
+        HIP_TRY(c, lane_scale_shift(c, A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, X, nullptr, nullptr,
                                       nullptr, st, c->half_kind));
-        HIP_TRY(c, launch_scale_shift(X, n, B, 0.f, unscale, inv_c, 0.f, X, 0.f, 0.f, nullptr, nullptr, nullptr,
+        HIP_TRY(c, lane_scale_shift(c, X, n, B, 0.f, unscale, inv_c, 0.f, X, 0.f, 0.f, nullptr, nullptr, nullptr,
                                       nonfinite, st, c->half_kind));
         (void)tmp_f32;
         return DASH_OK;
     }
-    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, nullptr, hb[2], hb[4],
+    HIP_TRY(c, lane_scale_shift(c, A, n, B, eps, inv_s, (float)(p + 1), 0.f, nullptr, -ip, a, nullptr, hb[2], hb[4],
                                   nullptr, st, c->half_kind, mid(2), mid(4), low(2), low(4)));
     int xcur = 4;                                   // X_1 = (1/c) C_0: the first update needs no product
     for (int k = 0; k + 1 < iters; ++k) {
@@ -570,7 +618,7 @@ dash_status clenshaw_chunk(dash_ctx* c, float* buf[3], const float* A, float* X,
     const float m1 = (float)(2.0 / (cb - ca)), m0 = (float)(-(ca + cb) / (cb - ca));
     // S = (2 A_s - (a+b) I)/(b-a);  B_{d-1} = 2 c_d S + c_{d-1} I.  B_d = c_d I is never stored:
     // it only enters B_{d-2} through "- B_d + c_{d-2} I" = (c_{d-2} - c_d) I.
-    HIP_TRY(c, launch_scale_shift(A, n, B, eps, inv_s, m1, m0, S, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
+    HIP_TRY(c, lane_scale_shift(c, A, n, B, eps, inv_s, m1, m0, S, (float)(2.0 * cf[d]), (float)cf[d - 1], b1,
                                   nullptr, nullptr, nullptr, st));
     if (d == 2) {
         // result = S B_1 - B_2 + c_0 I with B_2 = c_2 I
@@ -587,6 +635,46 @@ dash_status clenshaw_chunk(dash_ctx* c, float* buf[3], const float* A, float* X,
     // result = S B_1 - B_2 + c_0 I, un-scaled
     return gemm1(c, problem(S, b1, b2, X, unscale, 1.f, -1.f, (float)cf[0]), n, B, nonfinite, 0, true);
 }
+
+// Two lanes for blocks of at most LANE_MAX_B when a single-product launch over the whole chunk would have at least
+// LANE_MIN_TILES_* output tiles of 128 x 128 (fp32: one full round of resident workgroups; 16-bit launches are shorter
+// and gain from a quarter of that).  Measured, lanes on against off: 256 blocks of 256 Newton-DB 3.70 -> 3.62 ms,
+// Clenshaw 1.03 -> 0.89, two fp16 planes on 64 blocks of 256 0.93 -> 0.73; below the thresholds they lose (64 blocks of
+// 128: 0.31 -> 0.36 ms), above B = 512 nothing is left to gain.
+constexpr int LANE_MAX_B = 512;
+constexpr int64_t LANE_MIN_TILES_FP32 = 1024, LANE_MIN_TILES_16BIT = 256;
+inline bool chunk_takes_lanes(const dash_ctx* c, int64_t nb, int B, dash_precision precision) {
+    if (!c->use_lanes || B > LANE_MAX_B || nb < 2) return false;
+    const int64_t tiles = nb * B * B / (128 * 128);
+    return tiles >= (precision == DASH_FP32 ? LANE_MIN_TILES_FP32 : LANE_MIN_TILES_16BIT);
+}
+
+// fork: the second lane's stream waits for everything enqueued so far on the context's stream; join: the context's
+// stream waits for the second lane.  Both are event record / wait pairs (legal under stream capture: the second
+// stream joins the capture at the fork and leaves it at the join).
+struct LaneScope {
+    dash_ctx* c;
+    int lanes;
+    bool forked = false;
+    LaneScope(dash_ctx* ctx, int n) : c(ctx), lanes(n) {}
+    dash_status fork() {
+        if (lanes < 2) return DASH_OK;
+        HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));
+        HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_fork, 0));
+        forked = true;
+        c->lanes = lanes;
+        return DASH_OK;
+    }
+    dash_status join() {
+        c->lanes = 1;
+        if (!forked) return DASH_OK;
+        forked = false;
+        HIP_TRY(c, hipEventRecord(c->ev_join, c->aux));
+        HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
+        return DASH_OK;
+    }
+    ~LaneScope() { if (forked) (void)join(); }
+};
 
 }  // namespace
 
@@ -624,6 +712,13 @@ dash_status dash_create(dash_ctx** out, int device, void* hip_stream) {
         return DASH_ERR_HIP;
     }
     c->static_scratch = static_cast<float*>(sp);
+    // the second lane's stream (default priority) and the events that fork it from and join it into the context's stream
+    if (hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+        dash_destroy(c);
+        return DASH_ERR_HIP;
+    }
     *out = c;
     return DASH_OK;
 }
@@ -637,6 +732,9 @@ dash_status dash_set_stream(dash_ctx* c, void* hip_stream) {
 dash_status dash_destroy(dash_ctx* c) {
     if (!c) return DASH_ERR_INVALID_ARG;
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->aux) (void)hipStreamDestroy(c->aux);
     delete c;
     return DASH_OK;
 }
@@ -678,6 +776,12 @@ dash_status dash_set_timing(dash_ctx* c, int on) {
 dash_status dash_set_symmetric(dash_ctx* c, int on) {
     if (!c) return DASH_ERR_INVALID_ARG;
     c->symmetric = on != 0;
+    return DASH_OK;
+}
+
+dash_status dash_set_lanes(dash_ctx* c, int on) {
+    if (!c) return DASH_ERR_INVALID_ARG;
+    c->use_lanes = on != 0;
     return DASH_OK;
 }
 
@@ -1035,6 +1139,11 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         // Sections 3.4, 3.5: s = ||A + eps I||_F, trace, or 2 lambda_PI, kept with 1/s and s^(-1/p)
         DASH_TRY(compute_scales(c, Ac, nb, B, eps, scaling, p, sc, scale_out ? scale_out + b0 : sc.s));
 
+        // small blocks: the iterative part of the chunk runs as two lanes on two streams (see dash_ctx::lanes)
+        LaneScope lanes_of_chunk(c, chunk_takes_lanes(c, nb, B, precision) ? 2 : 1);
+        DASH_TRY(lanes_of_chunk.fork());
+        const dash_status chunk_status = [&]() -> dash_status {
+
         if (method == DASH_COUPLED_NEWTON && lowp) {
             DASH_TRY(cn_chunk_half(c, hbuf, Ac, Xc, nb, B, p, iters, eps, inv_s, unscale, nf, nullptr,
                                    planes >= 2 ? hbuf + 9 : nullptr, planes == 3 ? hbuf + 18 : nullptr));
@@ -1066,6 +1175,11 @@ dash_status dash_inverse_root(dash_ctx* c, const float* A, float* X, int64_t N, 
         } else {
             DASH_TRY(clenshaw_chunk(c, buf, Ac, Xc, nb, B, iters, cheb_coeffs, cheb_a, cheb_b, eps, inv_s, unscale, nf));
         }
+        return DASH_OK;
+        }();
+        const dash_status join_status = lanes_of_chunk.join();       // joined also when a launch of the chunk failed
+        if (chunk_status != DASH_OK) return chunk_status;
+        DASH_TRY(join_status);
     }
     return DASH_OK;
 }
