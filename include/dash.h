@@ -80,8 +80,10 @@ typedef enum { DASH_FP32 = 0, DASH_BF16_ACC32 = 1, DASH_FP16_ACC32 = 2, DASH_BF1
 dash_status dash_create(dash_ctx** out, int device, void* hip_stream);
 dash_status dash_destroy(dash_ctx* ctx);
 /* Later calls enqueue on hip_stream (e.g. a stream under hipStreamBeginCapture: every entry point only
- * launches kernels on the context's stream -- no allocation, no memset or copy nodes, no synchronisation
- * unless dash_set_timing is on -- so a call sequence can be captured into a HIP graph and replayed). */
+ * launches kernels -- no allocation, no memset or copy nodes, no synchronisation unless dash_set_timing is
+ * on; the one thing besides kernels is the event pair with which dash_inverse_root forks and joins its
+ * second stream on stacks of small blocks, see dash_set_lanes -- so a call sequence can be captured into a
+ * HIP graph and replayed). */
 dash_status dash_set_stream(dash_ctx* ctx, void* hip_stream);
 
 /* Device scratch the iterative calls need.  dash_workspace_bytes(n, ...) is the size
