@@ -344,6 +344,59 @@ def other_configs(dash, cpu: bool):
     return out
 
 
+def design_choices(dash):
+    """Before/after rows of the design choices that can be switched from outside (all through the C ABI): symmetric
+    mode, lanes, chunk size.  Wall time per inverse-root call on resident stacks, each pair measured back to back on
+    the same box.  Returns a list of records (and prints a table on stderr)."""
+    import torch
+    from paper_2602_02016_amd import chebyshev_fit
+    coef = chebyshev_fit(4, 16, 0.05, 1.0)
+    cheb = dict(method="chebyshev", p=4, iters=16, eps=1e-6, cheb_coeffs=coef, cheb_a=0.05, cheb_b=1.0)
+    ndb = dict(method="newton_db", p=4, iters=10, eps=1e-6)
+    cn = dict(method="coupled_newton", p=4, iters=10, eps=1e-6)
+    rows = []
+
+    def pair(choice, what, setter, A, X, reps, kw, cap_off=None, cap_on=None):
+        res = {}
+        for state in ("off", "on", "off", "on"):             # two alternating repetitions: the mean of each
+            setter(state == "on")
+            cap = cap_on if state == "on" else cap_off
+            call = lambda: dash.inverse_root(A, X, **kw)
+            call()                                            # (sizes the binding's workspace tensor for the whole stack)
+            if cap is not None:                               # hand the library only `cap` bytes of it: it walks the stack in chunks
+                import ctypes
+                dash._check(dash.lib.dash_set_workspace(dash.h, ctypes.c_void_p(dash._ws.data_ptr()), int(cap)))
+                call()
+            res.setdefault(state, []).append(_timed(call, reps))
+        setter(True)
+        if cap_on is not None:
+            dash.set_workspace_bytes(0)                       # the whole tensor again
+        off, on = sum(res["off"]) / 2, sum(res["on"]) / 2
+        rows.append(dict(choice=choice, workload=what, off_ms=off, on_ms=on, gain=off / on - 1.0))
+        log(f"{choice:34s} {what:58s} off {off:9.3f} ms   on {on:9.3f} ms   {100 * (off / on - 1):+6.1f} %")
+
+    for N, B, reps in ((32, 1024, 5), (256, 1024, 3), (256, 256, 10)):
+        A = _spd_stack_on_device(N, B, 90 + B)
+        X = torch.empty_like(A)
+        for name, kw in (("Newton-DB p=4 k=10", ndb), ("Chebyshev d=16", cheb)):
+            pair("symmetric mode (mirrored products)", f"{N} x {B}, {name}, fp32", dash.set_symmetric, A, X, reps, kw)
+        del A, X
+    for N, B in ((256, 256), (1024, 256), (64, 512), (128, 384)):
+        A = _spd_stack_on_device(N, B, 91 + B)
+        X = torch.empty_like(A)
+        for name, kw in (("Newton-DB p=4 k=10", ndb), ("Chebyshev d=16", cheb), ("Coupled-Newton p=4 k=10", cn),
+                         ("Newton-DB, two fp16 planes", dict(ndb, precision="fp16x3")), ("Newton-DB, bf16 operands", dict(ndb, precision="bf16"))):
+            pair("lanes (two streams, B <= 512)", f"{N} x {B}, {name}", dash.set_lanes, A, X, 10, kw)
+        del A, X
+    A = _spd_stack_on_device(1024, 1024, 92)
+    X = torch.empty_like(A)
+    for chunk in (32, 128, 256):
+        pair(f"chunks of 1024 (off) vs {chunk} blocks (on)", "1024 x 1024, Newton-DB p=4 k=10, fp32", lambda on: None, A, X, 2, ndb,
+             cap_off=dash.workspace_bytes(1024, 1024), cap_on=dash.workspace_bytes(chunk, 1024))
+    del A, X
+    return rows
+
+
 def headline(dash, args, symmetric: bool, grads, S, X, U, nf, c):
     """W untimed warm-up steps, then exactly K timed steps of the cfg2 workload with the library's event timing OFF
     (nothing but the step's own launches inside the timed region); after that a second, instrumented pass of a few
@@ -436,6 +489,9 @@ def main():
                          "configurations, all methods and precisions (table on stderr, one JSON line)")
     ap.add_argument("--sweep-16bit", action="store_true",
                     help="as --sweep, but only the 16-bit cases on 1024 blocks of 1024 (bf16, fp16, split bf16)")
+    ap.add_argument("--design-choices", action="store_true",
+                    help="instead of the headline step: before/after rows of the switchable design choices (symmetric "
+                         "mode, lanes, chunk size) on resident stacks (table on stderr, one JSON line)")
     ap.add_argument("--hbm-kernels", action="store_true",
                     help="instead of the headline step: achieved bandwidth of the memory-bound kernels on a "
                          "1 GiB stack (table on stderr, one JSON line)")
@@ -455,6 +511,10 @@ def main():
     dev = torch.device("cuda", 0)
     dash = Dash(0)
     dash.set_symmetric(not args.full_products)
+
+    if args.design_choices:
+        print(json.dumps({"design_choices": design_choices(dash), "unit": "ms per inverse-root call", "n_gpus": 1, "data": "synthetic"}))
+        return
 
     if args.hbm_kernels:
         print(json.dumps({"hbm_kernels": hbm_kernels(dash), "peak_tb_per_s": 8.0, "n_gpus": 1, "data": "synthetic"}))
