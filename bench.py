@@ -344,6 +344,65 @@ def other_configs(dash, cpu: bool):
     return out
 
 
+def vendor_context(dash):
+    """Context only: the vendor's batched matmul (torch.bmm, i.e. the library the paper's own implementation calls) on
+    the same shapes as the library's plain product, and Newton-DB (Section 3.3, p=4, k=10) written with torch ops -- bmm
+    plus separate elementwise passes, every product in full, nothing skipped -- beside dash_inverse_root on the same
+    stack.  None of this is part of the product or of any reported roofline figure."""
+    import torch
+    torch.backends.cuda.matmul.allow_tf32 = False
+    rows = []
+    for N, B in ((32, 1024), (256, 1024), (256, 256), (64, 512)):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(N + B)
+        A = torch.randn(N, B, B, device="cuda", generator=gen) * 0.1
+        Bm = torch.randn(N, B, B, device="cuda", generator=gen) * 0.1
+        Cm = torch.empty_like(A)
+        fl = N * 2.0 * B ** 3
+        rec = {"N": N, "B": B}
+        for name, fn in (("vendor_fp32_tflops", lambda: torch.bmm(A, Bm, out=Cm)),
+                         ("dash_fp32_tflops", lambda: dash.gemm_batched(A, Bm, Cm))):
+            fn()
+            rec[name] = fl / (_timed(fn, 10) * 1e-3) / 1e12
+        Ah, Bh = A.bfloat16(), Bm.bfloat16()
+        Ch = torch.empty_like(Ah)
+        torch.bmm(Ah, Bh, out=Ch)
+        rec["vendor_bf16_in_bf16_out_tflops"] = fl / (_timed(lambda: torch.bmm(Ah, Bh, out=Ch), 10) * 1e-3) / 1e12
+        dash.gemm_batched(A, Bm, Cm, precision="bf16")
+        rec["dash_bf16_incl_operand_cast_fp32_out_tflops"] = fl / (_timed(lambda: dash.gemm_batched(A, Bm, Cm, precision="bf16"), 10) * 1e-3) / 1e12
+        rows.append(rec)
+        log("  ".join(f"{k}={v:.1f}" if isinstance(v, float) else f"{k}={v}" for k, v in rec.items()))
+        del A, Bm, Cm, Ah, Bh, Ch
+    N, B, k = 32, 1024, 10
+    A = _spd_stack_on_device(N, B, 5)
+    I = torch.eye(B, device="cuda")
+
+    def call(M):
+        E = 1.5 * I - 0.5 * M
+        Y, Z = torch.bmm(M, E), E
+        for _ in range(k - 1):
+            E = 1.5 * I - 0.5 * torch.bmm(Z, Y)
+            Y, Z = torch.bmm(Y, E), torch.bmm(E, Z)
+        return Y, Z
+
+    def root4():
+        s = torch.linalg.matrix_norm(A + 1e-6 * I).view(-1, 1, 1)
+        Y, _ = call((A + 1e-6 * I) / s)
+        _, Z = call(Y)
+        return Z * s ** -0.25
+
+    Xt = root4()
+    ms_t = _timed(root4, 5)
+    X = torch.empty_like(A)
+    dash.inverse_root(A, X, p=4, iters=k, eps=1e-6)
+    ms_d = _timed(lambda: dash.inverse_root(A, X, p=4, iters=k, eps=1e-6), 5)
+    diff = float(((Xt - X).flatten(1).norm(dim=1) / X.flatten(1).norm(dim=1)).max())
+    ndb = {"workload": "Newton-DB p=4 k=10 on 32 blocks of 1024, fp32", "torch_ops_ms": ms_t, "dash_inverse_root_ms": ms_d,
+           "max_rel_diff": diff}
+    log(f"Newton-DB p=4 k=10, 32 x 1024: torch ops {ms_t:.2f} ms, dash_inverse_root {ms_d:.2f} ms, results differ by {diff:.1e}")
+    return {"matmul": rows, "newton_db": ndb}
+
+
 def design_choices(dash):
     """Before/after rows of the design choices that can be switched from outside (all through the C ABI): symmetric
     mode, lanes, chunk size.  Wall time per inverse-root call on resident stacks, each pair measured back to back on
@@ -489,6 +548,9 @@ def main():
                          "configurations, all methods and precisions (table on stderr, one JSON line)")
     ap.add_argument("--sweep-16bit", action="store_true",
                     help="as --sweep, but only the 16-bit cases on 1024 blocks of 1024 (bf16, fp16, split bf16)")
+    ap.add_argument("--vendor-context", action="store_true",
+                    help="context only: the vendor's batched matmul (torch.bmm) and a torch-ops Newton-DB beside the library "
+                         "on the same shapes (table on stderr, one JSON line)")
     ap.add_argument("--design-choices", action="store_true",
                     help="instead of the headline step: before/after rows of the switchable design choices (symmetric "
                          "mode, lanes, chunk size) on resident stacks (table on stderr, one JSON line)")
@@ -511,6 +573,10 @@ def main():
     dev = torch.device("cuda", 0)
     dash = Dash(0)
     dash.set_symmetric(not args.full_products)
+
+    if args.vendor_context:
+        print(json.dumps({"vendor_context": vendor_context(dash), "n_gpus": 1, "data": "synthetic"}))
+        return
 
     if args.design_choices:
         print(json.dumps({"design_choices": design_choices(dash), "unit": "ms per inverse-root call", "n_gpus": 1, "data": "synthetic"}))
